@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged-attention hot path on one MI355X.
+
+One "step" is one pass of the whole path over one synthetic batch, with every input already
+resident in HBM: KV append of the step's new tokens, chunked prefill of the batch's prefill chunks
+and the decode step of its decode requests, all enqueued on one stream through the C ABI.
+
+Prints ONE JSON line.  `value` is the achieved HBM bandwidth of the decode step (algorithmic bytes
+of the batch / average duration of the decode call measured with HIP events on the launch stream);
+the prefill rate, the per-part times and the oracle timed on the host cores are in the same line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {2,3,4,5}]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=0, help="workload 2..5 (default: the largest supported)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def decode_bytes(w):
+    sh = w.shape
+    L = w.decode_lens.astype(np.int64)
+    kv = int(L.sum()) * 2 * sh.Hkv * sh.d * sh.elt
+    qo = w.S * sh.Hq * sh.d * sh.elt * 2
+    tab = 4 * int(((L + sh.B - 1) // sh.B).sum())
+    return kv + qo + tab
+
+
+def prefill_flops(w):
+    sh = w.shape
+    return 4 * sh.d * sh.Hq * w.prefill_pairs
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2412_18169_amd import kun, synth
+    from paper_2412_18169_amd.runner import DeviceWorkload
+
+    kun.lib()   # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    cfg = args.config or DEFAULT_CONFIG
+    t_setup = time.time()
+    w = synth.config(cfg)
+    sh = w.shape
+    dw = DeviceWorkload(w, poison=(cfg != 5))
+    torch.cuda.synchronize()
+    t_setup = time.time() - t_setup
+
+    # the step's new tokens: the last token of every decode request and every token of every chunk
+    seqs, poss, ks, vs = [], [], [], []
+    for s in range(w.S):
+        L = int(w.decode_lens[s])
+        k, v = synth.kv_logical(w, s, L - 1, L, dw.dev)
+        ks.append(k); vs.append(v); seqs.append(s); poss.append(L - 1)
+    for i, (p, c) in enumerate(w.chunks):
+        k, v = synth.kv_logical(w, w.S + i, p, p + c, dw.dev)
+        ks.append(k); vs.append(v); seqs += [w.S + i] * c; poss += list(range(p, p + c))
+    k_new = torch.cat(ks).contiguous(); v_new = torch.cat(vs).contiguous()
+    seq_of = torch.tensor(seqs, dtype=torch.int32, device=dw.dev)
+    pos_of = torch.tensor(poss, dtype=torch.int32, device=dw.dev)
+    all_table = torch.from_numpy(w.table_array(range(len(w.seq_lens)))).to(dw.dev)
+    T_new = len(seqs)
+    has_prefill = w.n_chunks > 0 and PREFILL_SUPPORTED
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        kun.kun_kv_append(dw.pool, k_new, v_new, seq_of, pos_of, T_new, all_table, all_table.shape[1])
+        if ev: ev[1].record()
+        if has_prefill:
+            dw.prefill()
+        if ev: ev[2].record()
+        dw.decode()
+        if ev: ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    t_app = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    t_pre = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    t_dec = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+    t_dec_med = float(np.median([e[2].elapsed_time(e[3]) for e in evs]))
+
+    dbytes = decode_bytes(w)
+    gbps = dbytes / (t_dec * 1e-3) / 1e9
+    out = {
+        "metric": "paged_decode_hbm_bandwidth", "value": round(gbps, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"cfg{cfg}:{w.name}", "decode_requests": w.S, "prefill_chunks": w.n_chunks if has_prefill else 0,
+                   "Hq": sh.Hq, "Hkv": sh.Hkv, "head_dim": sh.d, "block_size": sh.B,
+                   "pool_ranges": len(w.range_blocks), "pool_GB": round(w.num_blocks * sh.block_bytes / 1e9, 2),
+                   "decode_kv_tokens": w.decode_kv_tokens, "seed": w.seed},
+        "decode": {"ms": round(t_dec, 4), "ms_median": round(t_dec_med, 4), "algorithmic_bytes": dbytes,
+                   "GB_per_s": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+                   "requests_per_s": round(w.S / (t_dec * 1e-3), 1),
+                   "kv_tokens_per_s": round(w.decode_kv_tokens / (t_dec * 1e-3), 1)},
+        "append": {"ms": round(t_app, 4), "tokens": T_new},
+        "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC_BYTES.get(cfg),
+                     "kernel": "decode_partial_mfma (timed with its plan and merge launches)"},
+        "setup_s": round(t_setup, 1),
+    }
+    if has_prefill:
+        fl = prefill_flops(w)
+        tf = fl / (t_pre * 1e-3) / 1e12
+        out["prefill"] = {"ms": round(t_pre, 4), "flops": fl, "TFLOP_per_s": round(tf, 1),
+                          "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                          "new_tokens_per_s": round(dw.total_new / (t_pre * 1e-3), 1)}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"], out["max_abs_err_vs_oracle"] = cpu_baseline(dw, args.cpu_seconds)
+    dw.close()
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(dw, target_s):
+    """Time the oracle (as it stands) on a bounded sample of the same batch's decode requests and
+    check the GPU output of those requests against it."""
+    import torch
+    from oracle import bridge, paged_attention as O
+    w, sh = dw.w, dw.w.shape
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    out_gpu = dw.decode().double().cpu().numpy()
+    torch.cuda.synchronize()
+    # sample: requests in batch order until about ORACLE_TOKENS_PER_S * target_s KV tokens
+    budget = int(ORACLE_TOKENS_PER_S * target_s)
+    rows, tot = [], 0
+    for s in range(w.S):
+        rows.append(s)
+        tot += int(w.decode_lens[s])
+        if tot >= budget:
+            break
+    lens = [int(w.decode_lens[s]) for s in rows]
+    pool, tab = bridge.compact_pool(dw.ranges, w.range_blocks, [w.block_tables[s] for s in rows], lens,
+                                    sh.Hkv, sh.d, sh.B, sh.dtype)
+    qb = bridge.host_bits(dw.q_dec[rows])
+    t0 = time.perf_counter()
+    ref = O.paged_decode(pool, qb, tab, lens, sh.Hq, sh.scale)
+    dt = time.perf_counter() - t0
+    err = float(np.abs(out_gpu[rows] - ref).max())
+    nbytes = tot * 2 * sh.Hkv * sh.d * sh.elt + len(rows) * sh.Hq * sh.d * sh.elt * 2
+    return ({"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+             "seconds": round(dt, 2),
+             "sample": f"decode of the first {len(rows)} of {w.S} requests ({tot} KV tokens) of the same batch, "
+                       f"fp64 numpy oracle"}, err)
+
+
+# Largest workload every part of which is implemented; chunked prefill joins when its kernel lands.
+DEFAULT_CONFIG = 3
+PREFILL_SUPPORTED = False
+ORACLE_TOKENS_PER_S = 80000.0      # rough speed of the numpy oracle, only used to size its sample
+TRAFFIC_BYTES = {}                 # per-launch HBM bytes from rocprofv3 --pmc runs (see profiles/)
+
+if __name__ == "__main__":
+    main()

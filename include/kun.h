@@ -1,0 +1,160 @@
+/*
+ * kun.h -- C ABI of the MI355X (gfx950) paged-attention library.
+ *
+ * The library implements the attention step of one transformer layer over a block-table KVCache
+ * whose block pool can grow at run time: batched decode and chunked prefill.  It is the kernel a
+ * serving instance runs after a parameter drop has handed freed parameter memory to the KVCache
+ * (KunServe, Section 3 and Section 4.1 "Local instance memory management"): requests, fixed-size
+ * KV blocks and per-request block tables, with the pool described as a list of byte ranges -- the
+ * first pool plus one range per extension -- instead of the single static
+ * [base, base + num_blocks * block_size] layout that Section 4.1 says existing kernels assume.
+ *
+ * Conventions for every call
+ *   - Return value: a kun_status (0 = KUN_OK, negative = error).  Argument errors are found on
+ *     the host before anything is launched; no call leaves a partial launch behind.
+ *   - "device" pointers are HIP device addresses; "host" pointers are ordinary process memory.
+ *   - The caller owns every buffer it passes (pool ranges, q, out, tables, workspace) and keeps
+ *     it alive until the work enqueued on `stream` has finished; the library owns only the small
+ *     host object behind kun_kv_pool.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  kun_kv_append,
+ *     kun_paged_decode and kun_paged_prefill_chunk only enqueue kernels: they do not synchronise,
+ *     allocate or free.
+ *   - Physical block ids are int32, cumulative over the ranges in the order the ranges were
+ *     added, and never renumbered.  Block-table entries at or beyond ceil(L / block_size) of a
+ *     request are ignored and may hold anything (e.g. -1).  Ids the kernels do read must be
+ *     valid: check tables with kun_validate_block_table when in doubt.
+ *
+ * Page layout (part of the ABI).  One block is num_kv_heads pages; page (block, kv head) is
+ *     K  [block_size tokens][head_dim]      then
+ *     V  [head_dim][block_size tokens]      (V is stored transposed inside a page)
+ *   so block_bytes = 2 * num_kv_heads * block_size * head_dim * sizeof(element); with 8 KV heads
+ *   of 128 dims in bf16 that is 4096 bytes per token per layer, the figure behind the 192 KB per
+ *   token of a 48-layer model quoted in Section 2.2.
+ *   Query heads h with the same h / (num_q_heads / num_kv_heads) share a KV head (GQA).
+ *
+ * Supported shapes: block_size 16; head_dim 64 or 128; num_q_heads / num_kv_heads in
+ *   {1, 2, 4, 8}; dtype f32 or bf16 (accumulation is always fp32).  Chunked prefill needs bf16
+ *   with head_dim 128.  Anything else is KUN_ERR_UNSUPPORTED.
+ */
+#ifndef KUN_H
+#define KUN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KUN_API __attribute__((visibility("default")))
+
+typedef struct kun_kv_pool kun_kv_pool; /* opaque host object */
+
+typedef enum { KUN_F32 = 0, KUN_BF16 = 1 } kun_dtype;
+
+typedef enum {
+    KUN_OK = 0,
+    KUN_ERR_INVALID_ARG = -1,     /* null pointer, non-positive size, heads not divisible, ...  */
+    KUN_ERR_MISALIGNED = -2,      /* a range base that is not 256-byte aligned                  */
+    KUN_ERR_TOO_SMALL = -3,       /* a range smaller than one block                             */
+    KUN_ERR_TOO_MANY_RANGES = -4, /* more than KUN_MAX_RANGES ranges                            */
+    KUN_ERR_BLOCK_OOB = -5,       /* a block id outside [0, num_blocks)                         */
+    KUN_ERR_WORKSPACE = -6,       /* workspace missing, misaligned or smaller than required     */
+    KUN_ERR_HIP = -7,             /* a HIP launch failed                                        */
+    KUN_ERR_UNSUPPORTED = -8,     /* shape or dtype outside the supported set                   */
+    KUN_ERR_OVERLAP = -9          /* a new range overlaps one already in the pool               */
+} kun_status;
+
+#define KUN_MAX_RANGES 16
+
+/* Human-readable name of a status code (static storage). */
+KUN_API const char* kun_status_string(int status);
+
+/* ---- pool growth (Section 4.1: the KVCache region is extended at its tail with the memory of
+ *      dropped parameters; Section 5.6: two consecutive drops enlarge it twice) ---------------- */
+
+/* Create a pool whose first range is the device byte range [base, base + bytes).
+ * Usable blocks = floor(bytes / block_bytes); the remainder is unused.  Host-only. */
+KUN_API int kun_kv_pool_create(kun_kv_pool** out, void* base, size_t bytes, int dtype, int num_kv_heads,
+                       int head_dim, int block_size);
+
+/* Append the device byte range [base, base + bytes) -- e.g. the buffer of a dropped parameter --
+ * as a new range.  Existing block ids, addresses and contents are untouched; the new blocks get
+ * ids first_new_block .. first_new_block + num_new_blocks - 1 (both optional outputs, host).
+ * Takes effect for calls issued after it returns; kernels already enqueued keep the table they
+ * were launched with.  Host-only, no device work. */
+KUN_API int kun_kv_pool_extend(kun_kv_pool* pool, void* base, size_t bytes, int64_t* first_new_block,
+                       int64_t* num_new_blocks);
+
+KUN_API int kun_kv_pool_num_blocks(const kun_kv_pool* pool, int64_t* n);
+KUN_API int kun_kv_pool_num_ranges(const kun_kv_pool* pool, int* n);
+KUN_API int kun_kv_pool_block_bytes(const kun_kv_pool* pool, size_t* bytes);
+
+/* Block id -> range index, byte offset inside that range, device address (outputs optional).
+ * This is the address arithmetic the kernels apply to every table entry. */
+KUN_API int kun_kv_pool_resolve(const kun_kv_pool* pool, int64_t block, int* range, size_t* byte_off,
+                        void** addr);
+
+/* Frees the host object only; never touches the ranges. */
+KUN_API int kun_kv_pool_destroy(kun_kv_pool* pool);
+
+/* Host-side check of a HOST copy of a block table [rows, max_blocks] against HOST context lengths
+ * [rows]: every entry below ceil(len / block_size) must be in [0, num_blocks) and len must fit
+ * max_blocks.  Returns KUN_ERR_BLOCK_OOB / KUN_ERR_INVALID_ARG on the first violation. */
+KUN_API int kun_validate_block_table(const kun_kv_pool* pool, const int32_t* host_table, int rows,
+                             int max_blocks, const int32_t* host_ctx_len);
+
+/* ---- KV append: write the K/V rows of new tokens into their slots -------------------------- */
+
+/* k_new, v_new: device [T, num_kv_heads, head_dim] in the pool's dtype.  Token i belongs to row
+ * seq_of_tok[i] of block_table (device int32 [rows, max_blocks]) at logical position
+ * pos_of_tok[i] (device int32 [T]); it lands in block block_table[seq][pos / block_size], slot
+ * pos % block_size.  T == 0 is a no-op. */
+KUN_API int kun_kv_append(kun_kv_pool* pool, const void* k_new, const void* v_new,
+                  const int32_t* seq_of_tok, const int32_t* pos_of_tok, int T,
+                  const int32_t* block_table, int max_blocks, void* stream);
+
+/* ---- batched decode ------------------------------------------------------------------------ */
+
+/* Bytes of device workspace kun_paged_decode needs for S requests whose context lengths sum to at
+ * most total_ctx_upper_bound tokens (pass 0 to assume a full pool).  0 on bad arguments. */
+KUN_API size_t kun_decode_workspace_bytes(const kun_kv_pool* pool, int S, int num_q_heads,
+                                  int64_t total_ctx_upper_bound);
+
+/* One decode step for S requests (Section 2.1: decode reads the whole KVCache of each request
+ * and is memory-bound).  q, out: device [S, num_q_heads, head_dim] in the pool's dtype; request s
+ * has ctx_len[s] tokens in its pages INCLUDING the token being decoded, whose query is row s of q;
+ * out[s] = softmax(scale * q K^T) V over those tokens.  ctx_len: device int32 [S]; a request with
+ * ctx_len 0 is skipped and its output row left untouched.  block_table: device int32
+ * [S, max_blocks].  total_ctx_upper_bound: host-known bound on sum(ctx_len) (0 = full pool); it
+ * sizes the launch and must be the value used for kun_decode_workspace_bytes or smaller.
+ * workspace: device, 256-byte aligned, holds the split-K partial results; contents are scratch. */
+KUN_API int kun_paged_decode(kun_kv_pool* pool, const void* q, void* out, const int32_t* block_table,
+                     int max_blocks, const int32_t* ctx_len, int S, int num_q_heads, float scale,
+                     int64_t total_ctx_upper_bound, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/* ---- chunked prefill ----------------------------------------------------------------------- */
+
+/* Bytes of device workspace kun_paged_prefill_chunk needs for n_chunks chunks holding
+ * total_new_tokens query rows in total. */
+KUN_API size_t kun_prefill_workspace_bytes(const kun_kv_pool* pool, int n_chunks, int num_q_heads,
+                                   int total_new_tokens);
+
+/* Attention for n_chunks prefill chunks (Section 4.3, Eq. 1: chunk j of a request has c new tokens
+ * after p prior tokens; it attends to the p prior tokens and causally to itself, diagonal
+ * included, p*c + (c*c + c)/2 pairs).  The K/V of the chunk's own tokens must already be in the
+ * pages (kun_kv_append).  q, out: device [total_new_tokens, num_q_heads, head_dim], chunks packed
+ * back to back; q_start: device int32 [n_chunks + 1], row offsets with q_start[n_chunks] ==
+ * total_new_tokens; prior_len: device int32 [n_chunks]; block_table: device int32
+ * [n_chunks, max_blocks], row i covering the p_i + c_i tokens of chunk i's request.  Row r of
+ * chunk i sees logical keys 0 .. p_i + r.  A chunk with c == 0 is skipped. */
+KUN_API int kun_paged_prefill_chunk(kun_kv_pool* pool, const void* q, void* out, const int32_t* q_start,
+                            const int32_t* prior_len, const int32_t* block_table, int max_blocks,
+                            int n_chunks, int num_q_heads, int total_new_tokens, float scale,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KUN_H */

@@ -1,0 +1,642 @@
+// Batched paged decode: split-K over the KV blocks of each request, then a merge of the partial
+// results.  Decode streams the whole KVCache of every request once and is memory-bound
+// (Section 2.1); after a parameter drop the batch and the pool are larger (Section 3), so this is
+// the kernel whose time grows with the pool.
+//
+// Launch sequence (one stream, no host synchronisation):
+//   1. plan     -- one workgroup turns ctx_len[] into a list of work items (request, partition)
+//                  of `part_tokens` tokens each and a per-request index of its first item.
+//   2. partial  -- one workgroup per (item, kv head): online softmax over the item's tokens for
+//                  the G query heads that share the kv head, K/V pages read exactly once.
+//                  Requests that fit one partition are normalised and written to `out` directly.
+//   3. merge    -- one workgroup per (request, kv head) with more than one partition:
+//                  o = sum_i acc_i e^(m_i - M) / sum_i l_i e^(m_i - M).
+//
+// Two partial kernels: a generic one on the vector ALUs (any supported dtype/shape; used for
+// fp32) and an MFMA one for bf16 with head_dim 128, where the G query rows are padded to a
+// 16-wide MFMA tile so that the inner products cost almost nothing next to the page loads.
+#include <math.h>
+#include <stdlib.h>
+
+#include "kun_internal.h"
+
+namespace {
+
+constexpr int kBlock = 16;           // tokens per KV block (the only supported block size)
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct DecodeArgs {
+    KunRanges rt;
+    const void* q;
+    void* out;
+    const int32_t* table;
+    const int32_t* ctx_len;
+    int32_t* n_items;        // workspace: number of work items (written by plan)
+    int32_t* seq_first;      // workspace: [S + 1] first item of each request
+    int2* items;             // workspace: (request, partition)
+    float* part_ml;          // workspace: [item, kvh, G, 2]  (m in log2 units, l)
+    float* part_acc;         // workspace: [item, kvh, G, d]
+    int max_blocks;
+    int S, Hkv, G;
+    int part_tokens;         // tokens per partition, multiple of 32
+    int max_items;
+    float scale_log2;        // softmax scale * log2(e)
+    unsigned block_bytes, page_bytes;
+};
+
+// ---------------------------------------------------------------------------------------------
+// 1. plan
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void decode_plan_kernel(const int32_t* __restrict__ ctx_len, int S,
+                                                         int part_tokens, int max_items,
+                                                         int32_t* __restrict__ n_items,
+                                                         int32_t* __restrict__ seq_first,
+                                                         int2* __restrict__ items) {
+    __shared__ int wave_tot[16];
+    __shared__ int carry_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    for (int s0 = 0; s0 < S; s0 += 1024) {
+        const int s = s0 + tid;
+        int np = 0;
+        if (s < S) {
+            int L = ctx_len[s];
+            np = L > 0 ? (L + part_tokens - 1) / part_tokens : 0;
+        }
+        int incl = np;                       // inclusive scan inside the wave
+        for (int o = 1; o < 64; o <<= 1) {
+            int y = __shfl_up(incl, o);
+            if (lane >= o) incl += y;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        int before = carry_s;
+        for (int w = 0; w < wave; ++w) before += wave_tot[w];
+        const int first = before + incl - np;
+        if (s < S) {
+            seq_first[s] = first;
+            for (int p = 0; p < np; ++p)
+                if (first + p < max_items) items[first + p] = make_int2(s, p);
+        }
+        __syncthreads();
+        if (tid == 1023) carry_s = first + np;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        int tot = carry_s;
+        seq_first[S] = tot;
+        *n_items = tot < max_items ? tot : max_items;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) {
+    return __uint_as_float((unsigned)b << 16);
+}
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
+    unsigned u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);  // NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int kPerLoad = 4;   // elements per 16-byte load
+    __device__ static float get(const uint4& v, int i) {
+        return __uint_as_float(i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w);
+    }
+    __device__ static void store(float* p, float x) { *p = x; }
+};
+struct bf16_t { unsigned short bits; };
+template <> struct Elem<bf16_t> {
+    static constexpr int kPerLoad = 8;
+    __device__ static float get(const uint4& v, int i) {
+        unsigned w = (i >> 1) == 0 ? v.x : (i >> 1) == 1 ? v.y : (i >> 1) == 2 ? v.z : v.w;
+        return (i & 1) ? __uint_as_float(w & 0xffff0000u) : __uint_as_float(w << 16);
+    }
+    __device__ static void store(bf16_t* p, float x) { p->bits = f32_to_bf16_rne(x); }
+};
+
+// Combine the per-wave partial results held in LDS and write either the final output row (request
+// with one partition) or the item's partial record.  sm_m/sm_l: [NW][G]; sm_acc: [NW][G][D].
+template <typename T, int D, int NW>
+__device__ __forceinline__ void finish_item(const DecodeArgs& a, int item, int kvh, int seq, int nparts,
+                                            int G, const float* sm_m, const float* sm_l,
+                                            const float* sm_acc) {
+    for (int idx = threadIdx.x; idx < G * D; idx += blockDim.x) {
+        const int g = idx / D, j = idx - g * D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) M = fmaxf(M, sm_m[w * G + g]);
+        float l = 0.f, acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float mw = sm_m[w * G + g];
+            const float f = (mw == -INFINITY) ? 0.f : exp2f(mw - M);
+            l += f * sm_l[w * G + g];
+            acc += f * sm_acc[(w * G + g) * D + j];
+        }
+        if (nparts == 1) {
+            T* o = (T*)a.out + ((size_t)seq * a.Hkv * G + (size_t)kvh * G + g) * D + j;
+            Elem<T>::store(o, acc / l);
+        } else {
+            const size_t rec = ((size_t)item * a.Hkv + kvh) * G + g;
+            a.part_acc[rec * D + j] = acc;
+            if (j == 0) {
+                a.part_ml[rec * 2 + 0] = M;
+                a.part_ml[rec * 2 + 1] = l;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// 2a. generic partial kernel (vector ALUs).  4 waves; each wave takes every 4th block.
+//     Lane layout for K: LPR = D / EPL lanes cover one token row with one 16-byte load each, so a
+//     load instruction covers TPL = 64 / LPR tokens.  For V^T ([D][16 tokens]) lane x owns dims
+//     x, x + 64, ... and reads the 16 tokens of each.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D, int G>
+__global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a) {
+    constexpr int NW = 4;
+    constexpr int EPL = Elem<T>::kPerLoad;
+    constexpr int LPR = D / EPL;
+    constexpr int TPL = 64 / LPR;
+    constexpr int NIT = kBlock / TPL;
+    constexpr int DPL = D / 64;                    // dims per lane in the PV phase
+    constexpr int VLD = kBlock / EPL;              // 16-byte loads per V^T row
+    __shared__ float sm_m[NW * G], sm_l[NW * G];
+    __shared__ float sm_acc[NW * G * D];
+
+    const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
+    if (item >= *a.n_items) return;
+    const int2 it2 = a.items[item];
+    const int seq = it2.x, part = it2.y;
+    const int L = a.ctx_len[seq];
+    const int nparts = (L + a.part_tokens - 1) / a.part_tokens;
+    const int t0 = part * a.part_tokens;
+    const int t1 = min(L, t0 + a.part_tokens);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane % LPR, grp = lane / LPR;
+
+    float qf[G][EPL];
+    {
+        const T* qrow = (const T*)a.q + ((size_t)seq * a.Hkv + kvh) * G * D;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            uint4 v = *(const uint4*)((const char*)(qrow + g * D) + col * 16);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) qf[g][e] = Elem<T>::get(v, e);
+        }
+    }
+    float m[G], l[G], acc[G][DPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        m[g] = -INFINITY; l[g] = 0.f;
+#pragma unroll
+        for (int i = 0; i < DPL; ++i) acc[g][i] = 0.f;
+    }
+
+    const int32_t* trow = a.table + (size_t)seq * a.max_blocks;
+    for (int b = t0 / kBlock + wave; b * kBlock < t1; b += NW) {
+        const int blk = __builtin_amdgcn_readfirstlane(trow[b]);
+        const char* page = kun_block_addr(a.rt, blk, a.block_bytes) + (size_t)kvh * a.page_bytes;
+        const int tb = b * kBlock;
+        // scores: s[g][it] for token tb + it * TPL + grp
+        float s[G][NIT];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int tok = it * TPL + grp;
+            uint4 kv = *(const uint4*)(page + ((size_t)tok * D + col * EPL) * sizeof(T));
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float d = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) d = fmaf(qf[g][e], Elem<T>::get(kv, e), d);
+#pragma unroll
+                for (int o = 1; o < LPR; o <<= 1) d += __shfl_xor(d, o);
+                s[g][it] = (tb + tok < t1) ? d * a.scale_log2 : -INFINITY;
+            }
+        }
+        // online softmax update
+        float p[G][NIT];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float mx = s[g][0];
+#pragma unroll
+            for (int it = 1; it < NIT; ++it) mx = fmaxf(mx, s[g][it]);
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+            const float mn = fmaxf(m[g], mx);          // finite: the block has a visible token
+            const float alpha = exp2f(m[g] - mn);      // exp2(-inf) = 0 on the first block
+            float ps = 0.f;
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                p[g][it] = exp2f(s[g][it] - mn);
+                ps += p[g][it];
+            }
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) ps += __shfl_xor(ps, o);
+            l[g] = l[g] * alpha + ps;
+            m[g] = mn;
+#pragma unroll
+            for (int i = 0; i < DPL; ++i) acc[g][i] *= alpha;
+        }
+        // acc[g][dim] += sum_t p[g][t] * V^T[dim][t]
+        const char* vpage = page + (size_t)kBlock * D * sizeof(T);
+#pragma unroll
+        for (int i = 0; i < DPL; ++i) {
+            const int dim = lane + 64 * i;
+            float vrow[kBlock];
+#pragma unroll
+            for (int c = 0; c < VLD; ++c) {
+                uint4 vv = *(const uint4*)(vpage + ((size_t)dim * kBlock + c * EPL) * sizeof(T));
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) {
+                    const int t = c * EPL + e;
+                    vrow[t] = (tb + t < t1) ? Elem<T>::get(vv, e) : 0.f;   // unused slots may hold NaN
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < kBlock; ++t) {
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    const float pt = __shfl(p[g][t / TPL], (t % TPL) * LPR);
+                    acc[g][i] = fmaf(pt, vrow[t], acc[g][i]);
+                }
+            }
+        }
+    }
+    // per-wave results to LDS
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        if (lane == 0) { sm_m[wave * G + g] = m[g]; sm_l[wave * G + g] = l[g]; }
+#pragma unroll
+        for (int i = 0; i < DPL; ++i) sm_acc[(wave * G + g) * D + lane + 64 * i] = acc[g][i];
+    }
+    __syncthreads();
+    finish_item<T, D, NW>(a, item, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
+}
+
+// ---------------------------------------------------------------------------------------------
+// 2b. MFMA partial kernel: bf16, head_dim 128, block 16, G <= 16.
+//
+// Each wave walks PAIRS of blocks (32 tokens).  With lane = 16 * j + n:
+//   QK^T  S^T[token][head] = K[token][:] . Q[head][:]   as 2 tiles x 4 MFMA 16x16x32
+//         A = K rows (lane n picks the tile row's token, j picks the 16-byte chunk 4*kk + j of
+//         the row), B = Q (lane n = head, same chunk).  Tile rows are mapped to tokens so that
+//         after both tiles lane (n, j) holds the scores of head n for the 8 consecutive
+//         pair-local tokens 8j .. 8j+7.
+//   PV    O^T[dim][head] += V^T[dim][token] P^T[token][head]   as 8 MFMA 16x16x32 (one per 16 dims)
+//         A = V^T rows straight from the page (lane n = dim inside the slice, j = the 8 tokens
+//         8j..8j+7: one 16-byte load, since V is stored [dim][token]), B = P in registers.
+// The softmax state (m, l) of head n lives in lane column n; rescaling O^T needs no shuffles.
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+union Frag {
+    uint4 u;
+    bf16x8 v;
+};
+
+struct PairLoads {
+    uint4 k[2][4];   // [tile][kk]
+    uint4 v[8];      // [dim slice]
+};
+
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void decode_partial_mfma(const DecodeArgs a) {
+    constexpr int D = 128;
+    constexpr int GMAX = 16;
+    __shared__ float sm_m[NW * GMAX], sm_l[NW * GMAX];
+    __shared__ float sm_acc[NW * 8 * D];      // G <= 8 heads kept (G <= 8 is enforced on the host)
+
+    const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
+    if (item >= *a.n_items) return;
+    const int2 it2 = a.items[item];
+    const int seq = it2.x, part = it2.y;
+    const int G = a.G;
+    const int L = a.ctx_len[seq];
+    const int nparts = (L + a.part_tokens - 1) / a.part_tokens;
+    const int t0 = part * a.part_tokens;
+    const int t1 = min(L, t0 + a.part_tokens);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, j = lane >> 4;
+
+    // B operand of QK^T: Q[head n][chunk 4*kk + j], zero rows for the padding heads
+    Frag qf[4];
+    {
+        const char* qrow = (const char*)a.q + (((size_t)seq * a.Hkv + kvh) * G + (n < G ? n : 0)) * D * 2;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            uint4 v = *(const uint4*)(qrow + (4 * kk + j) * 16);
+            if (n >= G) v = make_uint4(0, 0, 0, 0);
+            qf[kk].u = v;
+        }
+    }
+    // tile row n -> token: rows 4jj + r; block jj / 2, slot 8 * (jj % 2) + r (+4 for tile 1)
+    const int krow_blk = n >> 3;                       // which block of the pair (0/1)
+    const int krow_slot = ((n >> 2) & 1) * 8 + (n & 3);
+    const unsigned k_off = (unsigned)krow_slot * (D * 2) + j * 16;      // + kk * 64, + 4 rows for tile 1
+    const int v_blk = j >> 1;
+    const unsigned v_off = kBlock * D * 2 + (unsigned)n * (kBlock * 2) + (j & 1) * 16;  // + slice * 512
+
+    f32x4 o[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) o[s] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, l = 0.f;
+
+    const int32_t* trow = a.table + (size_t)seq * a.max_blocks;
+    const int nblk = (t1 + kBlock - 1) / kBlock;       // blocks of the request this item may touch
+    const int pair0 = t0 / 32 + wave;
+    const int pair_end = (t1 + 31) / 32;
+
+    auto issue = [&](int pr, PairLoads& ld) {
+        const int bA = 2 * pr, bB = (2 * pr + 1 < nblk) ? 2 * pr + 1 : 2 * pr;
+        const int idA = __builtin_amdgcn_readfirstlane(trow[bA]);
+        const int idB = __builtin_amdgcn_readfirstlane(trow[bB]);
+        const char* pA = kun_block_addr(a.rt, idA, a.block_bytes) + (size_t)kvh * a.page_bytes;
+        const char* pB = kun_block_addr(a.rt, idB, a.block_bytes) + (size_t)kvh * a.page_bytes;
+        const char* kp = (krow_blk ? pB : pA) + k_off;
+        const char* vp = (v_blk ? pB : pA) + v_off;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            ld.k[0][kk] = *(const uint4*)(kp + kk * 64);
+            ld.k[1][kk] = *(const uint4*)(kp + kk * 64 + 4 * D * 2);
+        }
+#pragma unroll
+        for (int s = 0; s < 8; ++s) ld.v[s] = *(const uint4*)(vp + s * 512);
+    };
+
+    auto compute = [&](int pr, PairLoads& ld) {
+        f32x4 s0 = (f32x4){0.f, 0.f, 0.f, 0.f}, s1 = s0;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            Frag k0, k1;
+            k0.u = ld.k[0][kk];
+            k1.u = ld.k[1][kk];
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0.v, qf[kk].v, s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1.v, qf[kk].v, s1, 0, 0, 0);
+        }
+        // lane (n, j): scores of head n for tokens tbase + e, e = 0..7
+        const int tbase = pr * 32 + 8 * j;
+        float sc[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { sc[e] = s0[e] * a.scale_log2; sc[4 + e] = s1[e] * a.scale_log2; }
+        const bool tail = (pr * 32 + 32 > t1);
+        if (tail) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (tbase + e >= t1) sc[e] = -INFINITY;
+        }
+        float mx = sc[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sc[e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float mn = fmaxf(m, mx);                 // finite: the pair has a visible token
+        const float alpha = __builtin_amdgcn_exp2f(m - mn);
+        float ps = 0.f;
+        Frag pf;
+        unsigned short pb[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float p = __builtin_amdgcn_exp2f(sc[e] - mn);
+            ps += p;
+            pb[e] = f32_to_bf16_rne(p);
+        }
+        pf.u = make_uint4(pb[0] | ((unsigned)pb[1] << 16), pb[2] | ((unsigned)pb[3] << 16),
+                          pb[4] | ((unsigned)pb[5] << 16), pb[6] | ((unsigned)pb[7] << 16));
+        l = l * alpha + ps;
+        m = mn;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) o[s] *= alpha;
+        }
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            Frag vf;
+            vf.u = ld.v[s];
+            if (tail) {   // slots past the context may hold anything: zero them (0 * NaN = NaN)
+                unsigned w[4] = {vf.u.x, vf.u.y, vf.u.z, vf.u.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (tbase + e >= t1) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                vf.u = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+            o[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf.v, o[s], 0, 0, 0);
+        }
+    };
+
+    PairLoads cur, nxt;
+    int pr = pair0;
+    if (pr < pair_end) issue(pr, cur);
+    while (pr < pair_end) {
+        const int prn = pr + NW;
+        if (prn < pair_end) issue(prn, nxt);
+        compute(pr, cur);
+        cur = nxt;
+        pr = prn;
+    }
+
+    // l: sum over the 4 token groups j of this head
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (n < G) {
+        if (j == 0) { sm_m[wave * G + n] = m; sm_l[wave * G + n] = l; }
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sm_acc[(wave * G + n) * D + s * 16 + 4 * j + i] = o[s][i];
+    }
+    __syncthreads();
+    finish_item<bf16_t, D, NW>(a, item, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
+}
+
+// ---------------------------------------------------------------------------------------------
+// 3. merge: one workgroup per (request, kv head); only requests with more than one partition
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a, int D) {
+    const int seq = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
+    const int L = a.ctx_len[seq];
+    const int nparts = (L + a.part_tokens - 1) / a.part_tokens;
+    if (nparts <= 1) return;
+    const int first = a.seq_first[seq];
+    if (first + nparts > a.max_items) return;   // the caller's bound on sum(ctx_len) was too small
+    const int G = a.G;
+    for (int idx = threadIdx.x; idx < G * D; idx += blockDim.x) {
+        const int g = idx / D, j = idx - g * D;
+        float M = -INFINITY;
+        for (int p = 0; p < nparts; ++p)
+            M = fmaxf(M, a.part_ml[((((size_t)first + p) * a.Hkv + kvh) * G + g) * 2]);
+        float l = 0.f, acc = 0.f;
+        for (int p = 0; p < nparts; ++p) {
+            const size_t rec = (((size_t)first + p) * a.Hkv + kvh) * G + g;
+            const float f = exp2f(a.part_ml[rec * 2] - M);
+            l += f * a.part_ml[rec * 2 + 1];
+            acc += f * a.part_acc[rec * D + j];
+        }
+        T* o = (T*)a.out + ((size_t)seq * a.Hkv * G + (size_t)kvh * G + g) * D + j;
+        Elem<T>::store(o, acc / l);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+constexpr int kPartChoices[] = {256, 512, 1024, 2048, 4096};
+constexpr int kNumPartChoices = 5;
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int64_t default_bound(const kun_kv_pool* p, int S, int64_t ub) {
+    const int64_t cap = (int64_t)p->ranges.first[p->ranges.n] * p->B;
+    if (ub <= 0 || ub > cap) ub = cap;
+    return ub;
+}
+
+// Partition size: aim at a few thousand workgroups (256 CUs, several workgroups each).
+int choose_part_tokens(const kun_kv_pool* p, int64_t ub) {
+    const char* e = getenv("KUN_DECODE_PART");
+    if (e) {
+        int v = atoi(e);
+        if (v >= 32 && v % 32 == 0) return v;
+    }
+    const int64_t per = ub * p->Hkv / 4096;
+    int P = kPartChoices[0];
+    for (int i = 0; i < kNumPartChoices; ++i)
+        if (per >= kPartChoices[i]) P = kPartChoices[i];
+    return P;
+}
+
+struct DecodeLayout {
+    size_t off_first, off_items, off_ml, off_acc, total;
+    int max_items;
+};
+
+DecodeLayout layout_for(const kun_kv_pool* p, int S, int Hq, int64_t ub, int P) {
+    DecodeLayout lay;
+    const int G = Hq / p->Hkv;
+    int64_t mi = ub / P + S;
+    lay.max_items = (int)(mi > INT32_MAX / 2 ? INT32_MAX / 2 : mi);
+    size_t o = 256;
+    lay.off_first = o; o += align256(sizeof(int32_t) * ((size_t)S + 1));
+    lay.off_items = o; o += align256(sizeof(int2) * (size_t)lay.max_items);
+    lay.off_ml = o;    o += align256(sizeof(float) * 2 * (size_t)lay.max_items * p->Hkv * G);
+    lay.off_acc = o;   o += align256(sizeof(float) * (size_t)lay.max_items * p->Hkv * G * p->d);
+    lay.total = o;
+    return lay;
+}
+
+bool decode_shape_ok(const kun_kv_pool* p, int S, int Hq) {
+    if (!p || S < 0 || Hq <= 0 || Hq % p->Hkv != 0) return false;
+    return true;
+}
+
+template <typename T, int D>
+int launch_generic(const DecodeArgs& a, dim3 grid, hipStream_t st) {
+    switch (a.G) {
+        case 1: hipLaunchKernelGGL((decode_partial_generic<T, D, 1>), grid, dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((decode_partial_generic<T, D, 2>), grid, dim3(256), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((decode_partial_generic<T, D, 4>), grid, dim3(256), 0, st, a); break;
+        case 8: hipLaunchKernelGGL((decode_partial_generic<T, D, 8>), grid, dim3(256), 0, st, a); break;
+        default: return KUN_ERR_UNSUPPORTED;
+    }
+    return KUN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t kun_decode_workspace_bytes(const kun_kv_pool* p, int S, int Hq, int64_t ub) {
+    if (!decode_shape_ok(p, S, Hq)) return 0;
+    ub = default_bound(p, S, ub);
+    // The partition size steps up with the bound; size for the worst case at or below `ub`.
+    size_t need = layout_for(p, S, Hq, ub, choose_part_tokens(p, ub)).total;
+    for (int i = 1; i < kNumPartChoices; ++i) {
+        const int64_t edge = ((int64_t)kPartChoices[i] * 4096 + p->Hkv - 1) / p->Hkv - 1;   // last bound using choice i-1
+        if (edge < ub && edge > 0) {
+            size_t n2 = layout_for(p, S, Hq, edge, choose_part_tokens(p, edge)).total;
+            if (n2 > need) need = n2;
+        }
+    }
+    return need;
+}
+
+int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* block_table,
+                     int max_blocks, const int32_t* ctx_len, int S, int Hq, float scale,
+                     int64_t ub, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!decode_shape_ok(p, S, Hq)) return KUN_ERR_INVALID_ARG;
+    if (S == 0) return KUN_OK;
+    if (!q || !out || !block_table || !ctx_len || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
+    const int G = Hq / p->Hkv;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return KUN_ERR_UNSUPPORTED;
+    ub = default_bound(p, S, ub);
+    const int P = choose_part_tokens(p, ub);
+    const DecodeLayout lay = layout_for(p, S, Hq, ub, P);
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < lay.total)
+        return KUN_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+
+    DecodeArgs a;
+    a.rt = p->ranges;
+    a.q = q;
+    a.out = out;
+    a.table = block_table;
+    a.ctx_len = ctx_len;
+    a.n_items = (int32_t*)ws;
+    a.seq_first = (int32_t*)(ws + lay.off_first);
+    a.items = (int2*)(ws + lay.off_items);
+    a.part_ml = (float*)(ws + lay.off_ml);
+    a.part_acc = (float*)(ws + lay.off_acc);
+    a.max_blocks = max_blocks;
+    a.S = S;
+    a.Hkv = p->Hkv;
+    a.G = G;
+    a.part_tokens = P;
+    a.max_items = lay.max_items;
+    a.scale_log2 = scale * kLog2e;
+    a.block_bytes = (unsigned)p->block_bytes;
+    a.page_bytes = (unsigned)p->page_bytes;
+
+    hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(1024), 0, st, ctx_len, S, P, lay.max_items,
+                       a.n_items, a.seq_first, a.items);
+    KUN_HIP_CHECK_LAUNCH();
+
+    const dim3 grid((unsigned)((size_t)lay.max_items * p->Hkv));
+    const char* force = getenv("KUN_DECODE_KERNEL");     // "generic" forces the vector-ALU kernel
+    const bool generic_only = force && force[0] == 'g';
+    int rc = KUN_OK;
+    if (p->dtype == KUN_BF16 && p->d == 128 && !generic_only) {
+        int nw = 4;
+        const char* e = getenv("KUN_DECODE_WAVES");
+        if (e) nw = atoi(e);
+        if (nw == 1) hipLaunchKernelGGL(decode_partial_mfma<1>, grid, dim3(64), 0, st, a);
+        else if (nw == 2) hipLaunchKernelGGL(decode_partial_mfma<2>, grid, dim3(128), 0, st, a);
+        else hipLaunchKernelGGL(decode_partial_mfma<4>, grid, dim3(256), 0, st, a);
+    } else if (p->dtype == KUN_BF16) {
+        rc = p->d == 128 ? launch_generic<bf16_t, 128>(a, grid, st) : launch_generic<bf16_t, 64>(a, grid, st);
+    } else {
+        rc = p->d == 128 ? launch_generic<float, 128>(a, grid, st) : launch_generic<float, 64>(a, grid, st);
+    }
+    if (rc != KUN_OK) return rc;
+    KUN_HIP_CHECK_LAUNCH();
+
+    const dim3 mgrid((unsigned)((size_t)S * p->Hkv));
+    if (p->dtype == KUN_BF16)
+        hipLaunchKernelGGL(decode_merge_kernel<bf16_t>, mgrid, dim3(256), 0, st, a, p->d);
+    else
+        hipLaunchKernelGGL(decode_merge_kernel<float>, mgrid, dim3(256), 0, st, a, p->d);
+    KUN_HIP_CHECK_LAUNCH();
+    return KUN_OK;
+}
+
+}  // extern "C"

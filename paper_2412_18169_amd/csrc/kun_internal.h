@@ -1,0 +1,39 @@
+// Internal definitions shared by the library's translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kun.h"
+
+// Range table handed to every kernel BY VALUE, so that a later kun_kv_pool_extend cannot disturb
+// a launch already enqueued.  first[r] is the id of the first block of range r;
+// first[n] = total number of blocks.  Unused entries hold INT32_MAX / nullptr.
+struct KunRanges {
+    int32_t n;
+    int32_t first[KUN_MAX_RANGES + 1];
+    char* base[KUN_MAX_RANGES];
+};
+
+struct kun_kv_pool {
+    KunRanges ranges;
+    size_t range_bytes[KUN_MAX_RANGES];
+    int dtype;        // kun_dtype
+    int Hkv, d, B;
+    size_t elt;       // bytes per element
+    size_t block_bytes;
+    size_t page_bytes;   // one (block, kv head): K then V^T
+};
+
+// Device address of block `blk` (wave-uniform callers get scalar code).
+__device__ __forceinline__ char* kun_block_addr(const KunRanges& rt, int blk, size_t block_bytes) {
+    int r = 0;
+    for (int i = 1; i < rt.n; ++i)
+        if (blk >= rt.first[i]) r = i;
+    return rt.base[r] + (size_t)(blk - rt.first[r]) * block_bytes;
+}
+
+#define KUN_HIP_CHECK_LAUNCH()                      \
+    do {                                            \
+        if (hipGetLastError() != hipSuccess) return KUN_ERR_HIP; \
+    } while (0)

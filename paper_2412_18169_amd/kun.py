@@ -1,0 +1,189 @@
+"""Thin ctypes binding of the C-ABI library declared in include/kun.h.
+
+Argument marshalling only: every function here has the name of the C entry point it forwards to,
+takes torch tensors (or raw integers) for the pointer arguments, and raises KunError on a
+non-zero status.  All computation happens in the HIP kernels of libkun.so.  There is no CPU
+fallback: if the library is missing or cannot be loaded, importing this module's functions fails
+with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkun.so")
+
+KUN_F32, KUN_BF16 = 0, 1
+KUN_MAX_RANGES = 16
+
+SYMBOLS = [
+    "kun_status_string", "kun_kv_pool_create", "kun_kv_pool_extend", "kun_kv_pool_num_blocks",
+    "kun_kv_pool_num_ranges", "kun_kv_pool_block_bytes", "kun_kv_pool_resolve",
+    "kun_kv_pool_destroy", "kun_validate_block_table", "kun_kv_append",
+    "kun_decode_workspace_bytes", "kun_paged_decode", "kun_prefill_workspace_bytes",
+    "kun_paged_prefill_chunk",
+]
+
+
+class KunError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libkun.so once.  Fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} not found: build it with `python -m paper_2412_18169_amd.build` "
+                          "(there is no fallback path)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, sz, i32, i64, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int64, ctypes.c_float
+    P = ctypes.POINTER
+    L.kun_status_string.restype = ctypes.c_char_p
+    L.kun_status_string.argtypes = [i32]
+    L.kun_kv_pool_create.argtypes = [P(vp), vp, sz, i32, i32, i32, i32]
+    L.kun_kv_pool_extend.argtypes = [vp, vp, sz, P(i64), P(i64)]
+    L.kun_kv_pool_num_blocks.argtypes = [vp, P(i64)]
+    L.kun_kv_pool_num_ranges.argtypes = [vp, P(i32)]
+    L.kun_kv_pool_block_bytes.argtypes = [vp, P(sz)]
+    L.kun_kv_pool_resolve.argtypes = [vp, i64, P(i32), P(sz), P(vp)]
+    L.kun_kv_pool_destroy.argtypes = [vp]
+    L.kun_validate_block_table.argtypes = [vp, vp, i32, i32, vp]
+    L.kun_kv_append.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, vp]
+    L.kun_decode_workspace_bytes.restype = sz
+    L.kun_decode_workspace_bytes.argtypes = [vp, i32, i32, i64]
+    L.kun_paged_decode.argtypes = [vp, vp, vp, vp, i32, vp, i32, i32, f32, i64, vp, sz, vp]
+    L.kun_prefill_workspace_bytes.restype = sz
+    L.kun_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    L.kun_paged_prefill_chunk.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]
+    for name in SYMBOLS:
+        if name not in ("kun_status_string", "kun_decode_workspace_bytes", "kun_prefill_workspace_bytes"):
+            getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().kun_status_string(int(status)).decode()
+
+
+def _check(st: int, where: str) -> None:
+    if st != 0:
+        raise KunError(st, where)
+
+
+def _ptr(x) -> Optional[int]:
+    """Device/host address of a tensor, or a raw integer address, or None."""
+    if x is None:
+        return None
+    if isinstance(x, torch.Tensor):
+        return x.data_ptr()
+    return int(x)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def kun_kv_pool_create(base, nbytes: int, dtype: int, num_kv_heads: int, head_dim: int,
+                       block_size: int) -> int:
+    """Returns the opaque pool handle (an integer address)."""
+    h = ctypes.c_void_p()
+    _check(lib().kun_kv_pool_create(ctypes.byref(h), _ptr(base), int(nbytes), dtype, num_kv_heads,
+                                    head_dim, block_size), "kun_kv_pool_create")
+    return h.value
+
+
+def kun_kv_pool_extend(pool: int, base, nbytes: int):
+    """Returns (first_new_block, num_new_blocks)."""
+    first, n = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().kun_kv_pool_extend(pool, _ptr(base), int(nbytes), ctypes.byref(first),
+                                    ctypes.byref(n)), "kun_kv_pool_extend")
+    return first.value, n.value
+
+
+def kun_kv_pool_num_blocks(pool: int) -> int:
+    n = ctypes.c_int64()
+    _check(lib().kun_kv_pool_num_blocks(pool, ctypes.byref(n)), "kun_kv_pool_num_blocks")
+    return n.value
+
+
+def kun_kv_pool_num_ranges(pool: int) -> int:
+    n = ctypes.c_int()
+    _check(lib().kun_kv_pool_num_ranges(pool, ctypes.byref(n)), "kun_kv_pool_num_ranges")
+    return n.value
+
+
+def kun_kv_pool_block_bytes(pool: int) -> int:
+    n = ctypes.c_size_t()
+    _check(lib().kun_kv_pool_block_bytes(pool, ctypes.byref(n)), "kun_kv_pool_block_bytes")
+    return n.value
+
+
+def kun_kv_pool_resolve(pool: int, block: int):
+    """Returns (range index, byte offset inside the range, device address)."""
+    r, off, addr = ctypes.c_int(), ctypes.c_size_t(), ctypes.c_void_p()
+    _check(lib().kun_kv_pool_resolve(pool, int(block), ctypes.byref(r), ctypes.byref(off),
+                                     ctypes.byref(addr)), "kun_kv_pool_resolve")
+    return r.value, off.value, addr.value
+
+
+def kun_kv_pool_destroy(pool: int) -> None:
+    _check(lib().kun_kv_pool_destroy(pool), "kun_kv_pool_destroy")
+
+
+def kun_validate_block_table(pool: int, host_table: torch.Tensor, host_ctx_len: torch.Tensor) -> None:
+    """host_table: CPU int32 [rows, max_blocks]; host_ctx_len: CPU int32 [rows]."""
+    assert host_table.device.type == "cpu" and host_table.dtype == torch.int32 and host_table.is_contiguous()
+    assert host_ctx_len.device.type == "cpu" and host_ctx_len.dtype == torch.int32
+    rows, mb = host_table.shape
+    _check(lib().kun_validate_block_table(pool, _ptr(host_table), rows, mb, _ptr(host_ctx_len)),
+           "kun_validate_block_table")
+
+
+def kun_kv_append(pool: int, k_new, v_new, seq_of_tok, pos_of_tok, T: int, block_table,
+                  max_blocks: int, stream=None) -> None:
+    _check(lib().kun_kv_append(pool, _ptr(k_new), _ptr(v_new), _ptr(seq_of_tok), _ptr(pos_of_tok),
+                               int(T), _ptr(block_table), int(max_blocks), _stream(stream)),
+           "kun_kv_append")
+
+
+def kun_decode_workspace_bytes(pool: int, S: int, num_q_heads: int, total_ctx_upper_bound: int = 0) -> int:
+    return lib().kun_decode_workspace_bytes(pool, int(S), int(num_q_heads), int(total_ctx_upper_bound))
+
+
+def kun_paged_decode(pool: int, q, out, block_table, max_blocks: int, ctx_len, S: int,
+                     num_q_heads: int, scale: float, total_ctx_upper_bound: int, workspace,
+                     workspace_bytes: int, stream=None) -> None:
+    _check(lib().kun_paged_decode(pool, _ptr(q), _ptr(out), _ptr(block_table), int(max_blocks),
+                                  _ptr(ctx_len), int(S), int(num_q_heads), float(scale),
+                                  int(total_ctx_upper_bound), _ptr(workspace), int(workspace_bytes),
+                                  _stream(stream)), "kun_paged_decode")
+
+
+def kun_prefill_workspace_bytes(pool: int, n_chunks: int, num_q_heads: int, total_new_tokens: int) -> int:
+    return lib().kun_prefill_workspace_bytes(pool, int(n_chunks), int(num_q_heads), int(total_new_tokens))
+
+
+def kun_paged_prefill_chunk(pool: int, q, out, q_start, prior_len, block_table, max_blocks: int,
+                            n_chunks: int, num_q_heads: int, total_new_tokens: int, scale: float,
+                            workspace, workspace_bytes: int, stream=None) -> None:
+    _check(lib().kun_paged_prefill_chunk(pool, _ptr(q), _ptr(out), _ptr(q_start), _ptr(prior_len),
+                                         _ptr(block_table), int(max_blocks), int(n_chunks),
+                                         int(num_q_heads), int(total_new_tokens), float(scale),
+                                         _ptr(workspace), int(workspace_bytes), _stream(stream)),
+           "kun_paged_prefill_chunk")

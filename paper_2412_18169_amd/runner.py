@@ -1,0 +1,95 @@
+"""Device-side plumbing that turns a synthetic Workload into library calls.
+
+Owns the torch buffers (pool ranges, tables, q, out, workspaces) and the pool handle; every
+attention step goes through the C-ABI binding in `kun`.  Used by the GPU tests, the smoke check
+and the benchmark.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import kun, synth
+
+
+class DeviceWorkload:
+    def __init__(self, w: synth.Workload, device="cuda:0", poison: bool = True,
+                 n_ranges_at_create: Optional[int] = None, fill: bool = True):
+        """Allocates one buffer per pool range, creates the pool on range 0 and extends it with the
+        others (all of them unless n_ranges_at_create limits it; call extend_next() later)."""
+        self.w = w
+        self.dev = torch.device(device)
+        sh = w.shape
+        self.ranges: List[torch.Tensor] = synth.alloc_ranges(w, self.dev, poison=poison)
+        dt = kun.KUN_F32 if sh.dtype == "f32" else kun.KUN_BF16
+        r0 = self.ranges[0]
+        self.pool = kun.kun_kv_pool_create(r0, r0.numel() * r0.element_size(), dt, sh.Hkv, sh.d, sh.B)
+        self.n_attached = 1
+        want = len(self.ranges) if n_ranges_at_create is None else n_ranges_at_create
+        while self.n_attached < want:
+            self.extend_next()
+        if fill:
+            synth.fill_pool(w, self.ranges)
+        # decode side
+        self.S = w.S
+        if self.S:
+            self.dec_table = torch.from_numpy(w.table_array(range(self.S))).to(self.dev)
+            self.dec_len = torch.from_numpy(w.decode_lens.astype(np.int32)).to(self.dev)
+            self.q_dec = synth.q_decode(w, self.dev)
+            self.out_dec = torch.zeros_like(self.q_dec)
+        # prefill side
+        self.n_chunks = w.n_chunks
+        if self.n_chunks:
+            rows = [w.S + i for i in range(self.n_chunks)]
+            self.pre_table = torch.from_numpy(w.table_array(rows)).to(self.dev)
+            cs = [c for _, c in w.chunks]
+            self.q_start_host = np.concatenate([[0], np.cumsum(cs)]).astype(np.int32)
+            self.q_start = torch.from_numpy(self.q_start_host).to(self.dev)
+            self.prior = torch.tensor([p for p, _ in w.chunks], dtype=torch.int32, device=self.dev)
+            self.q_pre = torch.cat([synth.q_chunk(w, i, self.dev) for i in range(self.n_chunks)])
+            self.out_pre = torch.zeros_like(self.q_pre)
+            self.total_new = int(self.q_start_host[-1])
+        self._ws_dec = None
+        self._ws_pre = None
+
+    # ---- pool growth -------------------------------------------------------------------------
+    def extend_next(self):
+        r = self.ranges[self.n_attached]
+        first, n = kun.kun_kv_pool_extend(self.pool, r, r.numel() * r.element_size())
+        self.n_attached += 1
+        return first, n
+
+    # ---- decode ------------------------------------------------------------------------------
+    def decode(self, seqs: Optional[Sequence[int]] = None, ctx_bound: Optional[int] = None,
+               stream=None) -> torch.Tensor:
+        """One decode step over all decode requests (or the first `seqs` ones given as a count)."""
+        sh = self.w.shape
+        S = self.S if seqs is None else int(seqs)
+        if ctx_bound is None:
+            ctx_bound = int(self.w.decode_lens[:S].astype(np.int64).sum())
+        need = kun.kun_decode_workspace_bytes(self.pool, S, sh.Hq, ctx_bound)
+        if self._ws_dec is None or self._ws_dec.numel() < need:
+            self._ws_dec = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        kun.kun_paged_decode(self.pool, self.q_dec, self.out_dec, self.dec_table,
+                             self.dec_table.shape[1], self.dec_len, S, sh.Hq, sh.scale, ctx_bound,
+                             self._ws_dec, self._ws_dec.numel(), stream)
+        return self.out_dec
+
+    # ---- prefill -----------------------------------------------------------------------------
+    def prefill(self, stream=None) -> torch.Tensor:
+        sh = self.w.shape
+        need = kun.kun_prefill_workspace_bytes(self.pool, self.n_chunks, sh.Hq, self.total_new)
+        if self._ws_pre is None or self._ws_pre.numel() < need:
+            self._ws_pre = torch.empty(max(need, 256), dtype=torch.uint8, device=self.dev)
+        kun.kun_paged_prefill_chunk(self.pool, self.q_pre, self.out_pre, self.q_start, self.prior,
+                                    self.pre_table, self.pre_table.shape[1], self.n_chunks, sh.Hq,
+                                    self.total_new, sh.scale, self._ws_pre, self._ws_pre.numel(),
+                                    stream)
+        return self.out_pre
+
+    def close(self):
+        if self.pool is not None:
+            kun.kun_kv_pool_destroy(self.pool)
+            self.pool = None

@@ -1,0 +1,145 @@
+"""CPU-only tests of the C-ABI boundary: the library loads, exports every declared symbol, and the
+host-side pool logic (growth, block resolution, validation, error codes) is bit-exact against the
+oracle's own resolver.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import paged_attention as O
+from paper_2412_18169_amd import kun
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+BASE = 0x7F0000000000          # fake, 256-aligned "device" addresses: never dereferenced on the host
+BB = 65536                     # block bytes of 8 kv heads x 128 dims x 16 tokens in bf16
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "kun.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kun_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert len(names) >= 14
+    L = kun.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(kun.SYMBOLS) == names
+
+
+def make_pool(nbytes=BB * 5, base=BASE):
+    return kun.kun_kv_pool_create(base, nbytes, kun.KUN_BF16, 8, 128, 16)
+
+
+def test_block_bytes_formula():
+    p = make_pool()
+    assert kun.kun_kv_pool_block_bytes(p) == 2 * 8 * 16 * 128 * 2 == BB
+    kun.kun_kv_pool_destroy(p)
+    p = kun.kun_kv_pool_create(BASE, 1 << 20, kun.KUN_F32, 2, 64, 16)
+    assert kun.kun_kv_pool_block_bytes(p) == 16384 and kun.kun_kv_pool_num_blocks(p) == 64
+    kun.kun_kv_pool_destroy(p)
+
+
+def test_growth_and_resolve_match_oracle_bit_exact():
+    sizes = [BB * 5 + 100, BB * 1, BB * 7 + BB - 1, BB * 3]       # remainders are unused
+    bases = [BASE, BASE + (1 << 30), BASE + (2 << 30), BASE + (3 << 30)]
+    p = make_pool(sizes[0], bases[0])
+    rb = [O.usable_blocks(sizes[0], BB)]
+    assert kun.kun_kv_pool_num_blocks(p) == 5
+    before = [kun.kun_kv_pool_resolve(p, b) for b in range(5)]
+    for sz, base in zip(sizes[1:], bases[1:]):
+        first, n = kun.kun_kv_pool_extend(p, base, sz)
+        assert first == sum(rb) and n == O.usable_blocks(sz, BB)
+        rb.append(n)
+        # ids and addresses of existing blocks are stable across an extension
+        assert [kun.kun_kv_pool_resolve(p, b) for b in range(5)] == before
+    assert kun.kun_kv_pool_num_ranges(p) == 4 and kun.kun_kv_pool_num_blocks(p) == sum(rb) == 16
+    for blk in range(sum(rb)):
+        r, off, addr = kun.kun_kv_pool_resolve(p, blk)
+        assert (r, off) == O.block_byte_offset(rb, blk, BB)
+        assert addr == bases[r] + off
+    for bad in (-1, 16, 1 << 40):
+        with pytest.raises(kun.KunError) as e:
+            kun.kun_kv_pool_resolve(p, bad)
+        assert e.value.status == -5
+    kun.kun_kv_pool_destroy(p)
+
+
+def test_large_pool_offsets_are_64_bit():
+    # 150 GB in five ranges: byte offsets exceed 2^32 and block ids exceed 2^15
+    per = 30 * 10**9
+    p = make_pool(per, BASE)
+    for i in range(1, 5):
+        kun.kun_kv_pool_extend(p, BASE + i * (1 << 36), per)
+    nb = per // BB
+    assert kun.kun_kv_pool_num_blocks(p) == 5 * nb
+    for blk in (0, 32768, nb - 1, nb, 3 * nb + 12345, 5 * nb - 1):
+        r, off, addr = kun.kun_kv_pool_resolve(p, blk)
+        assert (r, off) == O.block_byte_offset([nb] * 5, blk, BB)
+        assert addr == BASE + r * (1 << 36) + off
+    kun.kun_kv_pool_destroy(p)
+
+
+def test_error_paths():
+    def status(fn, *a):
+        with pytest.raises(kun.KunError) as e:
+            fn(*a)
+        return e.value.status
+    assert status(kun.kun_kv_pool_create, BASE + 8, BB * 4, kun.KUN_BF16, 8, 128, 16) == -2    # misaligned
+    assert status(kun.kun_kv_pool_create, BASE, BB - 1, kun.KUN_BF16, 8, 128, 16) == -3        # too small
+    assert status(kun.kun_kv_pool_create, 0, BB * 4, kun.KUN_BF16, 8, 128, 16) == -1           # null base
+    assert status(kun.kun_kv_pool_create, BASE, BB * 4, 7, 8, 128, 16) == -1                   # bad dtype
+    assert status(kun.kun_kv_pool_create, BASE, BB * 4, kun.KUN_BF16, 8, 128, 32) == -8        # block size
+    assert status(kun.kun_kv_pool_create, BASE, BB * 4, kun.KUN_BF16, 8, 96, 16) == -8         # head dim
+    p = make_pool()
+    assert status(kun.kun_kv_pool_extend, p, BASE + 17, BB * 2) == -2
+    assert status(kun.kun_kv_pool_extend, p, BASE + (1 << 30), 100) == -3
+    assert status(kun.kun_kv_pool_extend, p, BASE + BB, BB * 2) == -9                          # overlaps range 0
+    assert status(kun.kun_kv_pool_extend, 0, BASE + (1 << 30), BB * 2) == -1                   # null handle
+    for i in range(1, kun.KUN_MAX_RANGES):
+        kun.kun_kv_pool_extend(p, BASE + i * (1 << 30), BB)
+    assert status(kun.kun_kv_pool_extend, p, BASE + 17 * (1 << 30), BB) == -4                  # too many ranges
+    assert kun.kun_kv_pool_num_ranges(p) == kun.KUN_MAX_RANGES
+    # decode argument checks happen before any launch
+    assert kun.kun_decode_workspace_bytes(p, 4, 30, 0) == 0                                    # 30 % 8 != 0
+    assert status(kun.kun_paged_decode, p, BASE, BASE, BASE, 4, BASE, 2, 30, 1.0, 0, BASE, 1 << 30, 0) == -1
+    assert status(kun.kun_paged_decode, p, BASE, BASE, BASE, 4, BASE, 2, 24, 1.0, 0, BASE, 1 << 30, 0) == -8  # G = 3
+    assert status(kun.kun_paged_decode, p, BASE, BASE, BASE, 4, BASE, 2, 32, 1.0, 0, BASE, 16, 0) == -6       # workspace small
+    assert status(kun.kun_paged_decode, p, BASE, BASE, BASE, 4, BASE, 2, 32, 1.0, 0, BASE + 4, 1 << 30, 0) == -6
+    assert status(kun.kun_paged_decode, p, 0, BASE, BASE, 4, BASE, 2, 32, 1.0, 0, BASE, 1 << 30, 0) == -1
+    assert status(kun.kun_kv_append, p, 0, BASE, BASE, BASE, 3, BASE, 4, 0) == -1
+    kun.kun_kv_append(p, 0, 0, 0, 0, 0, 0, 0, 0)                                               # T == 0: no-op
+    kun.kun_paged_decode(p, 0, 0, 0, 0, 0, 0, 32, 1.0, 0, 0, 0, 0)                             # S == 0: no-op
+    kun.kun_kv_pool_destroy(p)
+    assert kun.status_string(-5) == "KUN_ERR_BLOCK_OOB" and kun.status_string(0) == "KUN_OK"
+
+
+def test_validate_block_table():
+    p = make_pool(BB * 10)
+    tab = torch.tensor([[3, 9, -1, -1], [0, 1, 2, 4]], dtype=torch.int32)
+    kun.kun_validate_block_table(p, tab, torch.tensor([20, 64], dtype=torch.int32))
+    kun.kun_validate_block_table(p, tab, torch.tensor([32, 49], dtype=torch.int32))   # -1 beyond ctx ignored
+    for lens, code in [([33, 64], -5), ([20, 65], -1), ([-1, 3], -1)]:
+        with pytest.raises(kun.KunError) as e:
+            kun.kun_validate_block_table(p, tab, torch.tensor(lens, dtype=torch.int32))
+        assert e.value.status == code
+    tab[1, 3] = 10
+    with pytest.raises(kun.KunError) as e:
+        kun.kun_validate_block_table(p, tab, torch.tensor([20, 64], dtype=torch.int32))
+    assert e.value.status == -5
+    kun.kun_kv_pool_destroy(p)
+
+
+def test_workspace_size_is_monotone_in_the_bound():
+    p = make_pool(30 * 10**9)
+    prev = 0
+    for ub in [1, 1000, 100000, 131071, 131072, 262143, 262144, 600000, 1048575, 1048576, 2097151, 2097152, 5000000]:
+        need = kun.kun_decode_workspace_bytes(p, 256, 64, ub)
+        assert need >= prev and need % 256 == 0
+        prev = need
+    kun.kun_kv_pool_destroy(p)

@@ -186,8 +186,8 @@ def cpu_baseline(dw, target_s):
 
 
 # Largest workload every part of which is implemented; chunked prefill joins when its kernel lands.
-DEFAULT_CONFIG = 3
-PREFILL_SUPPORTED = False
+DEFAULT_CONFIG = 4
+PREFILL_SUPPORTED = True
 ORACLE_TOKENS_PER_S = 80000.0      # rough speed of the numpy oracle, only used to size its sample
 TRAFFIC_BYTES = {}                 # per-launch HBM bytes from rocprofv3 --pmc runs (see profiles/)
 

@@ -1,14 +1,360 @@
-// Chunked prefill (placeholder until the MFMA kernel lands): entry points reject every call.
+// Chunked prefill over paged K/V: bf16, head_dim 128, block 16, MFMA 32x32x16 with fp32 accumulation.
+//
+// A chunk of c new tokens after p prior tokens attends to keys 0 .. p + r for its row r
+// (Section 4.3, Eq. 1: prefix attention p*c plus causal self attention (c*c + c)/2 pairs).  This is
+// the compute-bound part of a serving iteration (Section 2.1), so it runs on the matrix cores.
+//
+// Work item = (chunk, tile of query positions, kv head).  The G query heads that share the kv head
+// are stacked into the row dimension (row = position * G + head), so a K/V tile staged in LDS
+// serves all of them.  A workgroup has 4 waves; each wave owns 32 * NQ rows and walks the keys in
+// tiles of 64 (four KV blocks), flash-attention style:
+//
+//   S^T[key][row]  = K[key][:] . Q[row][:]          A = K fragment from LDS, B = Q in registers
+//   online softmax over keys, per row: each lane column holds one row, so max/sum are in-lane
+//                                                    plus one exchange between the two lane halves
+//   O^T[dim][row] += V^T[dim][key] P^T[key][row]    A = V^T fragment from LDS (pages store V as
+//                                                    [dim][token]), B = P straight from the S^T
+//                                                    accumulator registers, rounded to bf16
+//
+// S^T tile rows are mapped to keys so that the 8 accumulator values a lane feeds to one PV MFMA
+// are 8 consecutive keys of one KV block, i.e. one 16-byte LDS read of V^T.
+#include <math.h>
+#include <stdlib.h>
+
 #include "kun_internal.h"
 
+namespace {
+
+constexpr int kBlock = 16;
+constexpr int D = 128;
+constexpr int BN = 64;                  // keys per LDS tile (4 KV blocks)
+constexpr int kBlocksPerTile = BN / kBlock;
+constexpr float kLog2e = 1.4426950408889634f;
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+union Frag {
+    uint4 u;
+    bf16x8 v;
+};
+
+struct PrefillArgs {
+    KunRanges rt;
+    const void* q;
+    void* out;
+    const int32_t* q_start;
+    const int32_t* prior;
+    const int32_t* table;
+    int32_t* n_items;     // workspace
+    int2* items;          // workspace: (chunk, position tile)
+    int max_blocks;
+    int n_chunks, Hkv, Hq;
+    int max_items;
+    float scale_log2;
+    unsigned block_bytes, page_bytes;
+};
+
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
+    unsigned u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
+    return (unsigned)f32_to_bf16_rne(a) | ((unsigned)f32_to_bf16_rne(b) << 16);
+}
+
+// One workgroup lists the (chunk, tile) items; later tiles of a chunk (more keys) come first.
+__global__ __launch_bounds__(256) void prefill_plan_kernel(const int32_t* __restrict__ q_start, int n_chunks,
+                                                         int pos_per_tile, int max_items,
+                                                         int32_t* __restrict__ n_items, int2* __restrict__ items) {
+    __shared__ int base_s;
+    if (threadIdx.x == 0) base_s = 0;
+    __syncthreads();
+    for (int c0 = 0; c0 < n_chunks; c0 += 256) {
+        const int ch = c0 + threadIdx.x;
+        int nt = 0;
+        if (ch < n_chunks) nt = (q_start[ch + 1] - q_start[ch] + pos_per_tile - 1) / pos_per_tile;
+        // serial scan inside the group of 256 (n_chunks is small)
+        __shared__ int cnt[256];
+        cnt[threadIdx.x] = nt;
+        __syncthreads();
+        int first = base_s;
+        for (int i = 0; i < threadIdx.x; ++i) first += cnt[i];
+        for (int t = 0; t < nt; ++t)
+            if (first + t < max_items) items[first + t] = make_int2(ch, nt - 1 - t);
+        __syncthreads();
+        if (threadIdx.x == 255) base_s = first + nt;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *n_items = base_s < max_items ? base_s : max_items;
+}
+
+template <int G, int NQ>
+__global__ __launch_bounds__(256) void prefill_kernel(const PrefillArgs a) {
+    constexpr int ROWS_W = 32 * NQ;            // rows per wave
+    constexpr int ROWS = 4 * ROWS_W;           // rows per workgroup
+    constexpr int POS = ROWS / G;              // query positions per workgroup
+    constexpr int POS_W = ROWS_W / G;          // query positions per wave
+    static_assert(ROWS_W % G == 0, "a wave must hold whole positions");
+
+    __shared__ __attribute__((aligned(16))) unsigned char lds_k[kBlocksPerTile * 4096];
+    __shared__ __attribute__((aligned(16))) unsigned char lds_v[kBlocksPerTile * 4096];
+
+    const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
+    if (item >= *a.n_items) return;
+    const int2 it2 = a.items[item];
+    const int chunk = it2.x, qt = it2.y;
+    const int p = a.prior[chunk];
+    const int qs = a.q_start[chunk];
+    const int c = a.q_start[chunk + 1] - qs;
+    const int ctx = p + c;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, jh = lane >> 5;
+    const int pos0 = qt * POS;                         // first position of the workgroup (chunk-local)
+    const int wpos0 = pos0 + wave * POS_W;             // first position of the wave
+
+    // ---- Q as the B operand: q[nq][ks] = Q[row][16 ks + 8 jh .. +8] ---------------------------
+    Frag qf[NQ][8];
+    int vis[NQ];                                       // last visible key of the lane's row
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        const int row = wave * ROWS_W + nq * 32 + n;
+        int pos = pos0 + row / G;
+        const int g = row % G;
+        const bool live = pos < c;
+        if (!live) pos = c - 1;
+        vis[nq] = p + pos;
+        const char* qrow = (const char*)a.q + (((size_t)(qs + pos)) * a.Hq + kvh * G + g) * (D * 2);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[nq][ks].u = *(const uint4*)(qrow + (2 * ks + jh) * 16);
+    }
+    const int wave_last_pos = min(wpos0 + POS_W, c) - 1;
+    const int wave_vis_max = p + wave_last_pos;        // last key any row of the wave sees
+    const int wave_vis_min = p + min(wpos0, c - 1);    // last key the wave's first row sees
+    const int wg_vis_max = p + min(pos0 + POS, c) - 1; // last key the workgroup needs
+
+    f32x16 o[NQ][4];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[nq][dt][i] = 0.f;
+    float m[NQ], l[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) { m[nq] = -INFINITY; l[nq] = 0.f; }
+
+    // A-operand addressing of K: S^T tile row n -> key 16 (n/16) + 8 ((n/4)%2) + 4 ((n/8)%2) + n%4
+    const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);   // key inside a 32-key sub-tile
+    const int krow_blk = krow >> 4, krow_in = krow & 15;
+
+    const int32_t* trow = a.table + (size_t)chunk * a.max_blocks;
+    const int nblk_ctx = (ctx + kBlock - 1) / kBlock;
+    const int n_tiles = wg_vis_max / BN + 1;
+
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        // ---- stage 4 KV blocks: K rows swizzled by 16-byte chunk, V^T as stored ----------------
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < kBlocksPerTile; ++b) {
+            const int lb = kt * kBlocksPerTile + b;            // logical block
+            uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+            if (lb < nblk_ctx) {
+                const int id = __builtin_amdgcn_readfirstlane(trow[lb]);
+                const char* page = kun_block_addr(a.rt, id, a.block_bytes) + (size_t)kvh * a.page_bytes;
+                kv = *(const uint4*)(page + tid * 16);
+                vv = *(const uint4*)(page + 4096 + tid * 16);
+                // V^T: thread holds dim tid/2, tokens 8 (tid%2) .. +8 of the block; zero slots past the context
+                const int t0 = lb * kBlock + (tid & 1) * 8;
+                if (t0 + 8 > ctx) {
+                    unsigned w[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (t0 + e >= ctx) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                    vv = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+            const int r = tid >> 4, ch = tid & 15;             // K: row r, 16-byte chunk ch
+            *(uint4*)(lds_k + b * 4096 + r * 256 + ((ch ^ r) * 16)) = kv;
+            *(uint4*)(lds_v + b * 4096 + tid * 16) = vv;
+        }
+        __syncthreads();
+
+#pragma unroll
+        for (int st = 0; st < BN / 32; ++st) {
+            const int key0 = kt * BN + st * 32;                // first key of the sub-tile
+            if (key0 > wave_vis_max) continue;                 // nothing visible for this wave
+            // ---- S^T = K Q^T -------------------------------------------------------------------
+            f32x16 s[NQ];
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[nq][i] = 0.f;
+            const unsigned char* kbase = lds_k + (st * 2 + krow_blk) * 4096 + krow_in * 256;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                Frag kf;
+                kf.u = *(const uint4*)(kbase + (((2 * ks + jh) ^ krow_in) * 16));
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq)
+                    s[nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[nq][ks].v, s[nq], 0, 0, 0);
+            }
+            // ---- online softmax; register i <-> key key0 + 16 (i/8) + 8 jh + i%8 ---------------
+            const bool need_mask = (key0 + 31 > wave_vis_min);
+            Frag pb[NQ][2];
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq) {
+                float sc[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sc[i] = s[nq][i] * a.scale_log2;
+                if (need_mask) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = key0 + 16 * (i >> 3) + 8 * jh + (i & 7);
+                        if (key > vis[nq]) sc[i] = -INFINITY;
+                    }
+                }
+                float mx = sc[0];
+#pragma unroll
+                for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sc[i]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float mn = fmaxf(m[nq], mx);             // finite: key 0 is visible to every row
+                const float alpha = __builtin_amdgcn_exp2f(m[nq] - mn);
+                float ps = 0.f, pr[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    pr[i] = __builtin_amdgcn_exp2f(sc[i] - mn);
+                    ps += pr[i];
+                }
+                l[nq] = l[nq] * alpha + ps;
+                m[nq] = mn;
+                pb[nq][0].u = make_uint4(pack_bf16(pr[0], pr[1]), pack_bf16(pr[2], pr[3]),
+                                         pack_bf16(pr[4], pr[5]), pack_bf16(pr[6], pr[7]));
+                pb[nq][1].u = make_uint4(pack_bf16(pr[8], pr[9]), pack_bf16(pr[10], pr[11]),
+                                         pack_bf16(pr[12], pr[13]), pack_bf16(pr[14], pr[15]));
+                if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+                    for (int dt = 0; dt < 4; ++dt) o[nq][dt] *= alpha;
+                }
+            }
+            // ---- O^T += V^T P^T ------------------------------------------------------------------
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const unsigned char* vbase = lds_v + (st * 2 + h) * 4096 + n * 32 + jh * 16;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) {
+                    Frag vf;
+                    vf.u = *(const uint4*)(vbase + dt * 1024);
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq)
+                        o[nq][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pb[nq][h].v, o[nq][dt], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // ---- normalise and store: lane (row n, half jh) holds dims 32 dt + 8 (i/4) + 4 jh + i%4 -------
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        const float lt = l[nq] + __shfl_xor(l[nq], 32);
+        const float inv = 1.0f / lt;
+        const int row = wave * ROWS_W + nq * 32 + n;
+        const int pos = pos0 + row / G;
+        const int g = row % G;
+        if (pos < c) {
+            char* orow = (char*)a.out + (((size_t)(qs + pos)) * a.Hq + kvh * G + g) * (D * 2);
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const int dim = 32 * dt + 8 * i4 + 4 * jh;
+                    uint2 w;
+                    w.x = pack_bf16(o[nq][dt][4 * i4 + 0] * inv, o[nq][dt][4 * i4 + 1] * inv);
+                    w.y = pack_bf16(o[nq][dt][4 * i4 + 2] * inv, o[nq][dt][4 * i4 + 3] * inv);
+                    *(uint2*)(orow + dim * 2) = w;
+                }
+        }
+    }
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int rows_per_wg(int nq) { return 128 * nq; }
+
+int choose_nq() {
+    const char* e = getenv("KUN_PREFILL_NQ");
+    if (e) {
+        int v = atoi(e);
+        if (v == 1 || v == 2) return v;
+    }
+    return 1;
+}
+
+bool prefill_shape_ok(const kun_kv_pool* p, int n_chunks, int Hq, int total_new) {
+    return p && n_chunks >= 0 && Hq > 0 && Hq % p->Hkv == 0 && total_new >= 0;
+}
+
+template <int G>
+void launch_prefill(const PrefillArgs& a, dim3 grid, int nq, hipStream_t st) {
+    if (nq == 2) hipLaunchKernelGGL((prefill_kernel<G, 2>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((prefill_kernel<G, 1>), grid, dim3(256), 0, st, a);
+}
+
+}  // namespace
+
 extern "C" size_t kun_prefill_workspace_bytes(const kun_kv_pool* p, int n_chunks, int Hq, int total_new_tokens) {
-    (void)p; (void)n_chunks; (void)Hq; (void)total_new_tokens;
-    return 256;
+    if (!prefill_shape_ok(p, n_chunks, Hq, total_new_tokens)) return 0;
+    const int G = Hq / p->Hkv;
+    const int pos_min = 128 / (G > 0 ? G : 1);             // smallest tile (NQ = 1)
+    const size_t max_items = (size_t)total_new_tokens / (pos_min > 0 ? pos_min : 1) + n_chunks;
+    return 256 + align256(sizeof(int2) * max_items);
 }
 
 extern "C" int kun_paged_prefill_chunk(kun_kv_pool* p, const void* q, void* out, const int32_t* q_start,
                                        const int32_t* prior_len, const int32_t* block_table, int max_blocks,
                                        int n_chunks, int Hq, int total_new_tokens, float scale,
                                        void* workspace, size_t workspace_bytes, void* stream) {
-    return KUN_ERR_UNSUPPORTED;
+    if (!prefill_shape_ok(p, n_chunks, Hq, total_new_tokens)) return KUN_ERR_INVALID_ARG;
+    if (n_chunks == 0 || total_new_tokens == 0) return KUN_OK;
+    if (!q || !out || !q_start || !prior_len || !block_table || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
+    if (p->dtype != KUN_BF16 || p->d != 128 || p->B != 16) return KUN_ERR_UNSUPPORTED;
+    const int G = Hq / p->Hkv;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return KUN_ERR_UNSUPPORTED;
+    const size_t need = kun_prefill_workspace_bytes(p, n_chunks, Hq, total_new_tokens);
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < need) return KUN_ERR_WORKSPACE;
+
+    const int nq = choose_nq();
+    const int pos_per_tile = rows_per_wg(nq) / G;
+    PrefillArgs a;
+    a.rt = p->ranges;
+    a.q = q;
+    a.out = out;
+    a.q_start = q_start;
+    a.prior = prior_len;
+    a.table = block_table;
+    a.n_items = (int32_t*)workspace;
+    a.items = (int2*)((char*)workspace + 256);
+    a.max_blocks = max_blocks;
+    a.n_chunks = n_chunks;
+    a.Hkv = p->Hkv;
+    a.Hq = Hq;
+    a.max_items = total_new_tokens / pos_per_tile + n_chunks;
+    a.scale_log2 = scale * kLog2e;
+    a.block_bytes = (unsigned)p->block_bytes;
+    a.page_bytes = (unsigned)p->page_bytes;
+    hipStream_t st = (hipStream_t)stream;
+
+    hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(256), 0, st, q_start, n_chunks, pos_per_tile,
+                       a.max_items, a.n_items, a.items);
+    KUN_HIP_CHECK_LAUNCH();
+    const dim3 grid((unsigned)((size_t)a.max_items * p->Hkv));
+    switch (G) {
+        case 1: launch_prefill<1>(a, grid, nq, st); break;
+        case 2: launch_prefill<2>(a, grid, nq, st); break;
+        case 4: launch_prefill<4>(a, grid, nq, st); break;
+        default: launch_prefill<8>(a, grid, nq, st); break;
+    }
+    KUN_HIP_CHECK_LAUNCH();
+    return KUN_OK;
 }

@@ -1,0 +1,126 @@
+"""GPU parity of kun_paged_prefill_chunk against the CPU oracle (through the C ABI).
+bf16 inputs, fp32 accumulation: max-abs error <= 2e-2 against the fp64 oracle."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import bridge, paged_attention as O
+from paper_2412_18169_amd import kun, synth
+from paper_2412_18169_amd.runner import DeviceWorkload
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print(f"\n[gpu-case] {request.node.nodeid}", flush=True)
+    yield
+    os.environ.pop("KUN_PREFILL_NQ", None)
+
+
+def check_prefill(dw, rows_per_chunk=None, seed=0):
+    """Compare every chunk (all rows, or a seeded sample of rows incl. first and last) with the oracle."""
+    w, sh = dw.w, dw.w.shape
+    out = dw.prefill()
+    torch.cuda.synchronize()
+    got = out.double().cpu().numpy()
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(seed)
+    worst = 0.0
+    for i, (p, c) in enumerate(w.chunks):
+        if c == 0:
+            continue
+        seq = w.S + i
+        q0 = int(dw.q_start_host[i])
+        if rows_per_chunk is None or rows_per_chunk >= c:
+            rows = list(range(c))
+        else:
+            rows = sorted(set([0, c - 1] + list(rng.choice(c, size=rows_per_chunk, replace=False))))
+        pool, tab = bridge.compact_pool(dw.ranges, w.range_blocks, [w.block_tables[seq]], [p + c], sh.Hkv, sh.d,
+                                        sh.B, sh.dtype)
+        ref, _ = O.paged_prefill_chunk(pool, bridge.host_bits(dw.q_pre[q0:q0 + c]), tab[0], p, c, sh.Hq, sh.scale,
+                                       rows=rows)
+        err = np.abs(got[q0:q0 + c][rows] - ref).max()
+        worst = max(worst, err)
+        assert err <= TOL, f"chunk {i} (p={p}, c={c}): max abs err {err}"
+    return worst
+
+
+@pytest.mark.parametrize("nq", [1, 2])
+@pytest.mark.parametrize("G", [4, 8, 1, 2])
+def test_ragged_chunks(G, nq):
+    os.environ["KUN_PREFILL_NQ"] = str(nq)
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=128, B=16, dtype="bf16")
+    # priors / sizes around block, sub-tile (32), tile (64) and workgroup-tile edges; p = 0; c = 1
+    chunks = [(0, 1), (0, 17), (5, 1), (15, 16), (16, 33), (31, 64), (63, 65), (64, 129), (100, 200), (0, 300),
+              (333, 77), (700, 257), (1000, 31)]
+    w = synth.custom_workload("pre", sh, [3], chunks=chunks, extra_blocks=5, range_fracs=(0.4, 0.6))
+    dw = DeviceWorkload(w)
+    err = check_prefill(dw)
+    print("max err", err)
+    dw.close()
+
+
+def test_empty_chunk_is_skipped_and_first_row_returns_v():
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
+    w = synth.custom_workload("pre0", sh, [3], chunks=[(0, 5), (7, 0), (0, 40)], extra_blocks=2)
+    dw = DeviceWorkload(w)
+    dw.out_pre.fill_(3.0)
+    out = dw.prefill()
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    for i in (0, 2):        # first row of a chunk with no prior tokens sees only its own token
+        q0 = int(dw.q_start_host[i])
+        _, v = synth.kv_logical(w, w.S + i, 0, 1)
+        for h in range(sh.Hq):
+            assert torch.equal(out[q0, h].cpu(), v[0, h // sh.G])
+    check_prefill(dw)
+    dw.close()
+
+
+def test_chunk_rows_equal_unchunked_prefill_on_gpu():
+    # a later chunk also attends to the earlier ones: rows of chunk (p, c) == rows p..p+c-1 of (0, p+c)
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
+    L = 333
+    w = synth.custom_workload("eq", sh, [], chunks=[(0, L), (0, 100), (100, 150), (250, 83)], extra_blocks=0)
+    dw = DeviceWorkload(w, fill=False)
+    k, v = synth.kv_logical(w, 0, 0, L, dw.dev)
+    for i in range(4):
+        synth.write_pages(w, dw.ranges, i, 0, w.chunks[i][0] + w.chunks[i][1], k[:w.chunks[i][0] + w.chunks[i][1]],
+                          v[:w.chunks[i][0] + w.chunks[i][1]])
+    qfull = synth.q_chunk(w, 0, dw.dev)
+    dw.q_pre = torch.cat([qfull, qfull[0:100], qfull[100:250], qfull[250:333]]).contiguous()
+    out = dw.prefill().clone()
+    torch.cuda.synchronize()
+    full = out[:L].float()
+    parts = out[L:].float()
+    # same keys, same arithmetic per row up to tile order: well inside the bf16 output rounding
+    assert (full - parts).abs().max().item() <= 1.6e-2
+    check_prefill(dw)
+    dw.close()
+
+
+def test_decode_equals_one_token_chunk_on_gpu():
+    sh = synth.SHAPE_8B
+    w = synth.custom_workload("d1", sh, [500], chunks=[(499, 1)], extra_blocks=0)
+    dw = DeviceWorkload(w, fill=False)
+    k, v = synth.kv_logical(w, 0, 0, 500, dw.dev)
+    synth.write_pages(w, dw.ranges, 0, 0, 500, k, v)
+    synth.write_pages(w, dw.ranges, 1, 0, 500, k, v)
+    dw.q_pre = dw.q_dec.clone()
+    a = dw.decode().float()
+    b = dw.prefill().float()
+    torch.cuda.synchronize()
+    assert (a - b).abs().max().item() <= 1.6e-2
+    dw.close()
+
+
+def test_config4_prefill_chunks_sampled_rows():
+    w = synth.config(4)
+    dw = DeviceWorkload(w)
+    err = check_prefill(dw, rows_per_chunk=48)
+    print("cfg4 prefill max err", err)
+    dw.close()

@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=0, help="workload 2..5 (default: the largest supported)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (known HBM traffic) to scale rocprofv3 --pmc counters")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -99,6 +101,13 @@ def main():
         dw.decode()
         if ev: ev[3].record()
 
+    if args.pmc_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dw.dev).zero_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -145,6 +154,8 @@ def main():
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"], out["max_abs_err_vs_oracle"] = cpu_baseline(dw, args.cpu_seconds)
+        if has_prefill:
+            out["prefill_max_abs_err_vs_oracle"] = prefill_check(dw)
     dw.close()
     print(json.dumps(out), flush=True)
 
@@ -185,11 +196,32 @@ def cpu_baseline(dw, target_s):
                        f"fp64 numpy oracle"}, err)
 
 
+def prefill_check(dw, rows_per_chunk=6):
+    """GPU prefill output of a few rows of every chunk (first, last, seeded random) against the oracle."""
+    import torch
+    from oracle import bridge, paged_attention as O
+    w, sh = dw.w, dw.w.shape
+    got = dw.prefill().double().cpu().numpy()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(w.seed)
+    worst = 0.0
+    for i, (p, c) in enumerate(w.chunks):
+        seq = w.S + i
+        q0 = int(dw.q_start_host[i])
+        rows = sorted(set([0, c - 1] + list(rng.choice(c, size=min(c, rows_per_chunk), replace=False))))
+        pool, tab = bridge.compact_pool(dw.ranges, w.range_blocks, [w.block_tables[seq]], [p + c], sh.Hkv, sh.d,
+                                        sh.B, sh.dtype)
+        ref, _ = O.paged_prefill_chunk(pool, bridge.host_bits(dw.q_pre[q0:q0 + c]), tab[0], p, c, sh.Hq, sh.scale,
+                                       rows=rows)
+        worst = max(worst, float(np.abs(got[q0:q0 + c][rows] - ref).max()))
+    return worst
+
+
 # Largest workload every part of which is implemented; chunked prefill joins when its kernel lands.
-DEFAULT_CONFIG = 4
+DEFAULT_CONFIG = 5
 PREFILL_SUPPORTED = True
 ORACLE_TOKENS_PER_S = 80000.0      # rough speed of the numpy oracle, only used to size its sample
-TRAFFIC_BYTES = {}                 # per-launch HBM bytes from rocprofv3 --pmc runs (see profiles/)
+TRAFFIC_BYTES = {5: 17116829872}                 # per-launch HBM bytes from rocprofv3 --pmc runs (see profiles/)
 
 if __name__ == "__main__":
     main()

@@ -32,6 +32,8 @@ constexpr int kBlocksPerTile = BN / kBlock;
 constexpr float kLog2e = 1.4426950408889634f;
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 union Frag {
@@ -64,42 +66,79 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
     return (unsigned)f32_to_bf16_rne(a) | ((unsigned)f32_to_bf16_rne(b) << 16);
 }
 
-// One workgroup lists the (chunk, tile) items; later tiles of a chunk (more keys) come first.
-__global__ __launch_bounds__(256) void prefill_plan_kernel(const int32_t* __restrict__ q_start, int n_chunks,
-                                                         int pos_per_tile, int max_items,
-                                                         int32_t* __restrict__ n_items, int2* __restrict__ items) {
+// One workgroup lists the (chunk, position tile) items and orders them by decreasing number of key
+// tiles (longest first), so that the ragged causal costs pack well onto the CUs.
+constexpr int kPlanThreads = 1024;
+constexpr int kPlanSortMax = 4096;      // items beyond this stay in chunk order
+
+__global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_t* __restrict__ q_start,
+                                                                  const int32_t* __restrict__ prior, int n_chunks,
+                                                                  int pos_per_tile, int max_items,
+                                                                  int32_t* __restrict__ n_items,
+                                                                  int2* __restrict__ items) {
     __shared__ int base_s;
-    if (threadIdx.x == 0) base_s = 0;
+    __shared__ int cnt[kPlanThreads];
+    __shared__ int cost[kPlanSortMax];
+    __shared__ int2 tmp_item[kPlanSortMax];
+    const int tid = threadIdx.x;
+    if (tid == 0) base_s = 0;
     __syncthreads();
-    for (int c0 = 0; c0 < n_chunks; c0 += 256) {
-        const int ch = c0 + threadIdx.x;
-        int nt = 0;
-        if (ch < n_chunks) nt = (q_start[ch + 1] - q_start[ch] + pos_per_tile - 1) / pos_per_tile;
-        // serial scan inside the group of 256 (n_chunks is small)
-        __shared__ int cnt[256];
-        cnt[threadIdx.x] = nt;
+    for (int c0 = 0; c0 < n_chunks; c0 += kPlanThreads) {
+        const int ch = c0 + tid;
+        int nt = 0, c = 0, p = 0;
+        if (ch < n_chunks) {
+            c = q_start[ch + 1] - q_start[ch];
+            p = prior[ch];
+            nt = (c + pos_per_tile - 1) / pos_per_tile;
+        }
+        cnt[tid] = nt;
         __syncthreads();
         int first = base_s;
-        for (int i = 0; i < threadIdx.x; ++i) first += cnt[i];
-        for (int t = 0; t < nt; ++t)
-            if (first + t < max_items) items[first + t] = make_int2(ch, nt - 1 - t);
+        for (int i = 0; i < tid; ++i) first += cnt[i];
+        for (int t = 0; t < nt; ++t) {
+            const int k = first + t;
+            if (k >= max_items) break;
+            const int last_key = p + min(c, (t + 1) * pos_per_tile) - 1;
+            const int2 it = make_int2(ch, t);
+            if (k < kPlanSortMax) { cost[k] = last_key / BN + 1; tmp_item[k] = it; }
+            else items[k] = it;
+        }
         __syncthreads();
-        if (threadIdx.x == 255) base_s = first + nt;
+        if (tid == kPlanThreads - 1) base_s = first + nt;
         __syncthreads();
     }
-    if (threadIdx.x == 0) *n_items = base_s < max_items ? base_s : max_items;
+    const int total = base_s < max_items ? base_s : max_items;
+    const int ns = total < kPlanSortMax ? total : kPlanSortMax;
+    for (int i = tid; i < ns; i += kPlanThreads) {
+        const int ci = cost[i];
+        int rank = 0;
+        for (int j = 0; j < ns; ++j) {
+            const int cj = cost[j];
+            rank += (cj > ci || (cj == ci && j < i)) ? 1 : 0;
+        }
+        items[rank] = tmp_item[i];
+    }
+    if (tid == 0) *n_items = total;
 }
 
-template <int G, int NQ>
-__global__ __launch_bounds__(256) void prefill_kernel(const PrefillArgs a) {
+// Staging of one 64-key tile (4 KV blocks): K rows XOR-swizzled by 16-byte chunk, V^T pages as stored.
+template <int NT>
+struct TileRegs {
+    uint4 k[1024 / NT];
+    uint4 v[1024 / NT];
+};
+
+template <int G, int NW, int NQ>
+__global__ __launch_bounds__(64 * NW) void prefill_kernel(const PrefillArgs a) {
+    constexpr int NT = 64 * NW;                // threads
+    constexpr int LOADS = 1024 / NT;           // 16-byte K (and V) loads per thread per tile
     constexpr int ROWS_W = 32 * NQ;            // rows per wave
-    constexpr int ROWS = 4 * ROWS_W;           // rows per workgroup
+    constexpr int ROWS = NW * ROWS_W;          // rows per workgroup
     constexpr int POS = ROWS / G;              // query positions per workgroup
     constexpr int POS_W = ROWS_W / G;          // query positions per wave
     static_assert(ROWS_W % G == 0, "a wave must hold whole positions");
 
-    __shared__ __attribute__((aligned(16))) unsigned char lds_k[kBlocksPerTile * 4096];
-    __shared__ __attribute__((aligned(16))) unsigned char lds_v[kBlocksPerTile * 4096];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2][2][kBlocksPerTile * 4096];   // [stage][K|V]
 
     const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
     if (item >= *a.n_items) return;
@@ -114,6 +153,53 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillArgs a) {
     const int pos0 = qt * POS;                         // first position of the workgroup (chunk-local)
     const int wpos0 = pos0 + wave * POS_W;             // first position of the wave
 
+    const int32_t* trow = a.table + (size_t)chunk * a.max_blocks;
+    const int nblk_ctx = (ctx + kBlock - 1) / kBlock;
+    const int wg_vis_max = p + min(pos0 + POS, c) - 1; // last key the workgroup needs
+    const int n_tiles = wg_vis_max / BN + 1;
+
+    auto issue = [&](int kt, TileRegs<NT>& t) {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int idx = tid + i * NT;
+            const int lb = kt * kBlocksPerTile + (idx >> 8);   // logical block; uniform inside a wave
+            const int w = idx & 255;
+            uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+            if (lb < nblk_ctx) {
+                const int id = __builtin_amdgcn_readfirstlane(trow[lb]);
+                const char* page = kun_block_addr(a.rt, id, a.block_bytes) + (size_t)kvh * a.page_bytes;
+                kv = *(const uint4*)(page + w * 16);
+                vv = *(const uint4*)(page + 4096 + w * 16);
+            }
+            t.k[i] = kv;
+            t.v[i] = vv;
+        }
+    };
+    auto commit = [&](int kt, int stage, TileRegs<NT>& t) {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int idx = tid + i * NT;
+            const int b = idx >> 8, w = idx & 255;
+            uint4 vv = t.v[i];
+            // V^T: this thread holds dim w/2, tokens 8 (w%2) .. +8 of the block; slots past the context
+            // may hold anything (0 * NaN = NaN), so zero them
+            const int t0 = (kt * kBlocksPerTile + b) * kBlock + (w & 1) * 8;
+            if (t0 + 8 > ctx) {
+                unsigned x[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (t0 + e >= ctx) x[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                vv = make_uint4(x[0], x[1], x[2], x[3]);
+            }
+            const int r = w >> 4, ch = w & 15;
+            *(uint4*)(&lds[stage][0][b * 4096 + r * 256 + ((ch ^ r) * 16)]) = t.k[i];
+            *(uint4*)(&lds[stage][1][b * 4096 + w * 16]) = vv;
+        }
+    };
+
+    TileRegs<NT> treg;
+    issue(0, treg);
+
     // ---- Q as the B operand: q[nq][ks] = Q[row][16 ks + 8 jh .. +8] ---------------------------
     Frag qf[NQ][8];
     int vis[NQ];                                       // last visible key of the lane's row
@@ -122,17 +208,14 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillArgs a) {
         const int row = wave * ROWS_W + nq * 32 + n;
         int pos = pos0 + row / G;
         const int g = row % G;
-        const bool live = pos < c;
-        if (!live) pos = c - 1;
+        if (pos >= c) pos = c - 1;
         vis[nq] = p + pos;
         const char* qrow = (const char*)a.q + (((size_t)(qs + pos)) * a.Hq + kvh * G + g) * (D * 2);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qf[nq][ks].u = *(const uint4*)(qrow + (2 * ks + jh) * 16);
     }
-    const int wave_last_pos = min(wpos0 + POS_W, c) - 1;
-    const int wave_vis_max = p + wave_last_pos;        // last key any row of the wave sees
-    const int wave_vis_min = p + min(wpos0, c - 1);    // last key the wave's first row sees
-    const int wg_vis_max = p + min(pos0 + POS, c) - 1; // last key the workgroup needs
+    const int wave_vis_max = p + min(wpos0 + POS_W, c) - 1;   // last key any row of the wave sees
+    const int wave_vis_min = p + min(wpos0, c - 1);           // last key the wave's first row sees
 
     f32x16 o[NQ][4];
 #pragma unroll
@@ -141,7 +224,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillArgs a) {
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int i = 0; i < 16; ++i) o[nq][dt][i] = 0.f;
-    float m[NQ], l[NQ];
+    float m[NQ], l[NQ];                                // m in scaled (log2) units
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) { m[nq] = -INFINITY; l[nq] = 0.f; }
 
@@ -149,37 +232,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillArgs a) {
     const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);   // key inside a 32-key sub-tile
     const int krow_blk = krow >> 4, krow_in = krow & 15;
 
-    const int32_t* trow = a.table + (size_t)chunk * a.max_blocks;
-    const int nblk_ctx = (ctx + kBlock - 1) / kBlock;
-    const int n_tiles = wg_vis_max / BN + 1;
+    commit(0, 0, treg);
+    __syncthreads();
 
     for (int kt = 0; kt < n_tiles; ++kt) {
-        // ---- stage 4 KV blocks: K rows swizzled by 16-byte chunk, V^T as stored ----------------
-        __syncthreads();
-#pragma unroll
-        for (int b = 0; b < kBlocksPerTile; ++b) {
-            const int lb = kt * kBlocksPerTile + b;            // logical block
-            uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-            if (lb < nblk_ctx) {
-                const int id = __builtin_amdgcn_readfirstlane(trow[lb]);
-                const char* page = kun_block_addr(a.rt, id, a.block_bytes) + (size_t)kvh * a.page_bytes;
-                kv = *(const uint4*)(page + tid * 16);
-                vv = *(const uint4*)(page + 4096 + tid * 16);
-                // V^T: thread holds dim tid/2, tokens 8 (tid%2) .. +8 of the block; zero slots past the context
-                const int t0 = lb * kBlock + (tid & 1) * 8;
-                if (t0 + 8 > ctx) {
-                    unsigned w[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (t0 + e >= ctx) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                    vv = make_uint4(w[0], w[1], w[2], w[3]);
-                }
-            }
-            const int r = tid >> 4, ch = tid & 15;             // K: row r, 16-byte chunk ch
-            *(uint4*)(lds_k + b * 4096 + r * 256 + ((ch ^ r) * 16)) = kv;
-            *(uint4*)(lds_v + b * 4096 + tid * 16) = vv;
-        }
-        __syncthreads();
+        const int stage = kt & 1;
+        if (kt + 1 < n_tiles) issue(kt + 1, treg);
 
 #pragma unroll
         for (int st = 0; st < BN / 32; ++st) {
@@ -191,7 +249,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillArgs a) {
             for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s[nq][i] = 0.f;
-            const unsigned char* kbase = lds_k + (st * 2 + krow_blk) * 4096 + krow_in * 256;
+            const unsigned char* kbase = &lds[stage][0][(st * 2 + krow_blk) * 4096 + krow_in * 256];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
                 Frag kf;
@@ -205,34 +263,37 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillArgs a) {
             Frag pb[NQ][2];
 #pragma unroll
             for (int nq = 0; nq < NQ; ++nq) {
-                float sc[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sc[i] = s[nq][i] * a.scale_log2;
                 if (need_mask) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int key = key0 + 16 * (i >> 3) + 8 * jh + (i & 7);
-                        if (key > vis[nq]) sc[i] = -INFINITY;
+                        if (key > vis[nq]) s[nq][i] = -INFINITY;
                     }
                 }
-                float mx = sc[0];
+                float mx = s[nq][0];
 #pragma unroll
-                for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sc[i]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float mn = fmaxf(m[nq], mx);             // finite: key 0 is visible to every row
+                for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[nq][i]);
+                {   // both lane halves hold keys of the same row: exchange the maxima
+                    auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                    mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                }
+                const float mn = fmaxf(m[nq], mx * a.scale_log2);   // finite: key 0 is visible to every row
                 const float alpha = __builtin_amdgcn_exp2f(m[nq] - mn);
-                float ps = 0.f, pr[16];
+                float ps = 0.f;
+                f32x2 pr[8];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    pr[i] = __builtin_amdgcn_exp2f(sc[i] - mn);
-                    ps += pr[i];
+                    const float pv = __builtin_amdgcn_exp2f(fmaf(s[nq][i], a.scale_log2, -mn));
+                    ps += pv;
+                    pr[i >> 1][i & 1] = pv;
                 }
                 l[nq] = l[nq] * alpha + ps;
                 m[nq] = mn;
-                pb[nq][0].u = make_uint4(pack_bf16(pr[0], pr[1]), pack_bf16(pr[2], pr[3]),
-                                         pack_bf16(pr[4], pr[5]), pack_bf16(pr[6], pr[7]));
-                pb[nq][1].u = make_uint4(pack_bf16(pr[8], pr[9]), pack_bf16(pr[10], pr[11]),
-                                         pack_bf16(pr[12], pr[13]), pack_bf16(pr[14], pr[15]));
+                union { bf16x2 h[8]; uint4 u[2]; } cv;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) cv.h[i] = __builtin_convertvector(pr[i], bf16x2);
+                pb[nq][0].u = cv.u[0];
+                pb[nq][1].u = cv.u[1];
                 if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
                     for (int dt = 0; dt < 4; ++dt) o[nq][dt] *= alpha;
@@ -241,7 +302,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillArgs a) {
             // ---- O^T += V^T P^T ------------------------------------------------------------------
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const unsigned char* vbase = lds_v + (st * 2 + h) * 4096 + n * 32 + jh * 16;
+                const unsigned char* vbase = &lds[stage][1][(st * 2 + h) * 4096 + n * 32 + jh * 16];
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) {
                     Frag vf;
@@ -252,6 +313,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillArgs a) {
                 }
             }
         }
+        // the other stage was last read in the previous iteration, which every wave has left
+        if (kt + 1 < n_tiles) commit(kt + 1, stage ^ 1, treg);
+        __syncthreads();
     }
 
     // ---- normalise and store: lane (row n, half jh) holds dims 32 dt + 8 (i/4) + 4 jh + i%4 -------
@@ -269,10 +333,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillArgs a) {
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4) {
                     const int dim = 32 * dt + 8 * i4 + 4 * jh;
-                    uint2 w;
-                    w.x = pack_bf16(o[nq][dt][4 * i4 + 0] * inv, o[nq][dt][4 * i4 + 1] * inv);
-                    w.y = pack_bf16(o[nq][dt][4 * i4 + 2] * inv, o[nq][dt][4 * i4 + 3] * inv);
-                    *(uint2*)(orow + dim * 2) = w;
+                    union { bf16x2 h[2]; uint2 u; } w;
+                    w.h[0] = __builtin_convertvector((f32x2){o[nq][dt][4 * i4 + 0] * inv, o[nq][dt][4 * i4 + 1] * inv}, bf16x2);
+                    w.h[1] = __builtin_convertvector((f32x2){o[nq][dt][4 * i4 + 2] * inv, o[nq][dt][4 * i4 + 3] * inv}, bf16x2);
+                    *(uint2*)(orow + dim * 2) = w.u;
                 }
         }
     }
@@ -280,25 +344,30 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillArgs a) {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-int rows_per_wg(int nq) { return 128 * nq; }
+// Tile shape: NW waves x 32 NQ rows.  Default 8 waves x 32 rows (256 rows per workgroup).
+struct TileShape { int nw, nq; };
 
-int choose_nq() {
-    const char* e = getenv("KUN_PREFILL_NQ");
-    if (e) {
-        int v = atoi(e);
-        if (v == 1 || v == 2) return v;
+TileShape choose_shape() {
+    TileShape t{8, 1};
+    const char* e = getenv("KUN_PREFILL_SHAPE");      // "8x1", "4x2", "4x1"
+    if (e && e[0] && e[1] == 'x' && e[2]) {
+        const int nw = e[0] - '0', nq = e[2] - '0';
+        if ((nw == 8 && nq == 1) || (nw == 4 && (nq == 1 || nq == 2))) t = TileShape{nw, nq};
     }
-    return 1;
+    return t;
 }
+
+int rows_per_wg(TileShape t) { return t.nw * 32 * t.nq; }
 
 bool prefill_shape_ok(const kun_kv_pool* p, int n_chunks, int Hq, int total_new) {
     return p && n_chunks >= 0 && Hq > 0 && Hq % p->Hkv == 0 && total_new >= 0;
 }
 
 template <int G>
-void launch_prefill(const PrefillArgs& a, dim3 grid, int nq, hipStream_t st) {
-    if (nq == 2) hipLaunchKernelGGL((prefill_kernel<G, 2>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((prefill_kernel<G, 1>), grid, dim3(256), 0, st, a);
+void launch_prefill(const PrefillArgs& a, dim3 grid, TileShape t, hipStream_t st) {
+    if (t.nw == 8) hipLaunchKernelGGL((prefill_kernel<G, 8, 1>), grid, dim3(512), 0, st, a);
+    else if (t.nq == 2) hipLaunchKernelGGL((prefill_kernel<G, 4, 2>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((prefill_kernel<G, 4, 1>), grid, dim3(256), 0, st, a);
 }
 
 }  // namespace
@@ -324,8 +393,8 @@ extern "C" int kun_paged_prefill_chunk(kun_kv_pool* p, const void* q, void* out,
     const size_t need = kun_prefill_workspace_bytes(p, n_chunks, Hq, total_new_tokens);
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < need) return KUN_ERR_WORKSPACE;
 
-    const int nq = choose_nq();
-    const int pos_per_tile = rows_per_wg(nq) / G;
+    const TileShape shape = choose_shape();
+    const int pos_per_tile = rows_per_wg(shape) / G;
     PrefillArgs a;
     a.rt = p->ranges;
     a.q = q;
@@ -345,15 +414,15 @@ extern "C" int kun_paged_prefill_chunk(kun_kv_pool* p, const void* q, void* out,
     a.page_bytes = (unsigned)p->page_bytes;
     hipStream_t st = (hipStream_t)stream;
 
-    hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(256), 0, st, q_start, n_chunks, pos_per_tile,
-                       a.max_items, a.n_items, a.items);
+    hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, q_start, prior_len, n_chunks,
+                       pos_per_tile, a.max_items, a.n_items, a.items);
     KUN_HIP_CHECK_LAUNCH();
     const dim3 grid((unsigned)((size_t)a.max_items * p->Hkv));
     switch (G) {
-        case 1: launch_prefill<1>(a, grid, nq, st); break;
-        case 2: launch_prefill<2>(a, grid, nq, st); break;
-        case 4: launch_prefill<4>(a, grid, nq, st); break;
-        default: launch_prefill<8>(a, grid, nq, st); break;
+        case 1: launch_prefill<1>(a, grid, shape, st); break;
+        case 2: launch_prefill<2>(a, grid, shape, st); break;
+        case 4: launch_prefill<4>(a, grid, shape, st); break;
+        default: launch_prefill<8>(a, grid, shape, st); break;
     }
     KUN_HIP_CHECK_LAUNCH();
     return KUN_OK;

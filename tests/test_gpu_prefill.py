@@ -18,7 +18,7 @@ TOL = 2e-2
 def _announce(request):
     print(f"\n[gpu-case] {request.node.nodeid}", flush=True)
     yield
-    os.environ.pop("KUN_PREFILL_NQ", None)
+    os.environ.pop("KUN_PREFILL_SHAPE", None)
 
 
 def check_prefill(dw, rows_per_chunk=None, seed=0):
@@ -49,10 +49,10 @@ def check_prefill(dw, rows_per_chunk=None, seed=0):
     return worst
 
 
-@pytest.mark.parametrize("nq", [1, 2])
+@pytest.mark.parametrize("shape", ["8x1", "4x2", "4x1"])
 @pytest.mark.parametrize("G", [4, 8, 1, 2])
-def test_ragged_chunks(G, nq):
-    os.environ["KUN_PREFILL_NQ"] = str(nq)
+def test_ragged_chunks(G, shape):
+    os.environ["KUN_PREFILL_SHAPE"] = shape
     sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=128, B=16, dtype="bf16")
     # priors / sizes around block, sub-tile (32), tile (64) and workgroup-tile edges; p = 0; c = 1
     chunks = [(0, 1), (0, 17), (5, 1), (15, 16), (16, 33), (31, 64), (63, 65), (64, 129), (100, 200), (0, 300),

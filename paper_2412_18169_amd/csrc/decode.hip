@@ -356,10 +356,26 @@ __global__ __launch_bounds__(64 * NW) void decode_partial_mfma(const DecodeArgs 
     const int pair0 = t0 / 32 + wave;
     const int pair_end = (t1 + 31) / 32;
 
+    // Block ids of this wave's pairs, 32 pairs per VGPR: lane 2k + b = block b of the wave's k-th
+    // pair of the current batch (one coalesced gather instead of a dependent load per pair).
+    auto load_ids = [&](int first_pair) -> int {
+        const int pr_l = first_pair + (lane >> 1) * NW;
+        int b = 2 * pr_l + (lane & 1);
+        if (b >= nblk) b = (2 * pr_l < nblk) ? 2 * pr_l : nblk - 1;   // odd tail / beyond the partition
+        return trow[b];
+    };
+    int ids = load_ids(pair0);
+    int ids_first = pair0;
+
     auto issue = [&](int pr, PairLoads& ld) {
-        const int bA = 2 * pr, bB = (2 * pr + 1 < nblk) ? 2 * pr + 1 : 2 * pr;
-        const int idA = __builtin_amdgcn_readfirstlane(trow[bA]);
-        const int idB = __builtin_amdgcn_readfirstlane(trow[bB]);
+        int k = (pr - ids_first) / NW;
+        if (k >= 32) {
+            ids = load_ids(pr);
+            ids_first = pr;
+            k = 0;
+        }
+        const int idA = __builtin_amdgcn_readlane(ids, 2 * k);
+        const int idB = __builtin_amdgcn_readlane(ids, 2 * k + 1);
         const char* pA = kun_block_addr(a.rt, idA, a.block_bytes) + (size_t)kvh * a.page_bytes;
         const char* pB = kun_block_addr(a.rt, idB, a.block_bytes) + (size_t)kvh * a.page_bytes;
         const char* kp = (krow_blk ? pB : pA) + k_off;
@@ -433,15 +449,30 @@ __global__ __launch_bounds__(64 * NW) void decode_partial_mfma(const DecodeArgs 
         }
     };
 
-    PairLoads cur, nxt;
+    // q must have landed before the loop: otherwise the wait for it is placed inside the loop, where
+    // it would also wait for the page loads that were just issued for the next pair
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(qf[kk].v));
+
+    // two register buffers used alternately, so the loads of the next pair stay in flight while the
+    // current pair is computed (no register copies, hence no wait on the younger loads)
+    PairLoads bufA, bufB;
     int pr = pair0;
-    if (pr < pair_end) issue(pr, cur);
-    while (pr < pair_end) {
-        const int prn = pr + NW;
-        if (prn < pair_end) issue(prn, nxt);
-        compute(pr, cur);
-        cur = nxt;
-        pr = prn;
+    if (pr < pair_end) {
+        issue(pr, bufA);
+        // The last pair is computed on a path of its own, so that the steady-state path always has
+        // the next pair's 16 loads behind the ones it waits for.
+        for (;;) {
+            const int pr1 = pr + NW;
+            if (pr1 >= pair_end) { compute(pr, bufA); break; }
+            issue(pr1, bufB);
+            compute(pr, bufA);
+            const int pr2 = pr1 + NW;
+            if (pr2 >= pair_end) { compute(pr1, bufB); break; }
+            issue(pr2, bufA);
+            compute(pr1, bufB);
+            pr = pr2;
+        }
     }
 
     // l: sum over the 4 token groups j of this head
@@ -492,6 +523,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a, i
 // ---------------------------------------------------------------------------------------------
 constexpr int kPartChoices[] = {256, 512, 1024, 2048, 4096};
 constexpr int kNumPartChoices = 5;
+constexpr int kPartDivisor = 2048;    // aim at >= this many (partition, kv head) workgroups
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -501,14 +533,15 @@ int64_t default_bound(const kun_kv_pool* p, int S, int64_t ub) {
     return ub;
 }
 
-// Partition size: aim at a few thousand workgroups (256 CUs, several workgroups each).
+// Partition size: the largest choice that still leaves a few thousand workgroups (256 CUs, several
+// workgroups each); measured best on the 8B/70B-shaped batches.
 int choose_part_tokens(const kun_kv_pool* p, int64_t ub) {
     const char* e = getenv("KUN_DECODE_PART");
     if (e) {
         int v = atoi(e);
         if (v >= 32 && v % 32 == 0) return v;
     }
-    const int64_t per = ub * p->Hkv / 4096;
+    const int64_t per = ub * p->Hkv / kPartDivisor;
     int P = kPartChoices[0];
     for (int i = 0; i < kNumPartChoices; ++i)
         if (per >= kPartChoices[i]) P = kPartChoices[i];
@@ -561,7 +594,7 @@ size_t kun_decode_workspace_bytes(const kun_kv_pool* p, int S, int Hq, int64_t u
     // The partition size steps up with the bound; size for the worst case at or below `ub`.
     size_t need = layout_for(p, S, Hq, ub, choose_part_tokens(p, ub)).total;
     for (int i = 1; i < kNumPartChoices; ++i) {
-        const int64_t edge = ((int64_t)kPartChoices[i] * 4096 + p->Hkv - 1) / p->Hkv - 1;   // last bound using choice i-1
+        const int64_t edge = ((int64_t)kPartChoices[i] * kPartDivisor + p->Hkv - 1) / p->Hkv - 1;   // last bound using choice i-1
         if (edge < ub && edge > 0) {
             size_t n2 = layout_for(p, S, Hq, edge, choose_part_tokens(p, edge)).total;
             if (n2 > need) need = n2;

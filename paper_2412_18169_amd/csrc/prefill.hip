@@ -30,6 +30,7 @@ constexpr int D = 128;
 constexpr int BN = 64;                  // keys per LDS tile (4 KV blocks)
 constexpr int kBlocksPerTile = BN / kBlock;
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLazy = 8.0f;           // log2 of the largest softmax numerator kept without rescaling
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
@@ -158,15 +159,28 @@ __global__ __launch_bounds__(64 * NW) void prefill_kernel(const PrefillArgs a) {
     const int wg_vis_max = p + min(pos0 + POS, c) - 1; // last key the workgroup needs
     const int n_tiles = wg_vis_max / BN + 1;
 
+    // Block ids this wave stages: LOADS per tile.  One VGPR holds them for TPB tiles (lane
+    // LOADS * t + i = tile batch_first + t, load i); the next batch is fetched half a batch early.
+    constexpr int TPB = 64 / LOADS;
+    auto load_ids = [&](int batch) -> int {
+        const int t = batch * TPB + lane / LOADS, i = lane % LOADS;
+        const int lb = t * kBlocksPerTile + ((wave * 64 + i * NT) >> 8);
+        return (lb < nblk_ctx) ? trow[lb] : 0;
+    };
+    int ids_cur = load_ids(0), ids_nxt = 0;
+
     auto issue = [&](int kt, TileRegs<NT>& t) {
+        const int rel = kt % TPB;
+        if (rel == 0 && kt > 0) ids_cur = ids_nxt;
+        if (rel == TPB / 2 && (kt / TPB + 1) * TPB < n_tiles) ids_nxt = load_ids(kt / TPB + 1);
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
             const int idx = tid + i * NT;
-            const int lb = kt * kBlocksPerTile + (idx >> 8);   // logical block; uniform inside a wave
+            const int lb = kt * kBlocksPerTile + ((wave * 64 + i * NT) >> 8);   // logical block; uniform inside a wave
             const int w = idx & 255;
             uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
             if (lb < nblk_ctx) {
-                const int id = __builtin_amdgcn_readfirstlane(trow[lb]);
+                const int id = __builtin_amdgcn_readlane(ids_cur, rel * LOADS + i);
                 const char* page = kun_block_addr(a.rt, id, a.block_bytes) + (size_t)kvh * a.page_bytes;
                 kv = *(const uint4*)(page + w * 16);
                 vv = *(const uint4*)(page + 4096 + w * 16);
@@ -193,7 +207,9 @@ __global__ __launch_bounds__(64 * NW) void prefill_kernel(const PrefillArgs a) {
             }
             const int r = w >> 4, ch = w & 15;
             *(uint4*)(&lds[stage][0][b * 4096 + r * 256 + ((ch ^ r) * 16)]) = t.k[i];
-            *(uint4*)(&lds[stage][1][b * 4096 + w * 16]) = vv;
+            // V^T rows are 32 B: swap the halves of every second group of 8 dims so that the 16 lanes of
+            // an A-operand read (dims n, n+1, ..) touch 16 different 16-byte bank groups
+            *(uint4*)(&lds[stage][1][b * 4096 + ((w ^ ((w >> 4) & 1)) * 16)]) = vv;
         }
     };
 
@@ -214,6 +230,12 @@ __global__ __launch_bounds__(64 * NW) void prefill_kernel(const PrefillArgs a) {
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qf[nq][ks].u = *(const uint4*)(qrow + (2 * ks + jh) * 16);
     }
+    // q must have landed before the loop: a wait for it inside the loop would also wait for the
+    // tile loads issued just before
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[nq][ks].v));
     const int wave_vis_max = p + min(wpos0 + POS_W, c) - 1;   // last key any row of the wave sees
     const int wave_vis_min = p + min(wpos0, c - 1);           // last key the wave's first row sees
 
@@ -277,7 +299,11 @@ __global__ __launch_bounds__(64 * NW) void prefill_kernel(const PrefillArgs a) {
                     auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
                     mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
                 }
-                const float mn = fmaxf(m[nq], mx * a.scale_log2);   // finite: key 0 is visible to every row
+                // The reference maximum only moves when the true one outgrows it by 2^kLazy: p stays
+                // below 2^kLazy (exact in fp32 and in bf16's exponent range) and o, l are rescaled rarely.
+                // mn is finite: key 0 is visible to every row and is in the first sub-tile.
+                const float mxs = mx * a.scale_log2;
+                const float mn = (mxs > m[nq] + kLazy) ? mxs : m[nq];
                 const float alpha = __builtin_amdgcn_exp2f(m[nq] - mn);
                 float ps = 0.f;
                 f32x2 pr[8];
@@ -302,7 +328,7 @@ __global__ __launch_bounds__(64 * NW) void prefill_kernel(const PrefillArgs a) {
             // ---- O^T += V^T P^T ------------------------------------------------------------------
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const unsigned char* vbase = &lds[stage][1][(st * 2 + h) * 4096 + n * 32 + jh * 16];
+                const unsigned char* vbase = &lds[stage][1][(st * 2 + h) * 4096 + n * 32 + ((jh ^ ((n >> 3) & 1)) * 16)];
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) {
                     Frag vf;

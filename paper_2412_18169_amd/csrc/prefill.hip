@@ -56,6 +56,7 @@ struct PrefillArgs {
     int max_items;
     float scale_log2;
     unsigned block_bytes, page_bytes;
+    unsigned flags;       // bit 0: skew the two waves of a SIMD with s_setprio
 };
 
 __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
@@ -368,17 +369,251 @@ __global__ __launch_bounds__(64 * NW) void prefill_kernel(const PrefillArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Ring variant (default): 8 waves x 32 rows, 64-key tiles in a 4-stage LDS ring filled by direct
+// global->LDS loads (no registers, no LDS stores), three tiles in flight, ONE barrier per tile.
+//
+// Every q tile of a (chunk, kv head) walks the same keys at about the same time, so a tile load sees
+// close to the full memory latency, not an L2 hit; the ring keeps ~96 KiB in flight per CU to cover it.
+//
+//   iteration kt:  wait until this thread's loads of tile kt have landed (two younger tiles stay in
+//                  flight)  ->  barrier (all parts of tile kt visible; everybody has left tile kt-1)
+//                  ->  issue tile kt+3 into the stage tile kt-1 used  ->  compute tile kt
+//
+// A lane's 16 bytes land at (wave-uniform LDS base in M0) + 16 * lane, so the K swizzle and the V^T swizzle
+// are applied on the global address side.  Loads past the context read the last valid block instead
+// (same count of loads per tile for every thread, so the wait counts stay exact); scores of such keys
+// are masked and their V^T fragments zeroed before the MFMA.
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(1))) const void* kun_gptr;
+typedef __attribute__((address_space(3))) void* kun_lptr;
+
+// s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt = bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+#define KUN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
+template <int G>
+__global__ __launch_bounds__(512) void prefill_ring_kernel(const PrefillArgs a) {
+    constexpr int NW = 8, NT = 512, LOADS = 2;
+    constexpr int ROWS_W = 32, ROWS = NW * ROWS_W, POS = ROWS / G, POS_W = ROWS_W / G;
+    constexpr int NSTAGE = 4, AHEAD = 3;
+    static_assert(ROWS_W % G == 0, "a wave must hold whole positions");
+    const bool getenv_prio = a.flags & 1;
+
+    __shared__ __attribute__((aligned(16))) unsigned char ring[NSTAGE][2 * kBlocksPerTile * 4096];
+    constexpr int V_OFF = kBlocksPerTile * 4096;       // V^T pages follow the K pages inside a stage
+
+    const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
+    if (item >= *a.n_items) return;
+    const int2 it2 = a.items[item];
+    const int chunk = it2.x, qt = it2.y;
+    const int p = a.prior[chunk];
+    const int qs = a.q_start[chunk];
+    const int c = a.q_start[chunk + 1] - qs;
+    const int ctx = p + c;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, jh = lane >> 5;
+    const int pos0 = qt * POS;
+    const int wpos0 = pos0 + wave * POS_W;
+
+    const int32_t* trow = a.table + (size_t)chunk * a.max_blocks;
+    const int nblk_ctx = (ctx + kBlock - 1) / kBlock;
+    const int wg_vis_max = p + min(pos0 + POS, c) - 1;
+    const int n_tiles = wg_vis_max / BN + 1;
+
+    // block ids this wave stages: LOADS per tile, TPB tiles per VGPR (see prefill_kernel)
+    constexpr int TPB = 64 / LOADS;
+    auto load_ids = [&](int batch) -> int {
+        const int t = batch * TPB + lane / LOADS, i = lane % LOADS;
+        int lb = t * kBlocksPerTile + (wave >> 2) + 2 * i;
+        if (lb >= nblk_ctx) lb = nblk_ctx - 1;          // past the context: re-read the last block
+        return trow[lb];
+    };
+    int ids_cur = load_ids(0), ids_nxt = 0;
+
+    // per-lane source offsets inside a page for the slot this lane fills (slot = (wave % 4) * 64 + lane)
+    const int slot = (wave & 3) * 64 + lane;
+    const unsigned k_src = (slot >> 4) * 256 + (((slot & 15) ^ (slot >> 4)) * 16);
+    const unsigned v_src = 4096 + ((slot ^ ((slot >> 4) & 1)) * 16);
+
+    // The loads are issued through inline asm: the compiler then neither tracks them nor adds waits of
+    // its own in front of LDS reads; completion is tracked by hand with vmcnt (see `iteration`).
+    auto dma16 = [&](const char* src, unsigned lds_addr) {
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr) : "memory", "m0");
+    };
+    const unsigned ring_addr = (unsigned)(size_t)(kun_lptr)&ring[0][0];
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    auto issue = [&](int kt) {
+        const int rel = kt % TPB;
+        if (rel == 0 && kt > 0) ids_cur = ids_nxt;
+        if (rel == TPB / 2 && (kt / TPB + 1) * TPB < n_tiles) ids_nxt = load_ids(kt / TPB + 1);
+        const unsigned stage_addr = ring_addr + (kt % NSTAGE) * (2 * kBlocksPerTile * 4096);
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int b = (wave_u >> 2) + 2 * i;        // block of the tile this wave fills
+            const int id = __builtin_amdgcn_readlane(ids_cur, rel * LOADS + i);
+            const char* page = kun_block_addr(a.rt, id, a.block_bytes) + (size_t)kvh * a.page_bytes;
+            const unsigned dk = stage_addr + b * 4096 + (wave_u & 3) * 1024;
+            dma16(page + k_src, dk);
+            dma16(page + v_src, dk + V_OFF);
+        }
+    };
+
+    // ---- prologue: the first AHEAD tiles go in flight, then Q ------------------------------------
+    issue(0);
+    if (n_tiles > 1) issue(1);
+    if (n_tiles > 2) issue(2);
+
+    Frag qf[8];
+    int pos = pos0 + (wave * ROWS_W + n) / G;
+    const int g_head = (wave * ROWS_W + n) % G;
+    const bool live_row = pos < c;
+    if (!live_row) pos = c - 1;
+    const int vis = p + pos;                           // last key this lane's row sees
+    {
+        const char* qrow = (const char*)a.q + (((size_t)(qs + pos)) * a.Hq + kvh * G + g_head) * (D * 2);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[ks].u = *(const uint4*)(qrow + (2 * ks + jh) * 16);
+    }
+    const int wave_vis_max = p + min(wpos0 + POS_W, c) - 1;
+    const int wave_vis_min = p + min(wpos0, c - 1);
+
+    f32x16 o[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+    float m = -INFINITY, l = 0.f;                      // m in scaled (log2) units
+
+    const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
+    const int krow_blk = krow >> 4, krow_in = krow & 15;
+    const unsigned k_lane = krow_blk * 4096 + krow_in * 256;
+    const unsigned v_lane = V_OFF + n * 32 + ((jh ^ ((n >> 3) & 1)) * 16);
+    const float sl2 = a.scale_log2;
+
+    // all of this wave's work on the 64-key tile kt, which sits in `stage_base`
+    auto compute = [&](int kt, const unsigned char* stage_base) {
+#pragma unroll
+        for (int st = 0; st < BN / 32; ++st) {
+            const int key0 = kt * BN + st * 32;
+            if (key0 > wave_vis_max) continue;
+            f32x16 s;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[i] = 0.f;
+            const unsigned char* kbase = stage_base + st * 8192 + k_lane;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                Frag kf;
+                kf.u = *(const uint4*)(kbase + (((2 * ks + jh) ^ krow_in) * 16));
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s, 0, 0, 0);
+            }
+            // register i <-> key key0 + 16 (i/8) + 8 jh + i%8
+            if (key0 + 31 > wave_vis_min) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int key = key0 + 16 * (i >> 3) + 8 * jh + (i & 7);
+                    if (key > vis) s[i] = -INFINITY;
+                }
+            }
+            float mx = s[0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+            {
+                auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            }
+            const float mxs = mx * sl2;
+            const bool grow = mxs > m + kLazy;         // also true on the first sub-tile (m = -inf)
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                const float mn = grow ? mxs : m;       // finite: key 0 is visible to every row
+                const float alpha = __builtin_amdgcn_exp2f(m - mn);
+                l *= alpha;
+                m = mn;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) o[dt] *= alpha;
+            }
+            float ps0 = 0.f, ps1 = 0.f;
+            union { bf16x2 h[8]; uint4 u[2]; } cv;
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -m));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(s[i + 1], sl2, -m));
+                ps0 += p0;
+                ps1 += p1;
+                cv.h[i >> 1] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+            }
+            l += ps0 + ps1;
+            Frag pb[2];
+            pb[0].u = cv.u[0];
+            pb[1].u = cv.u[1];
+            const bool tail = key0 + 32 > ctx;         // keys past the context: their V^T may hold anything
+            const unsigned char* vbase = stage_base + st * 8192 + v_lane;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) {
+                    Frag vf;
+                    vf.u = *(const uint4*)(vbase + h * 4096 + dt * 1024);
+                    if (tail) {                        // 0 * NaN = NaN: zero the fragment's dead keys
+                        const int t0 = key0 + 16 * h + 8 * jh;
+                        unsigned x[4] = {vf.u.x, vf.u.y, vf.u.z, vf.u.w};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (t0 + e >= ctx) x[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                        vf.u = make_uint4(x[0], x[1], x[2], x[3]);
+                    }
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pb[h].v, o[dt], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks].v));   // q landed before the loop
+
+    // The two waves of a SIMD would otherwise run in lockstep (both in the MFMA phase, then both in the
+    // softmax phase) and the matrix pipe and the vector ALU would take turns idling.  Giving one of them
+    // priority lets it run ahead; the other fills whatever the first leaves free.
+    if (getenv_prio && wave >= NW / 2) __builtin_amdgcn_s_setprio(1);
+
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        // this thread's 4 loads of tile kt are older than those of tiles kt+1 and kt+2
+        if (kt + 2 < n_tiles) KUN_WAIT_VMCNT(8);
+        else if (kt + 1 < n_tiles) KUN_WAIT_VMCNT(4);
+        else KUN_WAIT_VMCNT(0);
+        __builtin_amdgcn_s_barrier();                  // tile kt complete in LDS; everybody has left tile kt-1
+        if (kt + AHEAD < n_tiles) issue(kt + AHEAD);   // into the stage tile kt-1 used
+        compute(kt, &ring[kt % NSTAGE][0]);
+    }
+
+    const float lt = l + __shfl_xor(l, 32);
+    const float inv = 1.0f / lt;
+    if (live_row) {
+        char* orow = (char*)a.out + (((size_t)(qs + pos)) * a.Hq + kvh * G + g_head) * (D * 2);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int dim = 32 * dt + 8 * i4 + 4 * jh;
+                union { bf16x2 h[2]; uint2 u; } w;
+                w.h[0] = __builtin_convertvector((f32x2){o[dt][4 * i4 + 0] * inv, o[dt][4 * i4 + 1] * inv}, bf16x2);
+                w.h[1] = __builtin_convertvector((f32x2){o[dt][4 * i4 + 2] * inv, o[dt][4 * i4 + 3] * inv}, bf16x2);
+                *(uint2*)(orow + dim * 2) = w.u;
+            }
+    }
+}
+
+
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Tile shape: NW waves x 32 NQ rows.  Default 8 waves x 32 rows (256 rows per workgroup).
-struct TileShape { int nw, nq; };
+struct TileShape { int nw, nq; bool pipe; };
 
 TileShape choose_shape() {
-    TileShape t{8, 1};
-    const char* e = getenv("KUN_PREFILL_SHAPE");      // "8x1", "4x2", "4x1"
+    TileShape t{8, 1, true};
+    const char* e = getenv("KUN_PREFILL_SHAPE");      // "ring" (default), "8x1", "4x2", "4x1"
     if (e && e[0] && e[1] == 'x' && e[2]) {
         const int nw = e[0] - '0', nq = e[2] - '0';
-        if ((nw == 8 && nq == 1) || (nw == 4 && (nq == 1 || nq == 2))) t = TileShape{nw, nq};
+        if ((nw == 8 && nq == 1) || (nw == 4 && (nq == 1 || nq == 2))) t = TileShape{nw, nq, false};
     }
     return t;
 }
@@ -391,7 +626,8 @@ bool prefill_shape_ok(const kun_kv_pool* p, int n_chunks, int Hq, int total_new)
 
 template <int G>
 void launch_prefill(const PrefillArgs& a, dim3 grid, TileShape t, hipStream_t st) {
-    if (t.nw == 8) hipLaunchKernelGGL((prefill_kernel<G, 8, 1>), grid, dim3(512), 0, st, a);
+    if (t.nw == 8 && t.pipe) hipLaunchKernelGGL((prefill_ring_kernel<G>), grid, dim3(512), 0, st, a);
+    else if (t.nw == 8) hipLaunchKernelGGL((prefill_kernel<G, 8, 1>), grid, dim3(512), 0, st, a);
     else if (t.nq == 2) hipLaunchKernelGGL((prefill_kernel<G, 4, 2>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((prefill_kernel<G, 4, 1>), grid, dim3(256), 0, st, a);
 }
@@ -438,6 +674,10 @@ extern "C" int kun_paged_prefill_chunk(kun_kv_pool* p, const void* q, void* out,
     a.scale_log2 = scale * kLog2e;
     a.block_bytes = (unsigned)p->block_bytes;
     a.page_bytes = (unsigned)p->page_bytes;
+    {
+        const char* e = getenv("KUN_PREFILL_PRIO");
+        a.flags = (e && e[0] == '0') ? 0u : 1u;
+    }
     hipStream_t st = (hipStream_t)stream;
 
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, q_start, prior_len, n_chunks,

@@ -391,9 +391,11 @@ typedef __attribute__((address_space(3))) void* kun_lptr;
 // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt = bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 #define KUN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
-template <int G>
-__global__ __launch_bounds__(512) void prefill_ring_kernel(const PrefillArgs a) {
-    constexpr int NW = 8, NT = 512, LOADS = 2;
+template <int G, int NW>
+__global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs a) {
+    constexpr int NSTAGERS = 8;                        // waves that issue the tile loads (4 loads per lane and tile)
+    constexpr int NT = 64 * NSTAGERS, LOADS = 2;
+    static_assert(NW >= NSTAGERS, "the first 8 waves stage the tiles");
     constexpr int ROWS_W = 32, ROWS = NW * ROWS_W, POS = ROWS / G, POS_W = ROWS_W / G;
     constexpr int NSTAGE = 4, AHEAD = 3;
     static_assert(ROWS_W % G == 0, "a wave must hold whole positions");
@@ -420,15 +422,25 @@ __global__ __launch_bounds__(512) void prefill_ring_kernel(const PrefillArgs a) 
     const int wg_vis_max = p + min(pos0 + POS, c) - 1;
     const int n_tiles = wg_vis_max / BN + 1;
 
-    // block ids this wave stages: LOADS per tile, TPB tiles per VGPR (see prefill_kernel)
     constexpr int TPB = 64 / LOADS;
-    auto load_ids = [&](int batch) -> int {
+    // Page addresses this wave stages, resolved a batch at a time in the vector lanes (lane LOADS*t + i
+    // = tile batch_first + t, load i): one table gather and one walk over the range table per TPB
+    // tiles, instead of dependent scalar loads in front of every tile's loads.
+    auto load_pages = [&](int batch) -> unsigned long long {
         const int t = batch * TPB + lane / LOADS, i = lane % LOADS;
         int lb = t * kBlocksPerTile + (wave >> 2) + 2 * i;
         if (lb >= nblk_ctx) lb = nblk_ctx - 1;          // past the context: re-read the last block
-        return trow[lb];
+        const int id = trow[lb];
+        int first = a.rt.first[0];
+        unsigned long long base = (unsigned long long)a.rt.base[0];
+        for (int r = 1; r < a.rt.n; ++r) {
+            const bool in = id >= a.rt.first[r];
+            first = in ? a.rt.first[r] : first;
+            base = in ? (unsigned long long)a.rt.base[r] : base;
+        }
+        return base + (unsigned long long)(id - first) * a.block_bytes + (unsigned long long)kvh * a.page_bytes;
     };
-    int ids_cur = load_ids(0), ids_nxt = 0;
+    unsigned long long pages_cur = load_pages(0), pages_nxt = 0;
 
     // per-lane source offsets inside a page for the slot this lane fills (slot = (wave % 4) * 64 + lane)
     const int slot = (wave & 3) * 64 + lane;
@@ -442,26 +454,41 @@ __global__ __launch_bounds__(512) void prefill_ring_kernel(const PrefillArgs a) 
     };
     const unsigned ring_addr = (unsigned)(size_t)(kun_lptr)&ring[0][0];
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    auto issue = [&](int kt) {
+    // A tile is 4 loads per lane of a stager wave: issue_begin picks the tile's addresses, issue_part(j)
+    // sends load j (block j/2, K or V^T).
+    unsigned iss_stage = 0;
+    const char* iss_page[LOADS];
+    auto issue_begin = [&](int kt) {
         const int rel = kt % TPB;
-        if (rel == 0 && kt > 0) ids_cur = ids_nxt;
-        if (rel == TPB / 2 && (kt / TPB + 1) * TPB < n_tiles) ids_nxt = load_ids(kt / TPB + 1);
-        const unsigned stage_addr = ring_addr + (kt % NSTAGE) * (2 * kBlocksPerTile * 4096);
+        if (rel == 0 && kt > 0) pages_cur = pages_nxt;
+        if (rel == TPB / 2 && (kt / TPB + 1) * TPB < n_tiles) pages_nxt = load_pages(kt / TPB + 1);
+        iss_stage = ring_addr + (kt % NSTAGE) * (2 * kBlocksPerTile * 4096) + (wave_u & 3) * 1024;
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
-            const int b = (wave_u >> 2) + 2 * i;        // block of the tile this wave fills
-            const int id = __builtin_amdgcn_readlane(ids_cur, rel * LOADS + i);
-            const char* page = kun_block_addr(a.rt, id, a.block_bytes) + (size_t)kvh * a.page_bytes;
-            const unsigned dk = stage_addr + b * 4096 + (wave_u & 3) * 1024;
-            dma16(page + k_src, dk);
-            dma16(page + v_src, dk + V_OFF);
+            const unsigned lo = __builtin_amdgcn_readlane((unsigned)pages_cur, rel * LOADS + i);
+            const unsigned hi = __builtin_amdgcn_readlane((unsigned)(pages_cur >> 32), rel * LOADS + i);
+            iss_page[i] = (const char*)(((unsigned long long)hi << 32) | lo);
         }
+    };
+    auto issue_part = [&](int j) {
+        const int i = j >> 1;
+        const unsigned dk = iss_stage + ((wave_u >> 2) + 2 * i) * 4096;
+        if (j & 1) dma16(iss_page[i] + v_src, dk + V_OFF);
+        else dma16(iss_page[i] + k_src, dk);
+    };
+    auto issue = [&](int kt) {
+        issue_begin(kt);
+#pragma unroll
+        for (int j = 0; j < 2 * LOADS; ++j) issue_part(j);
     };
 
     // ---- prologue: the first AHEAD tiles go in flight, then Q ------------------------------------
-    issue(0);
-    if (n_tiles > 1) issue(1);
-    if (n_tiles > 2) issue(2);
+    const bool stager = wave_u < NSTAGERS;
+    if (stager) {
+        issue(0);
+        if (n_tiles > 1) issue(1);
+        if (n_tiles > 2) issue(2);
+    }
 
     Frag qf[8];
     int pos = pos0 + (wave * ROWS_W + n) / G;
@@ -573,7 +600,10 @@ __global__ __launch_bounds__(512) void prefill_ring_kernel(const PrefillArgs a) 
     // The two waves of a SIMD would otherwise run in lockstep (both in the MFMA phase, then both in the
     // softmax phase) and the matrix pipe and the vector ALU would take turns idling.  Giving one of them
     // priority lets it run ahead; the other fills whatever the first leaves free.
-    if (getenv_prio && wave >= NW / 2) __builtin_amdgcn_s_setprio(1);
+    if (getenv_prio) {
+        if ((wave >> 2) == 1) __builtin_amdgcn_s_setprio(1);
+        else if ((wave >> 2) == 2) __builtin_amdgcn_s_setprio(2);
+    }
 
     for (int kt = 0; kt < n_tiles; ++kt) {
         // this thread's 4 loads of tile kt are older than those of tiles kt+1 and kt+2
@@ -581,7 +611,7 @@ __global__ __launch_bounds__(512) void prefill_ring_kernel(const PrefillArgs a) 
         else if (kt + 1 < n_tiles) KUN_WAIT_VMCNT(4);
         else KUN_WAIT_VMCNT(0);
         __builtin_amdgcn_s_barrier();                  // tile kt complete in LDS; everybody has left tile kt-1
-        if (kt + AHEAD < n_tiles) issue(kt + AHEAD);   // into the stage tile kt-1 used
+        if (stager && kt + AHEAD < n_tiles) issue(kt + AHEAD);   // into the stage tile kt-1 used
         compute(kt, &ring[kt % NSTAGE][0]);
     }
 
@@ -615,6 +645,9 @@ TileShape choose_shape() {
         const int nw = e[0] - '0', nq = e[2] - '0';
         if ((nw == 8 && nq == 1) || (nw == 4 && (nq == 1 || nq == 2))) t = TileShape{nw, nq, false};
     }
+    if (e && e[0] == '1' && e[1] == '2') t = TileShape{12, 1, true};   // "12x1": ring kernel with 12 waves
+    if (false) {
+    }
     return t;
 }
 
@@ -626,7 +659,8 @@ bool prefill_shape_ok(const kun_kv_pool* p, int n_chunks, int Hq, int total_new)
 
 template <int G>
 void launch_prefill(const PrefillArgs& a, dim3 grid, TileShape t, hipStream_t st) {
-    if (t.nw == 8 && t.pipe) hipLaunchKernelGGL((prefill_ring_kernel<G>), grid, dim3(512), 0, st, a);
+    if (t.nw == 12) hipLaunchKernelGGL((prefill_ring_kernel<G, 12>), grid, dim3(768), 0, st, a);
+    else if (t.nw == 8 && t.pipe) hipLaunchKernelGGL((prefill_ring_kernel<G, 8>), grid, dim3(512), 0, st, a);
     else if (t.nw == 8) hipLaunchKernelGGL((prefill_kernel<G, 8, 1>), grid, dim3(512), 0, st, a);
     else if (t.nq == 2) hipLaunchKernelGGL((prefill_kernel<G, 4, 2>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((prefill_kernel<G, 4, 1>), grid, dim3(256), 0, st, a);

@@ -49,7 +49,7 @@ def check_prefill(dw, rows_per_chunk=None, seed=0):
     return worst
 
 
-@pytest.mark.parametrize("shape", ["ring", "8x1", "4x2", "4x1"])
+@pytest.mark.parametrize("shape", ["ring", "12x1", "8x1", "4x2", "4x1"])
 @pytest.mark.parametrize("G", [4, 8, 1, 2])
 def test_ragged_chunks(G, shape):
     os.environ["KUN_PREFILL_SHAPE"] = shape

@@ -56,7 +56,6 @@ struct PrefillArgs {
     int max_items;
     float scale_log2;
     unsigned block_bytes, page_bytes;
-    unsigned flags;       // bit 0: skew the two waves of a SIMD with s_setprio
 };
 
 __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
@@ -399,7 +398,6 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     constexpr int ROWS_W = 32, ROWS = NW * ROWS_W, POS = ROWS / G, POS_W = ROWS_W / G;
     constexpr int NSTAGE = 4, AHEAD = 3;
     static_assert(ROWS_W % G == 0, "a wave must hold whole positions");
-    const bool getenv_prio = a.flags & 1;
 
     __shared__ __attribute__((aligned(16))) unsigned char ring[NSTAGE][2 * kBlocksPerTile * 4096];
     constexpr int V_OFF = kBlocksPerTile * 4096;       // V^T pages follow the K pages inside a stage
@@ -597,14 +595,6 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks].v));   // q landed before the loop
 
-    // The two waves of a SIMD would otherwise run in lockstep (both in the MFMA phase, then both in the
-    // softmax phase) and the matrix pipe and the vector ALU would take turns idling.  Giving one of them
-    // priority lets it run ahead; the other fills whatever the first leaves free.
-    if (getenv_prio) {
-        if ((wave >> 2) == 1) __builtin_amdgcn_s_setprio(1);
-        else if ((wave >> 2) == 2) __builtin_amdgcn_s_setprio(2);
-    }
-
     for (int kt = 0; kt < n_tiles; ++kt) {
         // this thread's 4 loads of tile kt are older than those of tiles kt+1 and kt+2
         if (kt + 2 < n_tiles) KUN_WAIT_VMCNT(8);
@@ -708,10 +698,6 @@ extern "C" int kun_paged_prefill_chunk(kun_kv_pool* p, const void* q, void* out,
     a.scale_log2 = scale * kLog2e;
     a.block_bytes = (unsigned)p->block_bytes;
     a.page_bytes = (unsigned)p->page_bytes;
-    {
-        const char* e = getenv("KUN_PREFILL_PRIO");
-        a.flags = (e && e[0] == '0') ? 0u : 1u;
-    }
     hipStream_t st = (hipStream_t)stream;
 
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, q_start, prior_len, n_chunks,

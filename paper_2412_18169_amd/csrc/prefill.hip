@@ -517,6 +517,68 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
 
     // all of this wave's work on the 64-key tile kt, which sits in `stage_base`
     auto compute = [&](int kt, const unsigned char* stage_base) {
+        if (kt * BN + BN - 1 <= wave_vis_min) {
+            // Fast path, the whole 64-key tile is visible to every row of the wave (no mask, no dead
+            // keys): both sub-tiles go through each phase together -- 16 QK^T MFMAs in two independent
+            // chains, one softmax pass over 32 values per lane, 16 PV MFMAs -- which halves the number
+            // of MFMA -> VALU -> MFMA hand-overs whose latencies the wave has to sit out.
+            f32x16 sa, sb;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { sa[i] = 0.f; sb[i] = 0.f; }
+            const unsigned char* kbase = stage_base + k_lane;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                Frag ka, kb;
+                const unsigned off = ((2 * ks + jh) ^ krow_in) * 16;
+                ka.u = *(const uint4*)(kbase + off);
+                kb.u = *(const uint4*)(kbase + 8192 + off);
+                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.v, qf[ks].v, sa, 0, 0, 0);
+                sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb.v, qf[ks].v, sb, 0, 0, 0);
+            }
+            float mx = fmaxf(sa[0], sb[0]);
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(sa[i], sb[i]));
+            {
+                auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            }
+            const float mxs = mx * sl2;
+            const bool grow = mxs > m + kLazy;
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                const float mn = grow ? mxs : m;
+                const float alpha = __builtin_amdgcn_exp2f(m - mn);
+                l *= alpha;
+                m = mn;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) o[dt] *= alpha;
+            }
+            float ps0 = 0.f, ps1 = 0.f, ps2 = 0.f, ps3 = 0.f;
+            union { bf16x2 h[16]; uint4 u[4]; } cv;
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[i], sl2, -m));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(sa[i + 1], sl2, -m));
+                const float p2 = __builtin_amdgcn_exp2f(fmaf(sb[i], sl2, -m));
+                const float p3 = __builtin_amdgcn_exp2f(fmaf(sb[i + 1], sl2, -m));
+                ps0 += p0; ps1 += p1; ps2 += p2; ps3 += p3;
+                cv.h[i >> 1] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+                cv.h[8 + (i >> 1)] = __builtin_convertvector((f32x2){p2, p3}, bf16x2);
+            }
+            l += (ps0 + ps1) + (ps2 + ps3);
+            const unsigned char* vbase = stage_base + v_lane;
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {              // the four KV blocks of the tile
+                Frag pb;
+                pb.u = cv.u[h];
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) {
+                    Frag vf;
+                    vf.u = *(const uint4*)(vbase + h * 4096 + dt * 1024);
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pb.v, o[dt], 0, 0, 0);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int st = 0; st < BN / 32; ++st) {
             const int key0 = kt * BN + st * 32;

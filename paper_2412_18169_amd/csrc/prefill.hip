@@ -58,6 +58,14 @@ struct PrefillArgs {
     unsigned block_bytes, page_bytes;
 };
 
+// max of three floats in one instruction.  Plain fmaxf makes the compiler canonicalise every MFMA
+// output first (one extra v_max per value); the instruction itself already handles NaN inputs.
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
     unsigned u = __float_as_uint(f);
     u += 0x7fffu + ((u >> 16) & 1u);
@@ -535,9 +543,15 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
                 sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.v, qf[ks].v, sa, 0, 0, 0);
                 sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb.v, qf[ks].v, sb, 0, 0, 0);
             }
-            float mx = fmaxf(sa[0], sb[0]);
+            float mx = max3(sa[0], sb[0], sa[1]);
+            float my = max3(sb[1], sa[2], sb[2]);      // two chains, half the dependent depth
 #pragma unroll
-            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(sa[i], sb[i]));
+            for (int i = 3; i < 15; i += 2) {
+                mx = max3(mx, sa[i], sb[i]);
+                my = max3(my, sa[i + 1], sb[i + 1]);
+            }
+            mx = max3(mx, sa[15], sb[15]);
+            mx = fmaxf(mx, my);
             {
                 auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
                 mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
@@ -601,9 +615,10 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
                     if (key > vis) s[i] = -INFINITY;
                 }
             }
-            float mx = s[0];
+            float mx = max3(s[0], s[1], s[2]);
 #pragma unroll
-            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+            for (int i = 3; i < 15; i += 2) mx = max3(mx, s[i], s[i + 1]);
+            mx = fmaxf(mx, s[15]);
             {
                 auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
                 mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));

@@ -356,28 +356,39 @@ __global__ __launch_bounds__(64 * NW) void decode_partial_mfma(const DecodeArgs 
     const int pair0 = t0 / 32 + wave;
     const int pair_end = (t1 + 31) / 32;
 
-    // Block ids of this wave's pairs, 32 pairs per VGPR: lane 2k + b = block b of the wave's k-th
-    // pair of the current batch (one coalesced gather instead of a dependent load per pair).
-    auto load_ids = [&](int first_pair) -> int {
+    // Page addresses of this wave's pairs, 32 pairs per register pair: lane 2k + b = block b of the
+    // wave's k-th pair of the current batch.  One coalesced table gather and one walk over the range
+    // table in the vector lanes, instead of dependent scalar loads in front of every pair's loads.
+    auto load_pages = [&](int first_pair) -> unsigned long long {
         const int pr_l = first_pair + (lane >> 1) * NW;
         int b = 2 * pr_l + (lane & 1);
         if (b >= nblk) b = (2 * pr_l < nblk) ? 2 * pr_l : nblk - 1;   // odd tail / beyond the partition
-        return trow[b];
+        const int id = trow[b];
+        int first = a.rt.first[0];
+        unsigned long long base = (unsigned long long)a.rt.base[0];
+        for (int r = 1; r < a.rt.n; ++r) {
+            const bool in = id >= a.rt.first[r];
+            first = in ? a.rt.first[r] : first;
+            base = in ? (unsigned long long)a.rt.base[r] : base;
+        }
+        return base + (unsigned long long)(id - first) * a.block_bytes + (unsigned long long)kvh * a.page_bytes;
     };
-    int ids = load_ids(pair0);
-    int ids_first = pair0;
+    unsigned long long pages = load_pages(pair0);
+    int pages_first = pair0;
 
     auto issue = [&](int pr, PairLoads& ld) {
-        int k = (pr - ids_first) / NW;
+        int k = (pr - pages_first) / NW;
         if (k >= 32) {
-            ids = load_ids(pr);
-            ids_first = pr;
+            pages = load_pages(pr);
+            pages_first = pr;
             k = 0;
         }
-        const int idA = __builtin_amdgcn_readlane(ids, 2 * k);
-        const int idB = __builtin_amdgcn_readlane(ids, 2 * k + 1);
-        const char* pA = kun_block_addr(a.rt, idA, a.block_bytes) + (size_t)kvh * a.page_bytes;
-        const char* pB = kun_block_addr(a.rt, idB, a.block_bytes) + (size_t)kvh * a.page_bytes;
+        const unsigned aLo = __builtin_amdgcn_readlane((unsigned)pages, 2 * k);
+        const unsigned aHi = __builtin_amdgcn_readlane((unsigned)(pages >> 32), 2 * k);
+        const unsigned bLo = __builtin_amdgcn_readlane((unsigned)pages, 2 * k + 1);
+        const unsigned bHi = __builtin_amdgcn_readlane((unsigned)(pages >> 32), 2 * k + 1);
+        const char* pA = (const char*)(((unsigned long long)aHi << 32) | aLo);
+        const char* pB = (const char*)(((unsigned long long)bHi << 32) | bLo);
         const char* kp = (krow_blk ? pB : pA) + k_off;
         const char* vp = (v_blk ? pB : pA) + v_off;
 #pragma unroll

@@ -79,6 +79,7 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 // tiles (longest first), so that the ragged causal costs pack well onto the CUs.
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanSortMax = 4096;      // items beyond this stay in chunk order
+constexpr int kPlanBuckets = 1024;      // cost buckets (key tiles); longer ones share the first bucket
 
 __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_t* __restrict__ q_start,
                                                                   const int32_t* __restrict__ prior, int n_chunks,
@@ -89,6 +90,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
     __shared__ int cnt[kPlanThreads];
     __shared__ int cost[kPlanSortMax];
     __shared__ int2 tmp_item[kPlanSortMax];
+    __shared__ int hist[kPlanBuckets];
     const int tid = threadIdx.x;
     if (tid == 0) base_s = 0;
     __syncthreads();
@@ -118,15 +120,30 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
     }
     const int total = base_s < max_items ? base_s : max_items;
     const int ns = total < kPlanSortMax ? total : kPlanSortMax;
+    // counting sort by decreasing cost: histogram, exclusive scan by one wave, scatter
+    for (int i = tid; i < kPlanBuckets; i += kPlanThreads) hist[i] = 0;
+    __syncthreads();
     for (int i = tid; i < ns; i += kPlanThreads) {
-        const int ci = cost[i];
-        int rank = 0;
-        for (int j = 0; j < ns; ++j) {
-            const int cj = cost[j];
-            rank += (cj > ci || (cj == ci && j < i)) ? 1 : 0;
-        }
-        items[rank] = tmp_item[i];
+        const int bkt = kPlanBuckets - 1 - min(cost[i], kPlanBuckets - 1);
+        cost[i] = bkt;
+        atomicAdd(&hist[bkt], 1);
     }
+    __syncthreads();
+    if (tid < 64) {
+        int carry = 0;
+        for (int b0 = 0; b0 < kPlanBuckets; b0 += 64) {
+            const int v = hist[b0 + tid];
+            int incl = v;
+            for (int o = 1; o < 64; o <<= 1) {
+                const int y = __shfl_up(incl, o);
+                if (tid >= o) incl += y;
+            }
+            hist[b0 + tid] = carry + incl - v;
+            carry += __shfl(incl, 63);
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < ns; i += kPlanThreads) items[atomicAdd(&hist[cost[i]], 1)] = tmp_item[i];
     if (tid == 0) *n_items = total;
 }
 

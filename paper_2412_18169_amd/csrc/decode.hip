@@ -310,7 +310,7 @@ struct PairLoads {
 };
 
 template <int NW>
-__global__ __launch_bounds__(64 * NW) void decode_partial_mfma(const DecodeArgs a) {
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_partial_mfma(const DecodeArgs a) {
     constexpr int D = 128;
     constexpr int GMAX = 16;
     __shared__ float sm_m[NW * GMAX], sm_l[NW * GMAX];

@@ -547,19 +547,32 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
             // keys): both sub-tiles go through each phase together -- 16 QK^T MFMAs in two independent
             // chains, one softmax pass over 32 values per lane, 16 PV MFMAs -- which halves the number
             // of MFMA -> VALU -> MFMA hand-overs whose latencies the wave has to sit out.
+            // All 16 K fragments are requested before the first MFMA and all 16 V^T fragments before the
+            // softmax, so one LDS latency is paid per phase instead of one per pair of MFMAs.
             f32x16 sa, sb;
 #pragma unroll
             for (int i = 0; i < 16; ++i) { sa[i] = 0.f; sb[i] = 0.f; }
             const unsigned char* kbase = stage_base + k_lane;
+            Frag ka[8], kb[8];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
-                Frag ka, kb;
                 const unsigned off = ((2 * ks + jh) ^ krow_in) * 16;
-                ka.u = *(const uint4*)(kbase + off);
-                kb.u = *(const uint4*)(kbase + 8192 + off);
-                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.v, qf[ks].v, sa, 0, 0, 0);
-                sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb.v, qf[ks].v, sb, 0, 0, 0);
+                ka[ks].u = *(const uint4*)(kbase + off);
+                kb[ks].u = *(const uint4*)(kbase + 8192 + off);
             }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks].v, qf[ks].v, sa, 0, 0, 0);
+                sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[ks].v, qf[ks].v, sb, 0, 0, 0);
+            }
+            const unsigned char* vbase = stage_base + v_lane;
+            Frag vf[16];
+#pragma unroll
+            for (int h = 0; h < 4; ++h)
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) vf[4 * h + dt].u = *(const uint4*)(vbase + h * 4096 + dt * 1024);
+            __builtin_amdgcn_sched_barrier(0);
             float mx = max3(sa[0], sb[0], sa[1]);
             float my = max3(sb[1], sa[2], sb[2]);      // two chains, half the dependent depth
 #pragma unroll
@@ -596,17 +609,13 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
                 cv.h[8 + (i >> 1)] = __builtin_convertvector((f32x2){p2, p3}, bf16x2);
             }
             l += (ps0 + ps1) + (ps2 + ps3);
-            const unsigned char* vbase = stage_base + v_lane;
 #pragma unroll
             for (int h = 0; h < 4; ++h) {              // the four KV blocks of the tile
                 Frag pb;
                 pb.u = cv.u[h];
 #pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    Frag vf;
-                    vf.u = *(const uint4*)(vbase + h * 4096 + dt * 1024);
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pb.v, o[dt], 0, 0, 0);
-                }
+                for (int dt = 0; dt < 4; ++dt)
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[4 * h + dt].v, pb.v, o[dt], 0, 0, 0);
             }
             return;
         }

@@ -1,0 +1,293 @@
+// Stand-alone measurement of what the two rooflines of the paged-attention path can reach on the
+// GPU at hand: it is not part of libkun.so and shares nothing with it.
+//
+//   1. HBM streaming read: a 16 GiB buffer read with grid-stride 16-byte loads, and read as
+//      scattered 8 KiB pieces at 64 KiB granularity (the footprint of one KV head's K + V^T page
+//      inside a block of the pool).  This is the ceiling of the decode step, which the paper
+//      classes as memory-bound (section 2.1).
+//   2. MFMA issue rate of v_mfma_f32_32x32x16_bf16 at two waves per SIMD with constant and with
+//      random operands (the clock the chip sustains depends on how much the operands toggle).
+//   3. The skeleton of a chunked-prefill tile loop (compute-bound per section 2.1): per 64-key
+//      tile and wave 16 MFMAs for S^T = K Q^T, an online softmax of the 32 x 64 scores, 16 MFMAs
+//      for O^T += V^T P^T, operands read from a 4-stage LDS ring, one barrier per tile, four
+//      direct global->LDS loads per lane and tile; every wave does the same work, nothing is
+//      masked, the source stays in L2.  Constant and random operands.
+//
+// Build: python -m paper_2412_18169_amd.build   (writes paper_2412_18169_amd/kun_ceilings)
+// Run:   ./paper_2412_18169_amd/kun_ceilings [hbm|mfma|tile|all]
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+union Frag {
+    uint4 u;
+    bf16x8 v;
+};
+
+#define CK(x)                                                                         \
+    do {                                                                              \
+        hipError_t e_ = (x);                                                          \
+        if (e_ != hipSuccess) {                                                       \
+            std::printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); \
+            std::exit(1);                                                             \
+        }                                                                             \
+    } while (0)
+
+template <typename F>
+static float time_ms(F launch, int reps) {
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    launch();
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0));
+    for (int r = 0; r < reps; ++r) launch();
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    float ms;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    CK(hipEventDestroy(e0));
+    CK(hipEventDestroy(e1));
+    return ms / reps;
+}
+
+// ---------------------------------------------------------------- 1. HBM read
+__global__ __launch_bounds__(256) void read_linear(const uint4* __restrict__ p, size_t n, unsigned* sink) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    unsigned s = 0;
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+        s += a.x ^ b.y ^ c.z ^ d.w;
+    }
+    for (; i < n; i += stride) s += p[i].x;
+    if (s == 0x12345678u) sink[0] = s;
+}
+
+// one workgroup reads 8 KiB (two 4 KiB halves) of head `h` of the 64 KiB block with a hashed id
+__global__ __launch_bounds__(256) void read_pages(const uint4* __restrict__ p, size_t nblocks, unsigned* sink) {
+    unsigned s = 0;
+    for (size_t w = blockIdx.x; w < nblocks * 8; w += gridDim.x) {
+        const size_t blk = (w / 8 * 2654435761ull) % nblocks, head = w % 8;
+        const uint4* page = p + blk * 4096 + head * 512;
+        const uint4 a = page[threadIdx.x], c = page[threadIdx.x + 256];
+        s += a.x ^ c.y;
+    }
+    if (s == 0x12345678u) sink[0] = s;
+}
+
+static void run_hbm() {
+    const size_t bytes = (size_t)16 << 30, n = bytes / 16, nblocks = bytes / 65536;
+    uint4* buf;
+    unsigned* sink;
+    CK(hipMalloc(&buf, bytes));
+    CK(hipMalloc(&sink, 4));
+    CK(hipMemset(buf, 1, bytes));
+    for (int grid : {2048, 8192, 16384}) {
+        const float ms = time_ms([&] { read_linear<<<grid, 256>>>(buf, n, sink); }, 5);
+        std::printf("hbm linear read, %5d workgroups:        %.0f GB/s\n", grid, bytes / ms / 1e6);
+    }
+    for (int grid : {2048, 8192, 32768}) {
+        const float ms = time_ms([&] { read_pages<<<grid, 256>>>(buf, nblocks, sink); }, 5);
+        std::printf("hbm scattered 8 KiB pages, %5d workgroups: %.0f GB/s\n", grid, bytes / ms / 1e6);
+    }
+    CK(hipFree(buf));
+    CK(hipFree(sink));
+}
+
+// bf16 bit patterns: constant 1.0, or sign/mantissa/low exponent bits from a linear congruential stream
+static std::vector<unsigned> operand_words(size_t nwords, bool random) {
+    std::vector<unsigned> h(nwords);
+    unsigned x = 99;
+    for (size_t i = 0; i < nwords; ++i) {
+        unsigned w = 0;
+        for (int half = 0; half < 2; ++half) {
+            x = x * 1664525u + 1013904223u;
+            w |= (0x3d00u + ((x >> 8) & 0x1ff) + ((x >> 31) << 15)) << (16 * half);
+        }
+        h[i] = random ? w : 0x3f803f80u;
+    }
+    return h;
+}
+
+// ---------------------------------------------------------------- 2. MFMA rate
+__global__ __launch_bounds__(512) void mfma_rate(float* out, const uint4* src, int iters) {
+    Frag a[8], b[8];
+    for (int i = 0; i < 8; ++i) {
+        a[i].u = src[(threadIdx.x * 8 + i) & 4095];
+        b[i].u = src[(threadIdx.x * 8 + i + 2048) & 4095];
+    }
+    f32x16 acc[4];
+    for (int k = 0; k < 4; ++k)
+        for (int i = 0; i < 16; ++i) acc[k][i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j].v, b[(j + k) & 7].v, acc[k], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int k = 0; k < 4; ++k)
+        for (int i = 0; i < 16; ++i) s += acc[k][i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+static void run_mfma(float* out, uint4* src) {
+    const int iters = 8000;
+    for (int random = 0; random < 2; ++random) {
+        const std::vector<unsigned> h = operand_words(4096 * 4, random);
+        CK(hipMemcpy(src, h.data(), 4096 * 16, hipMemcpyHostToDevice));
+        const float ms = time_ms([&] { mfma_rate<<<256, 512>>>(out, src, iters); }, 3);
+        std::printf("mfma 32x32x16 bf16, 2 waves/SIMD, %s operands: %.0f TFLOP/s\n", random ? "random  " : "constant",
+                    256.0 * 8 * iters * 32 * 32768.0 / ms / 1e9);
+    }
+}
+
+// ---------------------------------------------------------------- 3. attention tile loop
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// STAGE 0: operands from LDS only; 1: + one barrier per tile; 2: + the four global->LDS loads
+template <int STAGE>
+__global__ __launch_bounds__(512) void tile_loop(float* out, const uint4* gsrc, int iters, float sl2) {
+    __shared__ __attribute__((aligned(16))) unsigned char ring[4][32768];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, jh = lane >> 5;
+    for (int i = tid; i < 4 * 32768 / 16; i += 512) ((uint4*)&ring[0][0])[i] = gsrc[(i * 7 + blockIdx.x) & 8191];
+    __syncthreads();
+    Frag q;
+    q.u = gsrc[tid * 3 + 5];
+    f32x16 o[4];
+    for (int i = 0; i < 16; ++i)
+        for (int d = 0; d < 4; ++d) o[d][i] = 0;
+    float m = 0.f, l = 0.f;
+    // score row r of the 32 x 32 tile holds key krow, so that a lane's 8 scores per PV step are 8
+    // consecutive keys = one 16-byte read of a V^T row
+    const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
+    const int krow_blk = krow >> 4, krow_in = krow & 15;
+    const unsigned k_lane = krow_blk * 4096 + krow_in * 256;
+    const unsigned v_lane = 16384 + n * 32 + ((jh ^ ((n >> 3) & 1)) * 16);
+    const unsigned ring_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)&ring[0][0];
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    for (int it = 0; it < iters; ++it) {
+        if (STAGE >= 2) __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8): the tile read below has landed
+        if (STAGE >= 1) __builtin_amdgcn_s_barrier();
+        if (STAGE >= 2) {
+            const unsigned st = ring_addr + ((it + 3) & 3) * 32768 + (wave_u & 3) * 1024;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const char* page = (const char*)(gsrc + ((size_t)((it * 7 + wave_u * 2 + i) & 1023)) * 512);
+                const unsigned dk = st + ((wave_u >> 2) + 2 * i) * 4096;
+                asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(page + lane * 16), "s"(dk)
+                             : "memory", "m0");
+                asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(page + 4096 + lane * 16),
+                             "s"(dk + 16384)
+                             : "memory", "m0");
+            }
+        }
+        const unsigned char* stage_base = &ring[it & 3][0];
+        f32x16 sa, sb;
+        for (int i = 0; i < 16; ++i) {
+            sa[i] = 0.f;
+            sb[i] = 0.f;
+        }
+        const unsigned char* kbase = stage_base + k_lane;
+        Frag ka[8], kb[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const unsigned off = ((2 * ks + jh) ^ krow_in) * 16;
+            ka[ks].u = *(const uint4*)(kbase + off);
+            kb[ks].u = *(const uint4*)(kbase + 8192 + off);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks].v, q.v, sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[ks].v, q.v, sb, 0, 0, 0);
+        }
+        const unsigned char* vbase = stage_base + v_lane;
+        Frag vf[16];
+#pragma unroll
+        for (int h = 0; h < 4; ++h)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) vf[4 * h + d].u = *(const uint4*)(vbase + h * 4096 + d * 1024);
+        __builtin_amdgcn_sched_barrier(0);
+        float mx = max3(sa[0], sb[0], sa[1]), my = max3(sb[1], sa[2], sb[2]);
+#pragma unroll
+        for (int i = 3; i < 15; i += 2) {
+            mx = max3(mx, sa[i], sb[i]);
+            my = max3(my, sa[i + 1], sb[i + 1]);
+        }
+        mx = fmaxf(max3(mx, sa[15], sb[15]), my);
+        m = fmaxf(m, mx * sl2 - 8.f);
+        float ps0 = 0, ps1 = 0;
+        union {
+            bf16x2 h[16];
+            uint4 u[4];
+        } cv;
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[i], sl2, -m)), p1 = __builtin_amdgcn_exp2f(fmaf(sa[i + 1], sl2, -m));
+            const float p2 = __builtin_amdgcn_exp2f(fmaf(sb[i], sl2, -m)), p3 = __builtin_amdgcn_exp2f(fmaf(sb[i + 1], sl2, -m));
+            ps0 += p0 + p2;
+            ps1 += p1 + p3;
+            cv.h[i >> 1] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+            cv.h[8 + (i >> 1)] = __builtin_convertvector((f32x2){p2, p3}, bf16x2);
+        }
+        l += ps0 + ps1;
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            Frag pb;
+            pb.u = cv.u[h];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[4 * h + d].v, pb.v, o[d], 0, 0, 0);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no load into LDS may outlive the workgroup
+    float s = l + m;
+    for (int i = 0; i < 16; ++i)
+        for (int d = 0; d < 4; ++d) s += o[d][i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+static void run_tile(float* out, uint4* src) {
+    const int iters = 4000;
+    const double flops = 256.0 * 8 * iters * 32 * 32768.0;
+    for (int random = 0; random < 2; ++random) {
+        const std::vector<unsigned> h = operand_words(1024 * 8192 / 4, random);
+        CK(hipMemcpy(src, h.data(), 1024 * 8192, hipMemcpyHostToDevice));
+        const float t0 = time_ms([&] { tile_loop<0><<<256, 512>>>(out, src, iters, 0.01f); }, 1);
+        const float t1 = time_ms([&] { tile_loop<1><<<256, 512>>>(out, src, iters, 0.01f); }, 1);
+        const float t2 = time_ms([&] { tile_loop<2><<<256, 512>>>(out, src, iters, 0.01f); }, 1);
+        std::printf("attention tile loop, %s operands: LDS operands %.0f | + barrier %.0f | + global->LDS loads %.0f TFLOP/s\n",
+                    random ? "random  " : "constant", flops / t0 / 1e9, flops / t1 / 1e9, flops / t2 / 1e9);
+    }
+}
+
+int main(int argc, char** argv) {
+    const char* what = argc > 1 ? argv[1] : "all";
+    const bool all = !std::strcmp(what, "all");
+    hipDeviceProp_t prop;
+    CK(hipGetDeviceProperties(&prop, 0));
+    std::printf("device: %s (%s), %d CUs\n", prop.name, prop.gcnArchName, prop.multiProcessorCount);
+    float* out;
+    uint4* src;
+    CK(hipMalloc(&out, 256 * 512 * sizeof(float)));
+    CK(hipMalloc(&src, 1024 * 8192));
+    if (all || !std::strcmp(what, "mfma")) run_mfma(out, src);
+    if (all || !std::strcmp(what, "tile")) run_tile(out, src);
+    if (all || !std::strcmp(what, "hbm")) run_hbm();
+    CK(hipFree(out));
+    CK(hipFree(src));
+    return 0;
+}

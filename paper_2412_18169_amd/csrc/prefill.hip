@@ -31,6 +31,7 @@ constexpr int BN = 64;                  // keys per LDS tile (4 KV blocks)
 constexpr int kBlocksPerTile = BN / kBlock;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazy = 8.0f;           // log2 of the largest softmax numerator kept without rescaling
+constexpr float kSumCap = 8192.0f;      // 32 * 2^kLazy: a lane's 32 numerators can only sum above it if one exceeds 2^kLazy
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
@@ -60,6 +61,10 @@ struct PrefillArgs {
 
 // max of three floats in one instruction.  Plain fmaxf makes the compiler canonicalise every MFMA
 // output first (one extra v_max per value); the instruction itself already handles NaN inputs.
+// The compiler does not add the wait states an MFMA result needs before a vector ALU reads it when
+// the reader is inline asm, so `a` must come out of an instruction the compiler generated itself
+// after the MFMAs that wrote `b` and `c` (a chain that starts from a plain fmaxf over both
+// accumulators): by then every lane of those results has landed.
 __device__ __forceinline__ float max3(float a, float b, float c) {
     float r;
     asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
@@ -532,7 +537,7 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
-    float m = -INFINITY, l = 0.f;                      // m in scaled (log2) units
+    float m = -INFINITY, l = 0.f;                      // m in log2 units
 
     const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
     const int krow_blk = krow >> 4, krow_in = krow & 15;
@@ -542,16 +547,17 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
 
     // all of this wave's work on the 64-key tile kt, which sits in `stage_base`
     auto compute = [&](int kt, const unsigned char* stage_base) {
-        if (kt * BN + BN - 1 <= wave_vis_min) {
+        if (kt > 0 && kt * BN + BN - 1 <= wave_vis_min) {
             // Fast path, the whole 64-key tile is visible to every row of the wave (no mask, no dead
-            // keys): both sub-tiles go through each phase together -- 16 QK^T MFMAs in two independent
-            // chains, one softmax pass over 32 values per lane, 16 PV MFMAs -- which halves the number
-            // of MFMA -> VALU -> MFMA hand-overs whose latencies the wave has to sit out.
-            // All 16 K fragments are requested before the first MFMA and all 16 V^T fragments before the
-            // softmax, so one LDS latency is paid per phase instead of one per pair of MFMAs.
+            // keys) and the rows have a reference maximum m from an earlier tile.  Both sub-tiles go
+            // through each phase together: 16 QK^T MFMAs in two independent chains, one softmax pass
+            // over 32 values per lane, 16 PV MFMAs.  No maximum is taken: the row sums, needed anyway,
+            // show when a row's scores have outgrown its reference (sum of 32 numerators above
+            // 32 * 2^kLazy, or not a number after an overflow of exp2), and only
+            // then are the tile's scores taken again with a new reference.  All 16 K fragments are requested before
+            // the first MFMA and all 16 V^T fragments before the softmax, so one LDS latency is paid
+            // per phase instead of one per pair of MFMAs.
             f32x16 sa, sb;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) { sa[i] = 0.f; sb[i] = 0.f; }
             const unsigned char* kbase = stage_base + k_lane;
             Frag ka[8], kb[8];
 #pragma unroll
@@ -562,53 +568,75 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
+            for (int i = 0; i < 16; ++i) { sa[i] = 0.f; sb[i] = 0.f; }
+#pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
                 sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks].v, qf[ks].v, sa, 0, 0, 0);
                 sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[ks].v, qf[ks].v, sb, 0, 0, 0);
             }
             const unsigned char* vbase = stage_base + v_lane;
-            Frag vf[16];
+            Frag vf[16];                               // requested in two halves to stay inside the register file
 #pragma unroll
-            for (int h = 0; h < 4; ++h)
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) vf[4 * h + dt].u = *(const uint4*)(vbase + h * 4096 + dt * 1024);
             __builtin_amdgcn_sched_barrier(0);
-            float mx = max3(sa[0], sb[0], sa[1]);
-            float my = max3(sb[1], sa[2], sb[2]);      // two chains, half the dependent depth
+            float ps0 = 0.f, ps1 = 0.f, ps2 = 0.f, ps3 = 0.f;
+            union { bf16x2 h[16]; uint4 u[4]; } cv;
 #pragma unroll
-            for (int i = 3; i < 15; i += 2) {
-                mx = max3(mx, sa[i], sb[i]);
-                my = max3(my, sa[i + 1], sb[i + 1]);
+            for (int i = 0; i < 16; i += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[i], sl2, -m)), p1 = __builtin_amdgcn_exp2f(fmaf(sa[i + 1], sl2, -m));
+                const float p2 = __builtin_amdgcn_exp2f(fmaf(sb[i], sl2, -m)), p3 = __builtin_amdgcn_exp2f(fmaf(sb[i + 1], sl2, -m));
+                ps0 += p0; ps1 += p1; ps2 += p2; ps3 += p3;
+                cv.h[i >> 1] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+                cv.h[8 + (i >> 1)] = __builtin_convertvector((f32x2){p2, p3}, bf16x2);
             }
-            mx = max3(mx, sa[15], sb[15]);
-            mx = fmaxf(mx, my);
-            {
-                auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-            }
-            const float mxs = mx * sl2;
-            const bool grow = mxs > m + kLazy;
-            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-                const float mn = grow ? mxs : m;
+            float pt = (ps0 + ps1) + (ps2 + ps3);
+            if (__builtin_amdgcn_ballot_w64(!(pt <= kSumCap)) != 0) {
+                // rare: some row outgrew its reference.  Take the scores again, move the reference of
+                // those rows and redo the numerators.
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { sa[i] = 0.f; sb[i] = 0.f; }
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    const unsigned off = ((2 * ks + jh) ^ krow_in) * 16;
+                    Frag k0, k1;
+                    k0.u = *(const uint4*)(kbase + off);
+                    k1.u = *(const uint4*)(kbase + 8192 + off);
+                    sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0.v, qf[ks].v, sa, 0, 0, 0);
+                    sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1.v, qf[ks].v, sb, 0, 0, 0);
+                }
+                float mx = fmaxf(sa[0], sb[0]);        // the chain's first read of both accumulators
+#pragma unroll
+                for (int i = 1; i < 16; ++i) mx = max3(mx, sa[i], sb[i]);
+                {
+                    auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                    mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                }
+                const float mxs = mx * sl2;
+                const float mn = (mxs > m + kLazy) ? mxs : m;
                 const float alpha = __builtin_amdgcn_exp2f(m - mn);
                 l *= alpha;
                 m = mn;
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) o[dt] *= alpha;
-            }
-            float ps0 = 0.f, ps1 = 0.f, ps2 = 0.f, ps3 = 0.f;
-            union { bf16x2 h[16]; uint4 u[4]; } cv;
+                ps0 = ps1 = ps2 = ps3 = 0.f;
 #pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[i], sl2, -m));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(sa[i + 1], sl2, -m));
-                const float p2 = __builtin_amdgcn_exp2f(fmaf(sb[i], sl2, -m));
-                const float p3 = __builtin_amdgcn_exp2f(fmaf(sb[i + 1], sl2, -m));
-                ps0 += p0; ps1 += p1; ps2 += p2; ps3 += p3;
-                cv.h[i >> 1] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
-                cv.h[8 + (i >> 1)] = __builtin_convertvector((f32x2){p2, p3}, bf16x2);
+                for (int i = 0; i < 16; i += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[i], sl2, -m)), p1 = __builtin_amdgcn_exp2f(fmaf(sa[i + 1], sl2, -m));
+                    const float p2 = __builtin_amdgcn_exp2f(fmaf(sb[i], sl2, -m)), p3 = __builtin_amdgcn_exp2f(fmaf(sb[i + 1], sl2, -m));
+                    ps0 += p0; ps1 += p1; ps2 += p2; ps3 += p3;
+                    cv.h[i >> 1] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+                    cv.h[8 + (i >> 1)] = __builtin_convertvector((f32x2){p2, p3}, bf16x2);
+                }
+                pt = (ps0 + ps1) + (ps2 + ps3);
             }
-            l += (ps0 + ps1) + (ps2 + ps3);
+            l += pt;
+#pragma unroll
+            for (int h = 2; h < 4; ++h)
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) vf[4 * h + dt].u = *(const uint4*)(vbase + h * 4096 + dt * 1024);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int h = 0; h < 4; ++h) {              // the four KV blocks of the tile
                 Frag pb;
@@ -641,10 +669,9 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
                     if (key > vis) s[i] = -INFINITY;
                 }
             }
-            float mx = max3(s[0], s[1], s[2]);
+            float mx = fmaxf(s[0], s[1]);              // the chain's first read of the accumulator
 #pragma unroll
-            for (int i = 3; i < 15; i += 2) mx = max3(mx, s[i], s[i + 1]);
-            mx = fmaxf(mx, s[15]);
+            for (int i = 2; i < 16; i += 2) mx = max3(mx, s[i], s[i + 1]);
             {
                 auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
                 mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));

@@ -64,6 +64,33 @@ def test_ragged_chunks(G, shape):
     dw.close()
 
 
+@pytest.mark.parametrize("shape", ["ring", "12x1", "8x1"])
+@pytest.mark.parametrize("profile", ["steps", "jump", "decay"])
+def test_scores_that_outgrow_the_running_maximum(profile, shape):
+    # Key magnitude changes along the context, so the rows' reference maximum has to move on tiles
+    # far from the first one ("jump": by more than exp2 can hold in fp32), or never again ("decay").
+    os.environ["KUN_PREFILL_SHAPE"] = shape
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
+    chunks = [(0, 700), (512, 300), (900, 64)]
+    w = synth.custom_workload("grow", sh, [], chunks=chunks, extra_blocks=0)
+    dw = DeviceWorkload(w, fill=False)
+    for i, (p, c) in enumerate(chunks):
+        L = p + c
+        k, v = synth.kv_logical(w, i, 0, L, dw.dev)
+        t = torch.arange(L, device=dw.dev, dtype=torch.float32)
+        if profile == "steps":
+            f = 0.05 * 2.0 ** torch.floor(t / 96)             # doubles every 96 tokens
+        elif profile == "jump":
+            f = torch.where(t < 200, 0.02, 40.0) * torch.where(t >= 640, 4.0, 1.0)
+        else:
+            f = 8.0 * 0.5 ** torch.floor(t / 128)
+        k = (k.float() * f[:, None, None]).to(k.dtype)
+        synth.write_pages(w, dw.ranges, i, 0, L, k, v)
+    err = check_prefill(dw)
+    print("max err", err)
+    dw.close()
+
+
 def test_empty_chunk_is_skipped_and_first_row_returns_v():
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     w = synth.custom_workload("pre0", sh, [3], chunks=[(0, 5), (7, 0), (0, 40)], extra_blocks=2)

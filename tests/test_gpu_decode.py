@@ -84,6 +84,33 @@ def test_result_is_invariant_to_partitioning(part, waves):
     dw.close()
 
 
+@pytest.mark.parametrize("kernel", ["mfma", "generic"])
+@pytest.mark.parametrize("profile", ["steps", "jump", "decay"])
+def test_scores_that_outgrow_the_running_maximum(profile, kernel):
+    # key magnitude changes along the context: the running maximum moves late and by a lot
+    # ("jump": by more than exp2 can hold in fp32), or never again ("decay")
+    if kernel == "generic":
+        os.environ["KUN_DECODE_KERNEL"] = "generic"
+    os.environ["KUN_DECODE_PART"] = "256"
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
+    lens = [700, 1300, 64, 2500, 201]
+    w = synth.custom_workload("grow", sh, lens, extra_blocks=0)
+    dw = DeviceWorkload(w, fill=False)
+    for s_, L in enumerate(lens):
+        k, v = synth.kv_logical(w, s_, 0, L, dw.dev)
+        t = torch.arange(L, device=dw.dev, dtype=torch.float32)
+        if profile == "steps":
+            f = 0.05 * 2.0 ** torch.clamp(torch.floor(t / 96), max=10)   # scores stay well inside fp32's precision
+        elif profile == "jump":
+            f = torch.where(t < 200, 0.02, 40.0) * torch.where(t >= 640, 4.0, 1.0)
+        else:
+            f = 8.0 * 0.5 ** torch.floor(t / 128)
+        k = (k.float() * f[:, None, None]).to(k.dtype)
+        synth.write_pages(w, dw.ranges, s_, 0, L, k, v)
+    check_decode(dw)
+    dw.close()
+
+
 def test_length_one_returns_v_exactly_and_zero_length_is_skipped():
     for dtype, d in (("bf16", 128), ("f32", 64)):
         sh = synth.LayerShape(Hq=8, Hkv=2, d=d, B=16, dtype=dtype)

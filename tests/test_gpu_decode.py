@@ -111,6 +111,19 @@ def test_scores_that_outgrow_the_running_maximum(profile, kernel):
     dw.close()
 
 
+def test_batch_larger_than_one_pass_of_the_plan_kernel():
+    # 2500 requests (the plan kernel walks the batch 1024 at a time), some empty, a few long
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
+    rng = np.random.default_rng(21)
+    lens = rng.integers(1, 200, size=2500)
+    lens[rng.choice(2500, size=40, replace=False)] = 0
+    lens[[5, 1023, 1024, 2047, 2048, 2499]] = [3000, 700, 1, 5000, 16, 900]
+    w = synth.custom_workload("many", sh, lens, extra_blocks=3, range_fracs=(0.5, 0.25, 0.25))
+    dw = DeviceWorkload(w)
+    check_decode(dw)
+    dw.close()
+
+
 def test_length_one_returns_v_exactly_and_zero_length_is_skipped():
     for dtype, d in (("bf16", 128), ("f32", 64)):
         sh = synth.LayerShape(Hq=8, Hkv=2, d=d, B=16, dtype=dtype)

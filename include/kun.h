@@ -104,6 +104,19 @@ KUN_API int kun_kv_pool_destroy(kun_kv_pool* pool);
 KUN_API int kun_validate_block_table(const kun_kv_pool* pool, const int32_t* host_table, int rows,
                              int max_blocks, const int32_t* host_ctx_len);
 
+/* Device-side view of block resolution (section 4.1: blocks that live in the remapped tail of the
+ * KV region are addressed like any other).  For each of T (row, position) pairs -- device int32
+ * arrays as in kun_kv_append -- a kernel walks block_table (device int32 [rows, max_blocks]) and
+ * the range table exactly as the attention kernels do and writes, for KV head kv_head:
+ *   range_out[i]  index of the range that holds the token's block          (device int32 [T])
+ *   k_off_out[i]  byte offset inside that range of K[position][0]          (device int64 [T])
+ *   v_off_out[i]  byte offset inside that range of V[position][0]; element j of the V row sits
+ *                 j * block_size elements further on                       (device int64 [T])
+ * Integer outputs, exact.  T == 0 is a no-op. */
+KUN_API int kun_slot_map(const kun_kv_pool* pool, const int32_t* seq_of_tok, const int32_t* pos_of_tok,
+                 int T, const int32_t* block_table, int max_blocks, int kv_head,
+                 int32_t* range_out, int64_t* k_off_out, int64_t* v_off_out, void* stream);
+
 /* ---- KV append: write the K/V rows of new tokens into their slots -------------------------- */
 
 /* k_new, v_new: device [T, num_kv_heads, head_dim] in the pool's dtype.  Token i belongs to row

@@ -23,7 +23,7 @@ KUN_MAX_RANGES = 16
 SYMBOLS = [
     "kun_status_string", "kun_kv_pool_create", "kun_kv_pool_extend", "kun_kv_pool_num_blocks",
     "kun_kv_pool_num_ranges", "kun_kv_pool_block_bytes", "kun_kv_pool_resolve",
-    "kun_kv_pool_destroy", "kun_validate_block_table", "kun_kv_append",
+    "kun_kv_pool_destroy", "kun_validate_block_table", "kun_slot_map", "kun_kv_append",
     "kun_decode_workspace_bytes", "kun_paged_decode", "kun_prefill_workspace_bytes",
     "kun_paged_prefill_chunk",
 ]
@@ -60,6 +60,7 @@ def lib() -> ctypes.CDLL:
     L.kun_kv_pool_destroy.argtypes = [vp]
     L.kun_validate_block_table.argtypes = [vp, vp, i32, i32, vp]
     L.kun_kv_append.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, vp]
+    L.kun_slot_map.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp]
     L.kun_decode_workspace_bytes.restype = sz
     L.kun_decode_workspace_bytes.argtypes = [vp, i32, i32, i64]
     L.kun_paged_decode.argtypes = [vp, vp, vp, vp, i32, vp, i32, i32, f32, i64, vp, sz, vp]
@@ -153,6 +154,13 @@ def kun_validate_block_table(pool: int, host_table: torch.Tensor, host_ctx_len: 
     rows, mb = host_table.shape
     _check(lib().kun_validate_block_table(pool, _ptr(host_table), rows, mb, _ptr(host_ctx_len)),
            "kun_validate_block_table")
+
+
+def kun_slot_map(pool: int, seq_of_tok, pos_of_tok, T: int, block_table, max_blocks: int, kv_head: int,
+                 range_out, k_off_out, v_off_out, stream=None) -> None:
+    _check(lib().kun_slot_map(pool, _ptr(seq_of_tok), _ptr(pos_of_tok), int(T), _ptr(block_table),
+                              int(max_blocks), int(kv_head), _ptr(range_out), _ptr(k_off_out), _ptr(v_off_out),
+                              _stream(stream)), "kun_slot_map")
 
 
 def kun_kv_append(pool: int, k_new, v_new, seq_of_tok, pos_of_tok, T: int, block_table,

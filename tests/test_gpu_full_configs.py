@@ -113,4 +113,50 @@ def test_config5_150GB_pool_sampled():
         e = float(np.abs(got[q0:q0 + c][rws] - ref).max())
         print(f"cfg5 chunk {i} (p={p}) max err {e:.3e}")
         assert e <= TOL
+    # device-side resolution of 20000 sampled tokens: offsets beyond 4 GiB inside 30 GB ranges
+    seqs = rng.integers(0, len(w.seq_lens), size=20000)
+    poss = (rng.random(20000) * w.seq_lens[seqs]).astype(np.int64)
+    check_slot_map(dw, seqs, poss, kv_head=7)
+    dw.close()
+
+
+def check_slot_map(dw, seqs, poss, kv_head):
+    """kun_slot_map against the oracle's address arithmetic, bit-exact."""
+    w, sh = dw.w, dw.w.shape
+    table = w.table_array(range(len(w.seq_lens)))
+    T = len(seqs)
+    dev = dw.dev
+    r_out = torch.empty(T, dtype=torch.int32, device=dev)
+    k_out = torch.empty(T, dtype=torch.int64, device=dev)
+    v_out = torch.empty(T, dtype=torch.int64, device=dev)
+    kun.kun_slot_map(dw.pool, torch.from_numpy(np.asarray(seqs, dtype=np.int32)).to(dev),
+                     torch.from_numpy(np.asarray(poss, dtype=np.int32)).to(dev), T, torch.from_numpy(table).to(dev),
+                     table.shape[1], kv_head, r_out, k_out, v_out)
+    torch.cuda.synchronize()
+    geom = O.OraclePool([np.zeros(0, dtype=np.uint16)] * len(w.range_blocks), sh.Hkv, sh.d, sh.B, sh.dtype)
+    exp_r, exp_k, exp_v = [], [], []
+    for s_, t in zip(seqs, poss):
+        blk, slot = O.token_slot(table[int(s_)], int(t), sh.B)
+        r, local = O.resolve_block(w.range_blocks, blk)
+        exp_r.append(r)
+        exp_k.append(O.k_elem_offset(geom, local, kv_head, slot) * sh.elt)
+        exp_v.append(O.v_elem_offset(geom, local, kv_head, slot, 0) * sh.elt)
+    assert np.array_equal(r_out.cpu().numpy(), np.asarray(exp_r, dtype=np.int32))
+    assert np.array_equal(k_out.cpu().numpy(), np.asarray(exp_k, dtype=np.int64))
+    assert np.array_equal(v_out.cpu().numpy(), np.asarray(exp_v, dtype=np.int64))
+    return max(exp_k)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+def test_slot_map_matches_oracle_for_every_token(dtype, d):
+    sh = synth.LayerShape(Hq=8, Hkv=4, d=d, B=16, dtype=dtype)
+    w = synth.custom_workload("slots", sh, [37, 1, 16, 250, 1000], chunks=[(20, 70)], extra_blocks=5,
+                              range_fracs=(0.3, 0.3, 0.4))
+    dw = DeviceWorkload(w, fill=False, poison=False)
+    seqs, poss = [], []
+    for s_, L in enumerate(w.seq_lens):
+        seqs += [s_] * int(L)
+        poss += list(range(int(L)))
+    for h in (0, 3):
+        check_slot_map(dw, seqs, poss, kv_head=h)
     dw.close()

@@ -12,7 +12,9 @@
 //      a reference maximum that is checked through the row sums, 16 MFMAs
 //      for O^T += V^T P^T, operands read from a 4-stage LDS ring, one barrier per tile, four
 //      direct global->LDS loads per lane and tile; every wave does the same work, nothing is
-//      masked, the source stays in L2.  Constant and random operands.
+//      masked, the source stays in L2.  Constant and random operands.  Every wave reads the whole
+//      K and V^T tile from LDS (1 KiB per MFMA): at 4 MFMAs per 32 clocks and CU that is the LDS's
+//      128 B/clock, so a last variant drops half of the fragment reads to show that bound.
 //
 // Build: python -m paper_2412_18169_amd.build   (writes paper_2412_18169_amd/kun_ceilings)
 // Run:   ./paper_2412_18169_amd/kun_ceilings [hbm|mfma|tile|all]
@@ -153,8 +155,10 @@ static void run_mfma(float* out, uint4* src) {
 }
 
 // ---------------------------------------------------------------- 3. attention tile loop
-// STAGE 0: operands from LDS only; 1: + one barrier per tile; 2: + the four global->LDS loads
-template <int STAGE>
+// STAGE 0: operands from LDS only; 1: + one barrier per tile; 2: + the four global->LDS loads.
+// HALF: every second K and V^T fragment is a copy of the one before instead of an LDS read (wrong
+// results, same instruction mix otherwise): shows how much of the loop's time is LDS read bandwidth.
+template <int STAGE, bool HALF>
 __global__ __launch_bounds__(512) void tile_loop(float* out, const uint4* gsrc, int iters, float sl2) {
     __shared__ __attribute__((aligned(16))) unsigned char ring[4][32768];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, jh = lane >> 5;
@@ -202,7 +206,8 @@ __global__ __launch_bounds__(512) void tile_loop(float* out, const uint4* gsrc, 
         for (int ks = 0; ks < 8; ++ks) {
             const unsigned off = ((2 * ks + jh) ^ krow_in) * 16;
             ka[ks].u = *(const uint4*)(kbase + off);
-            kb[ks].u = *(const uint4*)(kbase + 8192 + off);
+            if (HALF) kb[ks].u = ka[ks].u;
+            else kb[ks].u = *(const uint4*)(kbase + 8192 + off);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -215,7 +220,10 @@ __global__ __launch_bounds__(512) void tile_loop(float* out, const uint4* gsrc, 
 #pragma unroll
         for (int h = 0; h < 4; ++h)
 #pragma unroll
-            for (int d = 0; d < 4; ++d) vf[4 * h + d].u = *(const uint4*)(vbase + h * 4096 + d * 1024);
+            for (int d = 0; d < 4; ++d) {
+                if (HALF && h >= 2) vf[4 * h + d].u = vf[4 * (h - 2) + d].u;
+                else vf[4 * h + d].u = *(const uint4*)(vbase + h * 4096 + d * 1024);
+            }
         __builtin_amdgcn_sched_barrier(0);
         float ps0 = 0, ps1 = 0;
         union {
@@ -255,11 +263,13 @@ static void run_tile(float* out, uint4* src) {
     for (int random = 0; random < 2; ++random) {
         const std::vector<unsigned> h = operand_words(1024 * 8192 / 4, random);
         CK(hipMemcpy(src, h.data(), 1024 * 8192, hipMemcpyHostToDevice));
-        const float t0 = time_ms([&] { tile_loop<0><<<256, 512>>>(out, src, iters, 0.01f); }, 1);
-        const float t1 = time_ms([&] { tile_loop<1><<<256, 512>>>(out, src, iters, 0.01f); }, 1);
-        const float t2 = time_ms([&] { tile_loop<2><<<256, 512>>>(out, src, iters, 0.01f); }, 1);
-        std::printf("attention tile loop, %s operands: LDS operands %.0f | + barrier %.0f | + global->LDS loads %.0f TFLOP/s\n",
-                    random ? "random  " : "constant", flops / t0 / 1e9, flops / t1 / 1e9, flops / t2 / 1e9);
+        const float t0 = time_ms([&] { tile_loop<0, false><<<256, 512>>>(out, src, iters, 0.01f); }, 1);
+        const float t1 = time_ms([&] { tile_loop<1, false><<<256, 512>>>(out, src, iters, 0.01f); }, 1);
+        const float t2 = time_ms([&] { tile_loop<2, false><<<256, 512>>>(out, src, iters, 0.01f); }, 1);
+        const float t3 = time_ms([&] { tile_loop<2, true><<<256, 512>>>(out, src, iters, 0.01f); }, 1);
+        std::printf("attention tile loop, %s operands: LDS operands %.0f | + barrier %.0f | + global->LDS loads %.0f TFLOP/s"
+                    " | the same with half of the LDS fragment reads %.0f\n",
+                    random ? "random  " : "constant", flops / t0 / 1e9, flops / t1 / 1e9, flops / t2 / 1e9, flops / t3 / 1e9);
     }
 }
 

@@ -6,8 +6,8 @@
 //
 // Work item = (chunk, tile of query positions, kv head).  The G query heads that share the kv head
 // are stacked into the row dimension (row = position * G + head), so a K/V tile staged in LDS
-// serves all of them.  A workgroup has 4 waves; each wave owns 32 * NQ rows and walks the keys in
-// tiles of 64 (four KV blocks), flash-attention style:
+// serves all of them.  A workgroup has 8 waves (4 or 12 in the variants); each wave owns 32 (* NQ)
+// rows and walks the keys in tiles of 64 (four KV blocks), flash-attention style:
 //
 //   S^T[key][row]  = K[key][:] . Q[row][:]          A = K fragment from LDS, B = Q in registers
 //   online softmax over keys, per row: each lane column holds one row, so max/sum are in-lane
@@ -20,6 +20,7 @@
 // are 8 consecutive keys of one KV block, i.e. one 16-byte LDS read of V^T.
 #include <math.h>
 #include <stdlib.h>
+#include <string.h>
 
 #include "kun_internal.h"
 
@@ -755,20 +756,20 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// Tile shape: NW waves x 32 NQ rows.  Default 8 waves x 32 rows (256 rows per workgroup).
-struct TileShape { int nw, nq; bool pipe; };
+// Tile shape: NW waves x 32 NQ rows per workgroup; `ring` selects prefill_ring_kernel (the default:
+// 8 waves x 32 rows), otherwise the register-staged prefill_kernel runs.  KUN_PREFILL_SHAPE picks
+// another one for sweeps and cross-checks: "ring", "12x1" (ring kernel, 12 waves), "8x1", "4x2", "4x1".
+struct TileShape { int nw, nq; bool ring; };
 
 TileShape choose_shape() {
-    TileShape t{8, 1, true};
-    const char* e = getenv("KUN_PREFILL_SHAPE");      // "ring" (default), "8x1", "4x2", "4x1"
-    if (e && e[0] && e[1] == 'x' && e[2]) {
-        const int nw = e[0] - '0', nq = e[2] - '0';
-        if ((nw == 8 && nq == 1) || (nw == 4 && (nq == 1 || nq == 2))) t = TileShape{nw, nq, false};
+    const char* e = getenv("KUN_PREFILL_SHAPE");
+    if (e) {
+        if (!strcmp(e, "12x1")) return TileShape{12, 1, true};
+        if (!strcmp(e, "8x1")) return TileShape{8, 1, false};
+        if (!strcmp(e, "4x2")) return TileShape{4, 2, false};
+        if (!strcmp(e, "4x1")) return TileShape{4, 1, false};
     }
-    if (e && e[0] == '1' && e[1] == '2') t = TileShape{12, 1, true};   // "12x1": ring kernel with 12 waves
-    if (false) {
-    }
-    return t;
+    return TileShape{8, 1, true};
 }
 
 int rows_per_wg(TileShape t) { return t.nw * 32 * t.nq; }
@@ -780,7 +781,7 @@ bool prefill_shape_ok(const kun_kv_pool* p, int n_chunks, int Hq, int total_new)
 template <int G>
 void launch_prefill(const PrefillArgs& a, dim3 grid, TileShape t, hipStream_t st) {
     if (t.nw == 12) hipLaunchKernelGGL((prefill_ring_kernel<G, 12>), grid, dim3(768), 0, st, a);
-    else if (t.nw == 8 && t.pipe) hipLaunchKernelGGL((prefill_ring_kernel<G, 8>), grid, dim3(512), 0, st, a);
+    else if (t.nw == 8 && t.ring) hipLaunchKernelGGL((prefill_ring_kernel<G, 8>), grid, dim3(512), 0, st, a);
     else if (t.nw == 8) hipLaunchKernelGGL((prefill_kernel<G, 8, 1>), grid, dim3(512), 0, st, a);
     else if (t.nq == 2) hipLaunchKernelGGL((prefill_kernel<G, 4, 2>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((prefill_kernel<G, 4, 1>), grid, dim3(256), 0, st, a);

@@ -152,12 +152,43 @@ def main():
                           "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                           "new_tokens_per_s": round(dw.total_new / (t_pre * 1e-3), 1)}
 
+    if has_prefill and not args.pmc_calibration:
+        out["mixed"] = mixed_batch(dw, args.steps)
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"], out["max_abs_err_vs_oracle"] = cpu_baseline(dw, args.cpu_seconds)
         if has_prefill:
             out["prefill_max_abs_err_vs_oracle"] = prefill_check(dw)
     dw.close()
     print(json.dumps(out), flush=True)
+
+
+def mixed_batch(dw, steps, prefill_workgroups=256):
+    """Prefill (on `prefill_workgroups` workgroups that fetch their items) and decode enqueued side by
+    side on two streams, against the same two calls back to back on one stream."""
+    import torch
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def timed(f):
+        for _ in range(2):
+            f()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            f()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / steps
+
+    def back_to_back():
+        dw.prefill()
+        dw.decode()
+
+    t_seq = timed(back_to_back)
+    t_mix = timed(lambda: dw.mixed(s1, s2, prefill_workgroups))
+    return {"ms_back_to_back": round(t_seq, 4), "ms_two_streams": round(t_mix, 4),
+            "prefill_workgroups": prefill_workgroups}
 
 
 def cpu_baseline(dw, target_s):

@@ -167,6 +167,17 @@ KUN_API int kun_paged_prefill_chunk(kun_kv_pool* pool, const void* q, void* out,
                             int n_chunks, int num_q_heads, int total_new_tokens, float scale,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* Mixed batches (Section 2.1: prefill is compute-bound, decode memory-bound, and serving systems
+ * batch the two): the same operation, results and workspace as kun_paged_prefill_chunk, but run by
+ * at most max_workgroups workgroups (> 0; rounded down to a multiple of 8, at least 8) that fetch
+ * the work items themselves.  One such workgroup fills a compute unit, so enqueuing this call on
+ * one stream and kun_paged_decode on another leaves the other compute units to the decode kernel
+ * and the two overlap instead of running back to back.  The two calls need separate workspaces. */
+KUN_API int kun_paged_prefill_chunk_on(kun_kv_pool* pool, const void* q, void* out, const int32_t* q_start,
+                               const int32_t* prior_len, const int32_t* block_table, int max_blocks,
+                               int n_chunks, int num_q_heads, int total_new_tokens, float scale,
+                               int max_workgroups, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -52,6 +52,7 @@ struct PrefillArgs {
     const int32_t* prior;
     const int32_t* table;
     int32_t* n_items;     // workspace
+    int32_t* next_item;   // workspace: 8 counters (one per XCD) for the workgroups that fetch their work
     int2* items;          // workspace: (chunk, position tile)
     int max_blocks;
     int n_chunks, Hkv, Hq;
@@ -91,6 +92,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
                                                                   const int32_t* __restrict__ prior, int n_chunks,
                                                                   int pos_per_tile, int max_items,
                                                                   int32_t* __restrict__ n_items,
+                                                                  int32_t* __restrict__ next_item,
                                                                   int2* __restrict__ items) {
     __shared__ int base_s;
     __shared__ int cnt[kPlanThreads];
@@ -99,6 +101,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
     __shared__ int hist[kPlanBuckets];
     const int tid = threadIdx.x;
     if (tid == 0) base_s = 0;
+    if (tid < 8) next_item[tid] = 0;
     __syncthreads();
     for (int c0 = 0; c0 < n_chunks; c0 += kPlanThreads) {
         const int ch = c0 + tid;
@@ -421,7 +424,7 @@ typedef __attribute__((address_space(3))) void* kun_lptr;
 // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt = bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 #define KUN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
-template <int G, int NW>
+template <int G, int NW, bool PERSIST>
 __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs a) {
     constexpr int NSTAGERS = 8;                        // waves that issue the tile loads (4 loads per lane and tile)
     constexpr int NT = 64 * NSTAGERS, LOADS = 2;
@@ -433,7 +436,20 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     __shared__ __attribute__((aligned(16))) unsigned char ring[NSTAGE][2 * kBlocksPerTile * 4096];
     constexpr int V_OFF = kBlocksPerTile * 4096;       // V^T pages follow the K pages inside a stage
 
-    const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
+    // Work index wi = item * Hkv + kvh.  Plain launch: one workgroup per index.  PERSIST: a fixed
+    // number of workgroups (a multiple of 8) fetch indices of their own residue class mod 8 -- the XCD
+    // the plain launch would have put them on, so K/V of a (chunk, kv head) stays in one L2 -- in
+    // increasing order (longest items first) until the list is exhausted; every workgroup then exits.
+    __shared__ int s_next;
+    int wi = blockIdx.x;
+    for (;;) {
+    if (PERSIST) {
+        __syncthreads();                               // everybody has left the previous item's ring
+        if (threadIdx.x == 0) s_next = atomicAdd(&a.next_item[blockIdx.x & 7], 1) * 8 + (blockIdx.x & 7);
+        __syncthreads();
+        wi = s_next;
+    }
+    const int item = wi / a.Hkv, kvh = wi % a.Hkv;
     if (item >= *a.n_items) return;
     const int2 it2 = a.items[item];
     const int chunk = it2.x, qt = it2.y;
@@ -751,25 +767,39 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
                 *(uint2*)(orow + dim * 2) = w.u;
             }
     }
+    if (!PERSIST) return;
+    }
 }
 
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// Tile shape: NW waves x 32 NQ rows per workgroup; `ring` selects prefill_ring_kernel (the default:
-// 8 waves x 32 rows), otherwise the register-staged prefill_kernel runs.  KUN_PREFILL_SHAPE picks
-// another one for sweeps and cross-checks: "ring", "12x1" (ring kernel, 12 waves), "8x1", "4x2", "4x1".
-struct TileShape { int nw, nq; bool ring; };
+// Tile shape: NW waves x 32 NQ rows per workgroup; `ring` selects prefill_ring_kernel, otherwise the
+// register-staged prefill_kernel runs; `persistent`: a fixed number of workgroups fetch the work
+// items (ring kernel, 8 waves) instead of one workgroup per item.  Default: ring kernel, 8 waves, one
+// workgroup per item (measured equal to one fetching workgroup per compute unit).
+// KUN_PREFILL_SHAPE picks another one for sweeps and cross-checks: "persistent" (one fetching
+// workgroup per compute unit), "12x1" (ring kernel, 12 waves), "8x1", "4x2", "4x1".
+struct TileShape { int nw, nq; bool ring, persistent; };
 
 TileShape choose_shape() {
     const char* e = getenv("KUN_PREFILL_SHAPE");
     if (e) {
-        if (!strcmp(e, "12x1")) return TileShape{12, 1, true};
-        if (!strcmp(e, "8x1")) return TileShape{8, 1, false};
-        if (!strcmp(e, "4x2")) return TileShape{4, 2, false};
-        if (!strcmp(e, "4x1")) return TileShape{4, 1, false};
+        if (!strcmp(e, "persistent")) return TileShape{8, 1, true, true};
+        if (!strcmp(e, "12x1")) return TileShape{12, 1, true, false};
+        if (!strcmp(e, "8x1")) return TileShape{8, 1, false, false};
+        if (!strcmp(e, "4x2")) return TileShape{4, 2, false, false};
+        if (!strcmp(e, "4x1")) return TileShape{4, 1, false, false};
     }
-    return TileShape{8, 1, true};
+    return TileShape{8, 1, true, false};
+}
+
+// compute units of the current device (one persistent workgroup each)
+int device_compute_units() {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+    return n;
 }
 
 int rows_per_wg(TileShape t) { return t.nw * 32 * t.nq; }
@@ -780,8 +810,9 @@ bool prefill_shape_ok(const kun_kv_pool* p, int n_chunks, int Hq, int total_new)
 
 template <int G>
 void launch_prefill(const PrefillArgs& a, dim3 grid, TileShape t, hipStream_t st) {
-    if (t.nw == 12) hipLaunchKernelGGL((prefill_ring_kernel<G, 12>), grid, dim3(768), 0, st, a);
-    else if (t.nw == 8 && t.ring) hipLaunchKernelGGL((prefill_ring_kernel<G, 8>), grid, dim3(512), 0, st, a);
+    if (t.persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, true>), grid, dim3(512), 0, st, a);
+    else if (t.nw == 12) hipLaunchKernelGGL((prefill_ring_kernel<G, 12, false>), grid, dim3(768), 0, st, a);
+    else if (t.nw == 8 && t.ring) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, false>), grid, dim3(512), 0, st, a);
     else if (t.nw == 8) hipLaunchKernelGGL((prefill_kernel<G, 8, 1>), grid, dim3(512), 0, st, a);
     else if (t.nq == 2) hipLaunchKernelGGL((prefill_kernel<G, 4, 2>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((prefill_kernel<G, 4, 1>), grid, dim3(256), 0, st, a);
@@ -797,11 +828,14 @@ extern "C" size_t kun_prefill_workspace_bytes(const kun_kv_pool* p, int n_chunks
     return 256 + align256(sizeof(int2) * max_items);
 }
 
-extern "C" int kun_paged_prefill_chunk(kun_kv_pool* p, const void* q, void* out, const int32_t* q_start,
-                                       const int32_t* prior_len, const int32_t* block_table, int max_blocks,
-                                       int n_chunks, int Hq, int total_new_tokens, float scale,
-                                       void* workspace, size_t workspace_bytes, void* stream) {
-    if (!prefill_shape_ok(p, n_chunks, Hq, total_new_tokens)) return KUN_ERR_INVALID_ARG;
+namespace {
+
+// max_workgroups == 0: the default shape (or what KUN_PREFILL_SHAPE asks for); otherwise that many
+// workgroups (rounded down to a multiple of 8, at least 8) of the ring kernel fetch the items.
+int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_start, const int32_t* prior_len,
+                    const int32_t* block_table, int max_blocks, int n_chunks, int Hq, int total_new_tokens,
+                    float scale, int max_workgroups, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!prefill_shape_ok(p, n_chunks, Hq, total_new_tokens) || max_workgroups < 0) return KUN_ERR_INVALID_ARG;
     if (n_chunks == 0 || total_new_tokens == 0) return KUN_OK;
     if (!q || !out || !q_start || !prior_len || !block_table || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
     if (p->dtype != KUN_BF16 || p->d != 128 || p->B != 16) return KUN_ERR_UNSUPPORTED;
@@ -810,7 +844,9 @@ extern "C" int kun_paged_prefill_chunk(kun_kv_pool* p, const void* q, void* out,
     const size_t need = kun_prefill_workspace_bytes(p, n_chunks, Hq, total_new_tokens);
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < need) return KUN_ERR_WORKSPACE;
 
-    const TileShape shape = choose_shape();
+    const TileShape shape = max_workgroups > 0 ? TileShape{8, 1, true, true} : choose_shape();
+    const bool persistent = shape.persistent;
+    if (persistent && max_workgroups == 0) max_workgroups = device_compute_units();
     const int pos_per_tile = rows_per_wg(shape) / G;
     PrefillArgs a;
     a.rt = p->ranges;
@@ -820,6 +856,7 @@ extern "C" int kun_paged_prefill_chunk(kun_kv_pool* p, const void* q, void* out,
     a.prior = prior_len;
     a.table = block_table;
     a.n_items = (int32_t*)workspace;
+    a.next_item = (int32_t*)workspace + 16;
     a.items = (int2*)((char*)workspace + 256);
     a.max_blocks = max_blocks;
     a.n_chunks = n_chunks;
@@ -832,9 +869,15 @@ extern "C" int kun_paged_prefill_chunk(kun_kv_pool* p, const void* q, void* out,
     hipStream_t st = (hipStream_t)stream;
 
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, q_start, prior_len, n_chunks,
-                       pos_per_tile, a.max_items, a.n_items, a.items);
+                       pos_per_tile, a.max_items, a.n_items, a.next_item, a.items);
     KUN_HIP_CHECK_LAUNCH();
-    const dim3 grid((unsigned)((size_t)a.max_items * p->Hkv));
+    size_t wgs = (size_t)a.max_items * p->Hkv;
+    if (persistent) {
+        const size_t lim = max_workgroups < 8 ? 8 : (size_t)(max_workgroups & ~7);
+        if (wgs > lim) wgs = lim;
+        wgs = (wgs + 7) & ~(size_t)7;                  // every residue class mod 8 needs a workgroup
+    }
+    const dim3 grid((unsigned)wgs);
     switch (G) {
         case 1: launch_prefill<1>(a, grid, shape, st); break;
         case 2: launch_prefill<2>(a, grid, shape, st); break;
@@ -843,4 +886,24 @@ extern "C" int kun_paged_prefill_chunk(kun_kv_pool* p, const void* q, void* out,
     }
     KUN_HIP_CHECK_LAUNCH();
     return KUN_OK;
+}
+
+}  // namespace
+
+extern "C" int kun_paged_prefill_chunk(kun_kv_pool* p, const void* q, void* out, const int32_t* q_start,
+                                       const int32_t* prior_len, const int32_t* block_table, int max_blocks,
+                                       int n_chunks, int Hq, int total_new_tokens, float scale,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+    return prefill_enqueue(p, q, out, q_start, prior_len, block_table, max_blocks, n_chunks, Hq, total_new_tokens,
+                           scale, 0, workspace, workspace_bytes, stream);
+}
+
+extern "C" int kun_paged_prefill_chunk_on(kun_kv_pool* p, const void* q, void* out, const int32_t* q_start,
+                                          const int32_t* prior_len, const int32_t* block_table, int max_blocks,
+                                          int n_chunks, int Hq, int total_new_tokens, float scale,
+                                          int max_workgroups, void* workspace, size_t workspace_bytes,
+                                          void* stream) {
+    if (max_workgroups <= 0) return KUN_ERR_INVALID_ARG;
+    return prefill_enqueue(p, q, out, q_start, prior_len, block_table, max_blocks, n_chunks, Hq, total_new_tokens,
+                           scale, max_workgroups, workspace, workspace_bytes, stream);
 }

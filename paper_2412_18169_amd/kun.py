@@ -25,7 +25,7 @@ SYMBOLS = [
     "kun_kv_pool_num_ranges", "kun_kv_pool_block_bytes", "kun_kv_pool_resolve",
     "kun_kv_pool_destroy", "kun_validate_block_table", "kun_slot_map", "kun_kv_append",
     "kun_decode_workspace_bytes", "kun_paged_decode", "kun_prefill_workspace_bytes",
-    "kun_paged_prefill_chunk",
+    "kun_paged_prefill_chunk", "kun_paged_prefill_chunk_on",
 ]
 
 
@@ -67,6 +67,7 @@ def lib() -> ctypes.CDLL:
     L.kun_prefill_workspace_bytes.restype = sz
     L.kun_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32]
     L.kun_paged_prefill_chunk.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]
+    L.kun_paged_prefill_chunk_on.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, sz, vp]
     for name in SYMBOLS:
         if name not in ("kun_status_string", "kun_decode_workspace_bytes", "kun_prefill_workspace_bytes"):
             getattr(L, name).restype = i32
@@ -195,3 +196,14 @@ def kun_paged_prefill_chunk(pool: int, q, out, q_start, prior_len, block_table, 
                                          int(num_q_heads), int(total_new_tokens), float(scale),
                                          _ptr(workspace), int(workspace_bytes), _stream(stream)),
            "kun_paged_prefill_chunk")
+
+
+def kun_paged_prefill_chunk_on(pool: int, q, out, q_start, prior_len, block_table, max_blocks: int,
+                               n_chunks: int, num_q_heads: int, total_new_tokens: int, scale: float,
+                               max_workgroups: int, workspace, workspace_bytes: int, stream=None) -> None:
+    _check(lib().kun_paged_prefill_chunk_on(pool, _ptr(q), _ptr(out), _ptr(q_start), _ptr(prior_len),
+                                            _ptr(block_table), int(max_blocks), int(n_chunks),
+                                            int(num_q_heads), int(total_new_tokens), float(scale),
+                                            int(max_workgroups), _ptr(workspace), int(workspace_bytes),
+                                            _stream(stream)),
+           "kun_paged_prefill_chunk_on")

@@ -78,16 +78,38 @@ class DeviceWorkload:
         return self.out_dec
 
     # ---- prefill -----------------------------------------------------------------------------
-    def prefill(self, stream=None) -> torch.Tensor:
+    def prefill(self, stream=None, max_workgroups: int = 0) -> torch.Tensor:
+        """All prefill chunks; max_workgroups > 0 runs them on that many workgroups (mixed batches)."""
         sh = self.w.shape
         need = kun.kun_prefill_workspace_bytes(self.pool, self.n_chunks, sh.Hq, self.total_new)
         if self._ws_pre is None or self._ws_pre.numel() < need:
             self._ws_pre = torch.empty(max(need, 256), dtype=torch.uint8, device=self.dev)
-        kun.kun_paged_prefill_chunk(self.pool, self.q_pre, self.out_pre, self.q_start, self.prior,
-                                    self.pre_table, self.pre_table.shape[1], self.n_chunks, sh.Hq,
-                                    self.total_new, sh.scale, self._ws_pre, self._ws_pre.numel(),
-                                    stream)
+        if max_workgroups > 0:
+            kun.kun_paged_prefill_chunk_on(self.pool, self.q_pre, self.out_pre, self.q_start, self.prior,
+                                           self.pre_table, self.pre_table.shape[1], self.n_chunks, sh.Hq,
+                                           self.total_new, sh.scale, max_workgroups, self._ws_pre,
+                                           self._ws_pre.numel(), stream)
+        else:
+            kun.kun_paged_prefill_chunk(self.pool, self.q_pre, self.out_pre, self.q_start, self.prior,
+                                        self.pre_table, self.pre_table.shape[1], self.n_chunks, sh.Hq,
+                                        self.total_new, sh.scale, self._ws_pre, self._ws_pre.numel(),
+                                        stream)
         return self.out_pre
+
+    def mixed(self, prefill_stream, decode_stream, prefill_workgroups: int) -> None:
+        """Prefill on `prefill_workgroups` compute units and the decode step side by side: both start
+        after the work already on the current stream, which in turn waits for both."""
+        cur = torch.cuda.current_stream()
+        start = torch.cuda.Event()
+        start.record(cur)
+        prefill_stream.wait_event(start)
+        decode_stream.wait_event(start)
+        self.prefill(stream=prefill_stream, max_workgroups=prefill_workgroups)
+        self.decode(stream=decode_stream)
+        for st in (prefill_stream, decode_stream):
+            done = torch.cuda.Event()
+            done.record(st)
+            cur.wait_event(done)
 
     def close(self):
         if self.pool is not None:

@@ -50,10 +50,16 @@ def check_prefill(dw, rows_per_chunk=None, seed=0, only=None):
     return worst
 
 
-@pytest.mark.parametrize("shape", ["ring", "12x1", "8x1", "4x2", "4x1"])
+def set_shape(shape):
+    """"ring": the library's own choice (environment left alone); else the named variant."""
+    if shape != "ring":
+        os.environ["KUN_PREFILL_SHAPE"] = shape
+
+
+@pytest.mark.parametrize("shape", ["ring", "persistent", "12x1", "8x1", "4x2", "4x1"])
 @pytest.mark.parametrize("G", [4, 8, 1, 2])
 def test_ragged_chunks(G, shape):
-    os.environ["KUN_PREFILL_SHAPE"] = shape
+    set_shape(shape)
     sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=128, B=16, dtype="bf16")
     # priors / sizes around block, sub-tile (32), tile (64) and workgroup-tile edges; p = 0; c = 1
     chunks = [(0, 1), (0, 17), (5, 1), (15, 16), (16, 33), (31, 64), (63, 65), (64, 129), (100, 200), (0, 300),
@@ -65,12 +71,12 @@ def test_ragged_chunks(G, shape):
     dw.close()
 
 
-@pytest.mark.parametrize("shape", ["ring", "12x1", "8x1"])
+@pytest.mark.parametrize("shape", ["ring", "persistent", "12x1", "8x1"])
 @pytest.mark.parametrize("profile", ["steps", "jump", "decay"])
 def test_scores_that_outgrow_the_running_maximum(profile, shape):
     # Key magnitude changes along the context, so the rows' reference maximum has to move on tiles
     # far from the first one ("jump": by more than exp2 can hold in fp32), or never again ("decay").
-    os.environ["KUN_PREFILL_SHAPE"] = shape
+    set_shape(shape)
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     chunks = [(0, 700), (512, 300), (900, 64)]
     w = synth.custom_workload("grow", sh, [], chunks=chunks, extra_blocks=0)
@@ -92,11 +98,11 @@ def test_scores_that_outgrow_the_running_maximum(profile, shape):
     dw.close()
 
 
-@pytest.mark.parametrize("shape", ["ring", "8x1"])
+@pytest.mark.parametrize("shape", ["ring", "persistent", "8x1"])
 def test_more_work_items_than_the_plan_kernel_sorts(shape):
     # 5000 chunks (the plan kernel walks them 1024 at a time and orders only the first 4096 items),
     # most of them a few tokens, some empty, a few spanning several position tiles
-    os.environ["KUN_PREFILL_SHAPE"] = shape
+    set_shape(shape)
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     rng = np.random.default_rng(33)
     c = rng.integers(1, 6, size=5000)
@@ -112,6 +118,44 @@ def test_more_work_items_than_the_plan_kernel_sorts(shape):
     print("max err", err)
     # rows of empty chunks do not exist and no other row may be left unwritten: all of `out` is finite
     assert torch.isfinite(dw.out_pre.float()).all()
+    dw.close()
+
+
+@pytest.mark.parametrize("limit", [1, 8, 20, 96, 100000])
+def test_prefill_on_a_limited_number_of_workgroups(limit):
+    # any number of fetching workgroups gives the bits of the plain launch (items are independent)
+    sh = synth.LayerShape(Hq=16, Hkv=4, d=128, B=16, dtype="bf16")
+    chunks = [(0, 300), (700, 257), (100, 200), (64, 129), (5, 1), (333, 77), (0, 17), (1000, 31)]
+    w = synth.custom_workload("lim", sh, [3], chunks=chunks, extra_blocks=5, range_fracs=(0.4, 0.6))
+    dw = DeviceWorkload(w)
+    ref = dw.prefill().clone()
+    dw.out_pre.fill_(float("nan"))
+    got = dw.prefill(max_workgroups=limit)
+    torch.cuda.synchronize()
+    assert torch.equal(got.view(torch.int16), ref.view(torch.int16))
+    check_prefill(dw)
+    with pytest.raises(kun.KunError):
+        kun.kun_paged_prefill_chunk_on(dw.pool, dw.q_pre, dw.out_pre, dw.q_start, dw.prior, dw.pre_table,
+                                       dw.pre_table.shape[1], dw.n_chunks, sh.Hq, dw.total_new, sh.scale, 0,
+                                       dw._ws_pre, dw._ws_pre.numel())
+    dw.close()
+
+
+def test_mixed_batch_on_two_streams_equals_the_calls_in_sequence():
+    w = synth.custom_workload("mix", synth.SHAPE_8B, [900, 3000, 17, 1500, 64] * 8,
+                              chunks=[(0, 512), (1024, 512), (300, 100)], extra_blocks=4, range_fracs=(0.5, 0.5))
+    dw = DeviceWorkload(w)
+    ref_p = dw.prefill().clone()
+    ref_d = dw.decode().clone()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(3):
+        dw.out_pre.fill_(float("nan"))
+        dw.out_dec.fill_(float("nan"))
+        dw.mixed(s1, s2, prefill_workgroups=16)
+        torch.cuda.synchronize()
+        assert torch.equal(dw.out_pre.view(torch.int16), ref_p.view(torch.int16))
+        assert torch.equal(dw.out_dec.view(torch.int16), ref_d.view(torch.int16))
+    check_prefill(dw)
     dw.close()
 
 

@@ -86,6 +86,15 @@ KUN_API int kun_kv_pool_create(kun_kv_pool** out, void* base, size_t bytes, int 
 KUN_API int kun_kv_pool_extend(kun_kv_pool* pool, void* base, size_t bytes, int64_t* first_new_block,
                        int64_t* num_new_blocks);
 
+/* The LAST range of the pool now spans new_bytes from its unchanged base: it grew in place (memory
+ * was mapped behind it, see kun_vmm_region below) or lost its tail (restoration).  Blocks that stay
+ * keep their ids and addresses; new blocks continue the numbering; after a shrink the ids from
+ * *first_changed_block on no longer exist, and it is the caller's job that no table still names
+ * them and no enqueued work still reads them.  *first_changed_block: first id added or removed;
+ * *num_blocks_delta: blocks added (> 0) or removed (< 0).  Outputs optional. */
+KUN_API int kun_kv_pool_resize_tail(kun_kv_pool* pool, size_t new_bytes, int64_t* first_changed_block,
+                            int64_t* num_blocks_delta);
+
 KUN_API int kun_kv_pool_num_blocks(const kun_kv_pool* pool, int64_t* n);
 KUN_API int kun_kv_pool_num_ranges(const kun_kv_pool* pool, int* n);
 KUN_API int kun_kv_pool_block_bytes(const kun_kv_pool* pool, size_t* bytes);
@@ -177,6 +186,34 @@ KUN_API int kun_paged_prefill_chunk_on(kun_kv_pool* pool, const void* q, void* o
                                const int32_t* prior_len, const int32_t* block_table, int max_blocks,
                                int n_chunks, int num_q_heads, int total_new_tokens, float scale,
                                int max_workgroups, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- the KVCache region as ONE growing virtual range (Section 4.1) -------------------------- */
+
+/* Section 4.1 keeps attention kernels unchanged by reserving one virtual address range for the
+ * largest KVCache, mapping physical memory at its tail as the pool grows and remapping the
+ * physical memory of dropped parameters there without a copy; Section 4.4 moves it back when the
+ * parameters are restored.  A kun_vmm_region is such a range on the current device.  All calls are
+ * host calls that change address mappings: the caller synchronises first with any enqueued work
+ * that touches the bytes being unmapped.  Sizes passed to grow are multiples of the region's
+ * granularity; sizes passed to move_tail / shrink must add up to whole chunks at the tail (a chunk
+ * = the bytes of one grow call): KUN_ERR_MISALIGNED otherwise.  KUN_ERR_TOO_SMALL: reservation
+ * exhausted.  KUN_ERR_HIP: the driver refused (e.g. out of memory). */
+typedef struct kun_vmm_region kun_vmm_region;
+
+/* Reserve reserve_bytes (rounded up to the granularity) of virtual addresses; nothing is mapped. */
+KUN_API int kun_vmm_region_create(kun_vmm_region** out, size_t reserve_bytes);
+/* base: device address of the range; mapped_bytes: [base, base + mapped_bytes) is usable memory. */
+KUN_API int kun_vmm_region_info(const kun_vmm_region* region, void** base, size_t* mapped_bytes,
+                        size_t* reserved_bytes, size_t* granularity);
+/* Allocate `bytes` of device memory as one chunk and map it at the tail. */
+KUN_API int kun_vmm_region_grow(kun_vmm_region* region, size_t bytes);
+/* Unmap the last `bytes` of src and map the same physical chunks, in the same order, at the tail of
+ * dst: the contents move with them, no copy is made. */
+KUN_API int kun_vmm_region_move_tail(kun_vmm_region* src, kun_vmm_region* dst, size_t bytes);
+/* Unmap the last `bytes` and give the physical memory back to the driver. */
+KUN_API int kun_vmm_region_shrink(kun_vmm_region* region, size_t bytes);
+/* Unmaps and releases whatever is still mapped, then frees the reservation and the object. */
+KUN_API int kun_vmm_region_destroy(kun_vmm_region* region);
 
 #ifdef __cplusplus
 }

@@ -91,6 +91,26 @@ int kun_kv_pool_extend(kun_kv_pool* p, void* base, size_t bytes, int64_t* first_
     return KUN_OK;
 }
 
+int kun_kv_pool_resize_tail(kun_kv_pool* p, size_t new_bytes, int64_t* first_changed_block,
+                            int64_t* num_blocks_delta) {
+    if (!p) return KUN_ERR_INVALID_ARG;
+    const int r = p->ranges.n - 1;
+    const int64_t nb = (int64_t)(new_bytes / p->block_bytes);
+    if (nb < 1) return KUN_ERR_TOO_SMALL;
+    const int64_t first = p->ranges.first[r], old_nb = (int64_t)p->ranges.first[r + 1] - first;
+    if (first + nb > (int64_t)INT32_MAX - 1) return KUN_ERR_INVALID_ARG;
+    uintptr_t lo = (uintptr_t)p->ranges.base[r], hi = lo + new_bytes;
+    for (int i = 0; i < r; ++i) {
+        uintptr_t a = (uintptr_t)p->ranges.base[i], b = a + p->range_bytes[i];
+        if (lo < b && a < hi) return KUN_ERR_OVERLAP;
+    }
+    p->range_bytes[r] = new_bytes;
+    p->ranges.first[r + 1] = (int32_t)(first + nb);
+    if (first_changed_block) *first_changed_block = first + (nb < old_nb ? nb : old_nb);
+    if (num_blocks_delta) *num_blocks_delta = nb - old_nb;
+    return KUN_OK;
+}
+
 int kun_kv_pool_num_blocks(const kun_kv_pool* p, int64_t* n) {
     if (!p || !n) return KUN_ERR_INVALID_ARG;
     *n = p->ranges.first[p->ranges.n];

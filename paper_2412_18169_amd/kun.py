@@ -25,7 +25,9 @@ SYMBOLS = [
     "kun_kv_pool_num_ranges", "kun_kv_pool_block_bytes", "kun_kv_pool_resolve",
     "kun_kv_pool_destroy", "kun_validate_block_table", "kun_slot_map", "kun_kv_append",
     "kun_decode_workspace_bytes", "kun_paged_decode", "kun_prefill_workspace_bytes",
-    "kun_paged_prefill_chunk", "kun_paged_prefill_chunk_on",
+    "kun_paged_prefill_chunk", "kun_paged_prefill_chunk_on", "kun_kv_pool_resize_tail",
+    "kun_vmm_region_create", "kun_vmm_region_info", "kun_vmm_region_grow", "kun_vmm_region_move_tail",
+    "kun_vmm_region_shrink", "kun_vmm_region_destroy",
 ]
 
 
@@ -54,6 +56,13 @@ def lib() -> ctypes.CDLL:
     L.kun_kv_pool_create.argtypes = [P(vp), vp, sz, i32, i32, i32, i32]
     L.kun_kv_pool_extend.argtypes = [vp, vp, sz, P(i64), P(i64)]
     L.kun_kv_pool_num_blocks.argtypes = [vp, P(i64)]
+    L.kun_kv_pool_resize_tail.argtypes = [vp, sz, P(i64), P(i64)]
+    L.kun_vmm_region_create.argtypes = [P(vp), sz]
+    L.kun_vmm_region_info.argtypes = [vp, P(vp), P(sz), P(sz), P(sz)]
+    L.kun_vmm_region_grow.argtypes = [vp, sz]
+    L.kun_vmm_region_move_tail.argtypes = [vp, vp, sz]
+    L.kun_vmm_region_shrink.argtypes = [vp, sz]
+    L.kun_vmm_region_destroy.argtypes = [vp]
     L.kun_kv_pool_num_ranges.argtypes = [vp, P(i32)]
     L.kun_kv_pool_block_bytes.argtypes = [vp, P(sz)]
     L.kun_kv_pool_resolve.argtypes = [vp, i64, P(i32), P(sz), P(vp)]
@@ -116,6 +125,53 @@ def kun_kv_pool_extend(pool: int, base, nbytes: int):
     _check(lib().kun_kv_pool_extend(pool, _ptr(base), int(nbytes), ctypes.byref(first),
                                     ctypes.byref(n)), "kun_kv_pool_extend")
     return first.value, n.value
+
+
+def kun_kv_pool_resize_tail(pool: int, new_bytes: int):
+    """Returns (first_changed_block, num_blocks_delta)."""
+    first, delta = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().kun_kv_pool_resize_tail(pool, int(new_bytes), ctypes.byref(first), ctypes.byref(delta)),
+           "kun_kv_pool_resize_tail")
+    return first.value, delta.value
+
+
+def kun_vmm_region_create(reserve_bytes: int) -> int:
+    h = ctypes.c_void_p()
+    _check(lib().kun_vmm_region_create(ctypes.byref(h), int(reserve_bytes)), "kun_vmm_region_create")
+    return h.value
+
+
+def kun_vmm_region_info(region: int):
+    """Returns (base address, mapped bytes, reserved bytes, granularity)."""
+    base, mapped, reserved, gran = ctypes.c_void_p(), ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().kun_vmm_region_info(region, ctypes.byref(base), ctypes.byref(mapped), ctypes.byref(reserved),
+                                     ctypes.byref(gran)), "kun_vmm_region_info")
+    return base.value, mapped.value, reserved.value, gran.value
+
+
+def kun_vmm_region_grow(region: int, nbytes: int) -> None:
+    _check(lib().kun_vmm_region_grow(region, int(nbytes)), "kun_vmm_region_grow")
+
+
+def kun_vmm_region_move_tail(src: int, dst: int, nbytes: int) -> None:
+    _check(lib().kun_vmm_region_move_tail(src, dst, int(nbytes)), "kun_vmm_region_move_tail")
+
+
+def kun_vmm_region_shrink(region: int, nbytes: int) -> None:
+    _check(lib().kun_vmm_region_shrink(region, int(nbytes)), "kun_vmm_region_shrink")
+
+
+def kun_vmm_region_destroy(region: int) -> None:
+    _check(lib().kun_vmm_region_destroy(region), "kun_vmm_region_destroy")
+
+
+def device_bytes(address: int, nbytes: int) -> torch.Tensor:
+    """uint8 tensor over [address, address + nbytes) of device memory the caller keeps mapped (no copy,
+    no ownership)."""
+    class _Span:
+        __cuda_array_interface__ = {"shape": (int(nbytes),), "typestr": "|u1", "data": (int(address), False),
+                                    "version": 3}
+    return torch.as_tensor(_Span(), device="cuda")
 
 
 def kun_kv_pool_num_blocks(pool: int) -> int:

@@ -16,16 +16,22 @@ from . import kun, synth
 
 class DeviceWorkload:
     def __init__(self, w: synth.Workload, device="cuda:0", poison: bool = True,
-                 n_ranges_at_create: Optional[int] = None, fill: bool = True):
+                 n_ranges_at_create: Optional[int] = None, fill: bool = True,
+                 ranges: Optional[List[torch.Tensor]] = None, create_bytes: Optional[int] = None):
         """Allocates one buffer per pool range, creates the pool on range 0 and extends it with the
-        others (all of them unless n_ranges_at_create limits it; call extend_next() later)."""
+        others (all of them unless n_ranges_at_create limits it; call extend_next() later).
+        `ranges`: use these buffers (shaped like synth.alloc_ranges') instead of allocating;
+        `create_bytes`: create the pool on the first create_bytes of range 0 only (a range that grows
+        in place: kun_kv_pool_resize_tail)."""
         self.w = w
         self.dev = torch.device(device)
         sh = w.shape
-        self.ranges: List[torch.Tensor] = synth.alloc_ranges(w, self.dev, poison=poison)
+        self.ranges: List[torch.Tensor] = (ranges if ranges is not None
+                                           else synth.alloc_ranges(w, self.dev, poison=poison))
         dt = kun.KUN_F32 if sh.dtype == "f32" else kun.KUN_BF16
         r0 = self.ranges[0]
-        self.pool = kun.kun_kv_pool_create(r0, r0.numel() * r0.element_size(), dt, sh.Hkv, sh.d, sh.B)
+        r0_bytes = r0.numel() * r0.element_size() if create_bytes is None else int(create_bytes)
+        self.pool = kun.kun_kv_pool_create(r0, r0_bytes, dt, sh.Hkv, sh.d, sh.B)
         self.n_attached = 1
         want = len(self.ranges) if n_ranges_at_create is None else n_ranges_at_create
         while self.n_attached < want:

@@ -143,3 +143,41 @@ def test_workspace_size_is_monotone_in_the_bound():
         assert need >= prev and need % 256 == 0
         prev = need
     kun.kun_kv_pool_destroy(p)
+
+
+def test_resize_of_the_last_range_matches_oracle_bit_exact():
+    # the pool as ONE growing range, and as a first range plus a growing second one
+    for lead in ([], [BB * 4]):
+        sizes = lead + [BB * 3 + 17]
+        p = make_pool(sizes[0], BASE)
+        if lead:
+            kun.kun_kv_pool_extend(p, BASE + (1 << 32), sizes[1])
+        tail_base = BASE + ((1 << 32) if lead else 0)
+        n_lead = sum(O.usable_blocks(x, BB) for x in lead)
+        seen = {}
+        for new_bytes in [BB * 3 + 17, BB * 9, BB * 9 + BB - 1, BB * 70000, BB * 6 + 5, BB * 1, BB * 2]:
+            old = kun.kun_kv_pool_num_blocks(p) - n_lead
+            first, delta = kun.kun_kv_pool_resize_tail(p, new_bytes)
+            nb = O.usable_blocks(new_bytes, BB)
+            assert delta == nb - old and first == n_lead + min(nb, old)
+            rb = [O.usable_blocks(x, BB) for x in lead] + [nb]
+            assert kun.kun_kv_pool_num_blocks(p) == sum(rb) and kun.kun_kv_pool_num_ranges(p) == len(rb)
+            for blk in sorted(set([0, n_lead, sum(rb) - 1, n_lead + nb // 2, n_lead + nb - 1])):
+                r, off, addr = kun.kun_kv_pool_resolve(p, blk)
+                assert (r, off) == O.block_byte_offset(rb, blk, BB)
+                assert addr == (BASE if r == 0 and lead else tail_base) + off
+                assert seen.setdefault(blk, addr) == addr          # a block that exists keeps its address
+            with pytest.raises(kun.KunError) as e:
+                kun.kun_kv_pool_resolve(p, sum(rb))
+            assert e.value.status == -5
+        with pytest.raises(kun.KunError) as e:
+            kun.kun_kv_pool_resize_tail(p, BB - 1)
+        assert e.value.status == -3
+        kun.kun_kv_pool_destroy(p)
+    # growing the last range into an earlier one is refused
+    p = make_pool(BB * 4, BASE + BB * 100)
+    kun.kun_kv_pool_extend(p, BASE, BB * 10)
+    with pytest.raises(kun.KunError) as e:
+        kun.kun_kv_pool_resize_tail(p, BB * 101)
+    assert e.value.status == -9
+    kun.kun_kv_pool_destroy(p)

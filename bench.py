@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) to scale rocprofv3 --pmc counters")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--vmm", action="store_true",
+                    help="also time the decode step over the same pool built as ONE virtual range that grew "
+                         "chunk by chunk, and the mapping calls themselves")
     return ap.parse_args()
 
 
@@ -155,6 +158,9 @@ def main():
     if has_prefill and not args.pmc_calibration:
         out["mixed"] = mixed_batch(dw, args.steps)
 
+    if args.vmm:
+        out["vmm"] = vmm_report(dw, args.steps)
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"], out["max_abs_err_vs_oracle"] = cpu_baseline(dw, args.cpu_seconds)
         if has_prefill:
@@ -189,6 +195,84 @@ def mixed_batch(dw, steps, prefill_workgroups=256):
     t_mix = timed(lambda: dw.mixed(s1, s2, prefill_workgroups))
     return {"ms_back_to_back": round(t_seq, 4), "ms_two_streams": round(t_mix, 4),
             "prefill_workgroups": prefill_workgroups}
+
+
+def vmm_report(dw, steps):
+    """The workload's pool built twice with the same block ids and contents -- as the range table (one
+    buffer per range) and as ONE virtual range that grew range by range, each range a chunk of physical
+    memory that starts life in another region (as parameter memory would) and is moved to the tail:
+    decode time of both, bit-identity of the outputs, and the host time of the mapping calls.
+    Ranges are rounded up to 2 MiB (32 blocks) so that chunk and range boundaries coincide."""
+    import copy
+    import torch
+    from paper_2412_18169_amd import kun, synth
+    from paper_2412_18169_amd.runner import DeviceWorkload
+    sh = dw.w.shape
+    bb = sh.block_bytes
+    unit = (1 << 21) // bb
+    if sum(dw.w.range_blocks) * bb > 40 * 10**9:
+        return {"skipped": "two more copies of this pool do not fit next to it"}
+    w = copy.copy(dw.w)
+    w.range_blocks = [(nb + unit - 1) // unit * unit for nb in dw.w.range_blocks]
+    if getattr(dw.w, "phase_resident", None) is not None:
+        synth.assign_blocks_phased(w)
+    else:
+        synth.assign_blocks_scattered(w)
+    torch.cuda.synchronize()
+
+    def host_us(f):
+        t0 = time.perf_counter()
+        f()
+        return (time.perf_counter() - t0) * 1e6
+
+    def dec_ms(d):
+        for _ in range(3):
+            d.decode()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            d.decode()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / steps
+
+    d0 = DeviceWorkload(w)
+    t_table = dec_ms(d0)
+    ref = d0.decode().clone()
+    torch.cuda.synchronize()
+    sizes = [nb * bb for nb in w.range_blocks]
+    region = kun.kun_vmm_region_create(sum(sizes))
+    scratch = kun.kun_vmm_region_create(max(sizes))
+    base, _, _, gran = kun.kun_vmm_region_info(region)
+    calls = []
+    for sz in sizes:
+        t_create = host_us(lambda: kun.kun_vmm_region_grow(scratch, sz))
+        t_move = host_us(lambda: kun.kun_vmm_region_move_tail(scratch, region, sz))
+        calls.append({"MiB": sz >> 20, "create_and_map_us": round(t_create, 1), "move_tail_us": round(t_move, 1)})
+    full = kun.device_bytes(base, sum(sizes)).view(sh.torch_dtype).view(-1, sh.Hkv, 2, sh.B * sh.d)
+    o = 0
+    for r in d0.ranges:                               # same contents at the same block ids
+        full[o:o + r.shape[0]].copy_(r)
+        o += r.shape[0]
+    w1 = copy.copy(w)
+    w1.range_blocks = [sum(w.range_blocks)]
+    d1 = DeviceWorkload(w1, ranges=[full], create_bytes=sizes[0], fill=False)
+    have = sizes[0]
+    for sz in sizes[1:]:
+        have += sz
+        kun.kun_kv_pool_resize_tail(d1.pool, have)
+    t_one = dec_ms(d1)
+    same = bool(torch.equal(d1.decode(), ref))
+    torch.cuda.synchronize()
+    t_back = host_us(lambda: kun.kun_vmm_region_move_tail(region, scratch, sizes[-1]))
+    d0.close()
+    d1.close()
+    kun.kun_vmm_region_destroy(region)
+    kun.kun_vmm_region_destroy(scratch)
+    return {"decode_ms_range_table": round(t_table, 4), "decode_ms_one_virtual_range": round(t_one, 4),
+            "ranges": len(sizes), "bit_identical": same, "mapping_calls": calls,
+            "move_last_chunk_back_us": round(t_back, 1), "granularity": gran}
 
 
 def cpu_baseline(dw, target_s):

@@ -70,6 +70,11 @@ typedef enum {
 /* Human-readable name of a status code (static storage). */
 KUN_API const char* kun_status_string(int status);
 
+/* After a call on this host thread returned KUN_ERR_HIP: which HIP call failed and the driver's
+ * message for it ("" if none has failed yet).  The string is owned by the library and overwritten
+ * by the next failure on the same thread. */
+KUN_API const char* kun_last_hip_error(void);
+
 /* ---- pool growth (Section 4.1: the KVCache region is extended at its tail with the memory of
  *      dropped parameters; Section 5.6: two consecutive drops enlarge it twice) ---------------- */
 

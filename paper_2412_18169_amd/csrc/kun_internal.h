@@ -33,7 +33,14 @@ __device__ __forceinline__ char* kun_block_addr(const KunRanges& rt, int blk, si
     return rt.base[r] + (size_t)(blk - rt.first[r]) * block_bytes;
 }
 
-#define KUN_HIP_CHECK_LAUNCH()                      \
-    do {                                            \
-        if (hipGetLastError() != hipSuccess) return KUN_ERR_HIP; \
+// Remembers which HIP call failed and how, per host thread, for kun_last_hip_error().
+void kun_note_hip_error(const char* call, hipError_t e);
+
+#define KUN_HIP_CHECK_LAUNCH()                               \
+    do {                                                     \
+        const hipError_t e_ = hipGetLastError();             \
+        if (e_ != hipSuccess) {                              \
+            kun_note_hip_error("kernel launch", e_);         \
+            return KUN_ERR_HIP;                              \
+        }                                                    \
     } while (0)

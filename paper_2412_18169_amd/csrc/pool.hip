@@ -7,9 +7,21 @@
 #include <limits.h>
 #include <new>
 
+#include <stdio.h>
+
 #include "kun_internal.h"
 
+namespace {
+thread_local char g_hip_error[160] = "";
+}
+
+void kun_note_hip_error(const char* call, hipError_t e) {
+    snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s (%d)", call, hipGetErrorString(e), (int)e);
+}
+
 extern "C" {
+
+const char* kun_last_hip_error(void) { return g_hip_error; }
 
 const char* kun_status_string(int st) {
     switch (st) {

@@ -23,6 +23,15 @@ struct kun_vmm_region {
 
 namespace {
 
+constexpr size_t kMinGranularity = (size_t)2 << 20;
+
+// true if the call failed (and notes it for kun_last_hip_error)
+bool failed(const char* call, hipError_t e) {
+    if (e == hipSuccess) return false;
+    kun_note_hip_error(call, e);
+    return true;
+}
+
 hipMemAllocationProp device_prop(int device) {
     hipMemAllocationProp prop = {};
     prop.type = hipMemAllocationTypePinned;
@@ -34,12 +43,12 @@ hipMemAllocationProp device_prop(int device) {
 int map_at_tail(kun_vmm_region* r, hipMemGenericAllocationHandle_t h, size_t bytes) {
     if (r->mapped + bytes > r->reserved) return KUN_ERR_TOO_SMALL;
     char* at = r->base + r->mapped;
-    if (hipMemMap(at, bytes, 0, h, 0) != hipSuccess) return KUN_ERR_HIP;
+    if (failed("hipMemMap", hipMemMap(at, bytes, 0, h, 0))) return KUN_ERR_HIP;
     hipMemAccessDesc acc = {};
     acc.location.type = hipMemLocationTypeDevice;
     acc.location.id = r->device;
     acc.flags = hipMemAccessFlagsProtReadWrite;
-    if (hipMemSetAccess(at, bytes, &acc, 1) != hipSuccess) {
+    if (failed("hipMemSetAccess", hipMemSetAccess(at, bytes, &acc, 1))) {
         (void)hipMemUnmap(at, bytes);
         return KUN_ERR_HIP;
     }
@@ -65,16 +74,23 @@ int kun_vmm_region_create(kun_vmm_region** out, size_t reserve_bytes) {
     if (reserve_bytes == 0) return KUN_ERR_INVALID_ARG;
     kun_vmm_region* r = new (std::nothrow) kun_vmm_region();
     if (!r) return KUN_ERR_INVALID_ARG;
-    if (hipGetDevice(&r->device) != hipSuccess) { delete r; return KUN_ERR_HIP; }
+    if (failed("hipGetDevice", hipGetDevice(&r->device))) { delete r; return KUN_ERR_HIP; }
     const hipMemAllocationProp prop = device_prop(r->device);
-    if (hipMemGetAllocationGranularity(&r->gran, &prop, hipMemAllocationGranularityRecommended) != hipSuccess ||
+    if (failed("hipMemGetAllocationGranularity",
+               hipMemGetAllocationGranularity(&r->gran, &prop, hipMemAllocationGranularityRecommended)) ||
         r->gran == 0) {
         delete r;
         return KUN_ERR_HIP;
     }
+    // The driver reports 4 KiB here, but access to large chunks can only be set on 2 MiB-aligned
+    // spans: the region works in units of at least 2 MiB, base included.
+    if (r->gran < kMinGranularity) r->gran = kMinGranularity;
     r->reserved = (reserve_bytes + r->gran - 1) / r->gran * r->gran;
     void* va = nullptr;
-    if (hipMemAddressReserve(&va, r->reserved, r->gran, nullptr, 0) != hipSuccess) { delete r; return KUN_ERR_HIP; }
+    if (failed("hipMemAddressReserve", hipMemAddressReserve(&va, r->reserved, r->gran, nullptr, 0))) {
+        delete r;
+        return KUN_ERR_HIP;
+    }
     r->base = (char*)va;
     *out = r;
     return KUN_OK;
@@ -96,7 +112,7 @@ int kun_vmm_region_grow(kun_vmm_region* r, size_t bytes) {
     if (r->mapped + bytes > r->reserved) return KUN_ERR_TOO_SMALL;
     const hipMemAllocationProp prop = device_prop(r->device);
     hipMemGenericAllocationHandle_t h;
-    if (hipMemCreate(&h, bytes, &prop, 0) != hipSuccess) return KUN_ERR_HIP;
+    if (failed("hipMemCreate", hipMemCreate(&h, bytes, &prop, 0))) return KUN_ERR_HIP;
     const int st = map_at_tail(r, h, bytes);
     if (st != KUN_OK) (void)hipMemRelease(h);
     return st;
@@ -114,7 +130,7 @@ int kun_vmm_region_move_tail(kun_vmm_region* src, kun_vmm_region* dst, size_t by
     size_t off = src->mapped - bytes;
     for (size_t i = first; i < src->chunks.size(); ++i) {
         const kun_vmm_region::Chunk c = src->chunks[i];
-        if (hipMemUnmap(src->base + off, c.bytes) != hipSuccess) return KUN_ERR_HIP;
+        if (failed("hipMemUnmap", hipMemUnmap(src->base + off, c.bytes))) return KUN_ERR_HIP;
         off += c.bytes;
         const int st = map_at_tail(dst, c.handle, c.bytes);
         if (st != KUN_OK) return st;
@@ -130,10 +146,10 @@ int kun_vmm_region_shrink(kun_vmm_region* r, size_t bytes) {
     if (n == 0) return KUN_ERR_MISALIGNED;
     for (size_t i = 0; i < n; ++i) {
         const kun_vmm_region::Chunk c = r->chunks.back();
-        if (hipMemUnmap(r->base + r->mapped - c.bytes, c.bytes) != hipSuccess) return KUN_ERR_HIP;
+        if (failed("hipMemUnmap", hipMemUnmap(r->base + r->mapped - c.bytes, c.bytes))) return KUN_ERR_HIP;
         r->chunks.pop_back();
         r->mapped -= c.bytes;
-        if (hipMemRelease(c.handle) != hipSuccess) return KUN_ERR_HIP;
+        if (failed("hipMemRelease", hipMemRelease(c.handle))) return KUN_ERR_HIP;
     }
     return KUN_OK;
 }
@@ -142,7 +158,7 @@ int kun_vmm_region_destroy(kun_vmm_region* r) {
     if (!r) return KUN_OK;
     int st = KUN_OK;
     if (r->mapped > 0) st = kun_vmm_region_shrink(r, r->mapped);
-    if (r->base && hipMemAddressFree(r->base, r->reserved) != hipSuccess) st = KUN_ERR_HIP;
+    if (r->base && failed("hipMemAddressFree", hipMemAddressFree(r->base, r->reserved))) st = KUN_ERR_HIP;
     delete r;
     return st;
 }

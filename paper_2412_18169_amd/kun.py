@@ -21,7 +21,7 @@ KUN_F32, KUN_BF16 = 0, 1
 KUN_MAX_RANGES = 16
 
 SYMBOLS = [
-    "kun_status_string", "kun_kv_pool_create", "kun_kv_pool_extend", "kun_kv_pool_num_blocks",
+    "kun_status_string", "kun_last_hip_error", "kun_kv_pool_create", "kun_kv_pool_extend", "kun_kv_pool_num_blocks",
     "kun_kv_pool_num_ranges", "kun_kv_pool_block_bytes", "kun_kv_pool_resolve",
     "kun_kv_pool_destroy", "kun_validate_block_table", "kun_slot_map", "kun_kv_append",
     "kun_decode_workspace_bytes", "kun_paged_decode", "kun_prefill_workspace_bytes",
@@ -34,7 +34,8 @@ SYMBOLS = [
 class KunError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {status_string(status)} ({status})")
+        detail = f": {last_hip_error()}" if status == -7 else ""
+        super().__init__(f"{where}: {status_string(status)} ({status}){detail}")
 
 
 _lib = None
@@ -53,6 +54,8 @@ def lib() -> ctypes.CDLL:
     P = ctypes.POINTER
     L.kun_status_string.restype = ctypes.c_char_p
     L.kun_status_string.argtypes = [i32]
+    L.kun_last_hip_error.restype = ctypes.c_char_p
+    L.kun_last_hip_error.argtypes = []
     L.kun_kv_pool_create.argtypes = [P(vp), vp, sz, i32, i32, i32, i32]
     L.kun_kv_pool_extend.argtypes = [vp, vp, sz, P(i64), P(i64)]
     L.kun_kv_pool_num_blocks.argtypes = [vp, P(i64)]
@@ -78,10 +81,15 @@ def lib() -> ctypes.CDLL:
     L.kun_paged_prefill_chunk.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]
     L.kun_paged_prefill_chunk_on.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, sz, vp]
     for name in SYMBOLS:
-        if name not in ("kun_status_string", "kun_decode_workspace_bytes", "kun_prefill_workspace_bytes"):
+        if name not in ("kun_status_string", "kun_last_hip_error", "kun_decode_workspace_bytes",
+                        "kun_prefill_workspace_bytes"):
             getattr(L, name).restype = i32
     _lib = L
     return L
+
+
+def last_hip_error() -> str:
+    return lib().kun_last_hip_error().decode()
 
 
 def status_string(status: int) -> str:

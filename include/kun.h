@@ -220,6 +220,54 @@ KUN_API int kun_vmm_region_shrink(kun_vmm_region* region, size_t bytes);
 /* Unmaps and releases whatever is still mapped, then frees the reservation and the object. */
 KUN_API int kun_vmm_region_destroy(kun_vmm_region* region);
 
+/* ---- host-side planning around the attention path ------------------------------------------ */
+
+/* Cost model of Section 4.3.  Eq. 1: a chunk of `tokens` new tokens after `prior` tokens of the same
+ * request costs alpha * (prior * tokens + (tokens^2 + tokens) / 2) + beta * tokens + gamma (prefix
+ * attention, causal self attention, per-token work, per-launch rest).  Eq. 2-3: a microbatch costs
+ * the sum over its chunks with tokens > 0 minus (n - 1) * gamma, the parameters being loaded once. */
+typedef struct kun_cost_model { double alpha, beta, gamma; } kun_cost_model;
+typedef struct kun_chunk { int32_t request, prior, tokens; } kun_chunk;
+
+/* NaN on bad arguments. */
+KUN_API double kun_cost_chunk(const kun_cost_model* model, int64_t prior, int64_t tokens);
+KUN_API double kun_cost_microbatch(const kun_cost_model* model, const kun_chunk* chunks, int n);
+
+/* Least-squares fit of the three constants to measured times (offline profiling, Section 4.3):
+ * microbatch k consists of host chunks[mb_start[k] .. mb_start[k + 1]) and took seconds[k].
+ * KUN_ERR_INVALID_ARG if fewer than 3 microbatches are given or they do not determine the model. */
+KUN_API int kun_cost_fit(const kun_chunk* chunks, const int32_t* mb_start, int n_microbatches,
+                 const double* seconds, kun_cost_model* out);
+
+/* Lookahead batch formulation (Section 4.3): the queued chunks (host array, queue order, one entry
+ * per request with its tokens still to run after `prior`) start as ONE microbatch, which is split
+ * recursively into two microbatches of as equal cost as a cut at a token boundary allows -- a cut
+ * request continues in the right half with a larger `prior` -- level by level, until a split would
+ * leave a side with fewer than min_tokens tokens or the next level would exceed max_microbatches
+ * (0 = no limit).  Writes the microbatches back to back into out_chunks (capacity
+ * chunk_capacity) with out_mb_start[k] .. out_mb_start[k + 1] delimiting microbatch k (capacity
+ * mb_capacity microbatches, mb_capacity + 1 entries).  KUN_ERR_TOO_SMALL if a capacity does not
+ * suffice; the constants of the model must be >= 0. */
+KUN_API int kun_lookahead(const kun_cost_model* model, const kun_chunk* queue, int n, int min_tokens,
+                  int max_microbatches, kun_chunk* out_chunks, int chunk_capacity,
+                  int32_t* out_mb_start, int mb_capacity, int* n_microbatches, int* n_chunks);
+
+/* Drop-plan generation (Section 4.2): instance groups, each holding one copy of the num_layers
+ * layers, wait in a priority queue by size (equal sizes: the group formed first); while
+ * demand_bytes is not met and two groups remain, the two smallest merge and one redundant copy
+ * (num_layers * layer_bytes) is dropped.  initial_group: host [n_instances], group number of each
+ * instance before the plan (NULL = every instance alone).  Outputs, host arrays [n_instances]:
+ * group_of_instance (final groups numbered by their smallest instance), kept_first / kept_end (the
+ * contiguous layers [first, end) the instance keeps: the j-th smallest instance of a group of g is
+ * pipeline stage j and keeps layers floor(j L / g) .. floor((j + 1) L / g) - 1), dropped_bytes
+ * (what it can hand to its KVCache: kun_kv_pool_extend or kun_vmm_region_move_tail).  Optional
+ * [2 * (n_instances - 1)]: merge_members (one instance of each of the two groups of every merge,
+ * in order) and merge_sizes.  *demand_met == 0 means no plan frees enough: fall back. */
+KUN_API int kun_drop_plan(int n_instances, const int32_t* initial_group, int num_layers, int64_t layer_bytes,
+                  int64_t demand_bytes, int32_t* group_of_instance, int32_t* kept_first,
+                  int32_t* kept_end, int64_t* dropped_bytes, int32_t* merge_members,
+                  int32_t* merge_sizes, int* n_merges, int64_t* freed_bytes, int* demand_met);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,7 +9,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["pool.hip", "vmm.hip", "append.hip", "decode.hip", "prefill.hip"]
+SOURCES = ["pool.hip", "vmm.hip", "plan.hip", "append.hip", "decode.hip", "prefill.hip"]
 LIB = os.path.join(HERE, "libkun.so")
 CEILINGS = os.path.join(HERE, "kun_ceilings")
 

@@ -28,7 +28,16 @@ SYMBOLS = [
     "kun_paged_prefill_chunk", "kun_paged_prefill_chunk_on", "kun_kv_pool_resize_tail",
     "kun_vmm_region_create", "kun_vmm_region_info", "kun_vmm_region_grow", "kun_vmm_region_move_tail",
     "kun_vmm_region_shrink", "kun_vmm_region_destroy",
+    "kun_cost_chunk", "kun_cost_microbatch", "kun_cost_fit", "kun_lookahead", "kun_drop_plan",
 ]
+
+
+class CostModel(ctypes.Structure):
+    _fields_ = [("alpha", ctypes.c_double), ("beta", ctypes.c_double), ("gamma", ctypes.c_double)]
+
+
+class Chunk(ctypes.Structure):
+    _fields_ = [("request", ctypes.c_int32), ("prior", ctypes.c_int32), ("tokens", ctypes.c_int32)]
 
 
 class KunError(RuntimeError):
@@ -66,6 +75,14 @@ def lib() -> ctypes.CDLL:
     L.kun_vmm_region_move_tail.argtypes = [vp, vp, sz]
     L.kun_vmm_region_shrink.argtypes = [vp, sz]
     L.kun_vmm_region_destroy.argtypes = [vp]
+    f64 = ctypes.c_double
+    L.kun_cost_chunk.restype = f64
+    L.kun_cost_chunk.argtypes = [P(CostModel), i64, i64]
+    L.kun_cost_microbatch.restype = f64
+    L.kun_cost_microbatch.argtypes = [P(CostModel), vp, i32]
+    L.kun_cost_fit.argtypes = [vp, vp, i32, vp, P(CostModel)]
+    L.kun_lookahead.argtypes = [P(CostModel), vp, i32, i32, i32, vp, i32, vp, i32, P(i32), P(i32)]
+    L.kun_drop_plan.argtypes = [i32, vp, i32, i64, i64, vp, vp, vp, vp, vp, vp, P(i32), P(i64), P(i32)]
     L.kun_kv_pool_num_ranges.argtypes = [vp, P(i32)]
     L.kun_kv_pool_block_bytes.argtypes = [vp, P(sz)]
     L.kun_kv_pool_resolve.argtypes = [vp, i64, P(i32), P(sz), P(vp)]
@@ -82,7 +99,7 @@ def lib() -> ctypes.CDLL:
     L.kun_paged_prefill_chunk_on.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, sz, vp]
     for name in SYMBOLS:
         if name not in ("kun_status_string", "kun_last_hip_error", "kun_decode_workspace_bytes",
-                        "kun_prefill_workspace_bytes"):
+                        "kun_prefill_workspace_bytes", "kun_cost_chunk", "kun_cost_microbatch"):
             getattr(L, name).restype = i32
     _lib = L
     return L
@@ -271,3 +288,65 @@ def kun_paged_prefill_chunk_on(pool: int, q, out, q_start, prior_len, block_tabl
                                             int(max_workgroups), _ptr(workspace), int(workspace_bytes),
                                             _stream(stream)),
            "kun_paged_prefill_chunk_on")
+
+
+# ---- host-side planning (no device work) ---------------------------------------------------------
+def _chunk_array(chunks):
+    arr = (Chunk * max(len(chunks), 1))()
+    for i, (r, p, c) in enumerate(chunks):
+        arr[i] = Chunk(int(r), int(p), int(c))
+    return arr
+
+
+def kun_cost_chunk(model, prior: int, tokens: int) -> float:
+    return lib().kun_cost_chunk(ctypes.byref(CostModel(*model)), int(prior), int(tokens))
+
+
+def kun_cost_microbatch(model, chunks) -> float:
+    return lib().kun_cost_microbatch(ctypes.byref(CostModel(*model)), _chunk_array(chunks), len(chunks))
+
+
+def kun_cost_fit(microbatches, seconds):
+    """microbatches: list of lists of (request, prior, tokens); returns (alpha, beta, gamma)."""
+    flat = [ch for mb in microbatches for ch in mb]
+    starts = (ctypes.c_int32 * (len(microbatches) + 1))()
+    o = 0
+    for k, mb in enumerate(microbatches):
+        starts[k] = o
+        o += len(mb)
+    starts[len(microbatches)] = o
+    t = (ctypes.c_double * max(len(seconds), 1))(*[float(x) for x in seconds])
+    out = CostModel()
+    _check(lib().kun_cost_fit(_chunk_array(flat), starts, len(microbatches), t, ctypes.byref(out)), "kun_cost_fit")
+    return out.alpha, out.beta, out.gamma
+
+
+def kun_lookahead(model, queue, min_tokens: int, max_microbatches: int = 0):
+    """Returns the microbatches as lists of (request, prior, tokens)."""
+    total = sum(c for _, _, c in queue)
+    mb_cap = max(1, min(total // max(min_tokens, 1) + 1, max_microbatches or (1 << 30)))
+    ch_cap = len(queue) + mb_cap
+    out = (Chunk * ch_cap)()
+    starts = (ctypes.c_int32 * (mb_cap + 1))()
+    n_mb, n_ch = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().kun_lookahead(ctypes.byref(CostModel(*model)), _chunk_array(queue), len(queue), int(min_tokens),
+                               int(max_microbatches), out, ch_cap, starts, mb_cap, ctypes.byref(n_mb),
+                               ctypes.byref(n_ch)), "kun_lookahead")
+    return [[(out[i].request, out[i].prior, out[i].tokens) for i in range(starts[k], starts[k + 1])]
+            for k in range(n_mb.value)]
+
+
+def kun_drop_plan(n_instances: int, initial_group, num_layers: int, layer_bytes: int, demand_bytes: int):
+    """Returns a dict: group_of_instance, kept (list of (first, end)), dropped_bytes, merges (list of
+    ((member, size), (member, size))), freed_bytes, demand_met."""
+    N = int(n_instances)
+    i32a, i64a = ctypes.c_int32 * N, ctypes.c_int64 * N
+    grp, kf, ke, db = i32a(), i32a(), i32a(), i64a()
+    mm, ms = (ctypes.c_int32 * (2 * max(N - 1, 1)))(), (ctypes.c_int32 * (2 * max(N - 1, 1)))()
+    init = None if initial_group is None else i32a(*[int(g) for g in initial_group])
+    n_m, freed, met = ctypes.c_int32(), ctypes.c_int64(), ctypes.c_int32()
+    _check(lib().kun_drop_plan(N, init, int(num_layers), int(layer_bytes), int(demand_bytes), grp, kf, ke, db, mm, ms,
+                               ctypes.byref(n_m), ctypes.byref(freed), ctypes.byref(met)), "kun_drop_plan")
+    return {"group_of_instance": list(grp), "kept": list(zip(kf, ke)), "dropped_bytes": list(db),
+            "merges": [((mm[2 * k], ms[2 * k]), (mm[2 * k + 1], ms[2 * k + 1])) for k in range(n_m.value)],
+            "freed_bytes": freed.value, "demand_met": bool(met.value)}

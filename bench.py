@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) to scale rocprofv3 --pmc counters")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--cost-model", action="store_true",
+                    help="also fit the chunk cost model (prefix + self attention pairs, tokens, constant) to "
+                         "measured prefill calls and report its error on held-out microbatches")
     ap.add_argument("--vmm", action="store_true",
                     help="also time the decode step over the same pool built as ONE virtual range that grew "
                          "chunk by chunk, and the mapping calls themselves")
@@ -160,6 +163,8 @@ def main():
 
     if args.vmm:
         out["vmm"] = vmm_report(dw, args.steps)
+    if args.cost_model:
+        out["cost_model"] = cost_model_report(sh)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"], out["max_abs_err_vs_oracle"] = cpu_baseline(dw, args.cpu_seconds)
@@ -195,6 +200,74 @@ def mixed_batch(dw, steps, prefill_workgroups=256):
     t_mix = timed(lambda: dw.mixed(s1, s2, prefill_workgroups))
     return {"ms_back_to_back": round(t_seq, 4), "ms_two_streams": round(t_mix, 4),
             "prefill_workgroups": prefill_workgroups}
+
+
+def cost_model_report(sh, reps=10):
+    """Times kun_paged_prefill_chunk on microbatches of 1-4 chunks over a grid of (prior, chunk) sizes,
+    fits the three constants of the chunk cost model with kun_cost_fit on two thirds of them and
+    reports the relative error of the fitted model, and of a model that counts tokens only, on the
+    held-out third."""
+    import torch
+    from paper_2412_18169_amd import kun, synth
+    from paper_2412_18169_amd.runner import DeviceWorkload
+    rng = np.random.default_rng(77)
+    priors = [0, 1024, 2048, 4096, 8192, 12288, 16384]
+    sizes = [1024, 2048, 4096]
+    combos = [(p, c) for p in priors for c in sizes]
+    w = synth.custom_workload("cost-model", sh, [1], chunks=combos, seed=77, extra_blocks=0)
+    dw = DeviceWorkload(w, poison=False)
+    # microbatches of 3-8 chunks: enough query tiles to fill every compute unit several times, as the
+    # lookahead formulation assumes of a microbatch (a launch that leaves compute units idle is bound
+    # by its longest workgroup instead, which no work-based model describes)
+    idx_sets = []
+    for _ in range(75):
+        idx_sets.append(sorted(rng.choice(len(combos), size=int(rng.integers(3, 9)), replace=False).tolist()))
+    table_all = dw.pre_table
+    times, mbs = [], []
+    for ids in idx_sets:
+        cs = [combos[i][1] for i in ids]
+        q_start = torch.tensor(np.concatenate([[0], np.cumsum(cs)]).astype(np.int32), device=dw.dev)
+        prior = torch.tensor([combos[i][0] for i in ids], dtype=torch.int32, device=dw.dev)
+        table = table_all[ids].contiguous()
+        total = int(sum(cs))
+        q = torch.cat([dw.q_pre[int(dw.q_start_host[i]):int(dw.q_start_host[i + 1])] for i in ids]).contiguous()
+        o = torch.empty_like(q)
+        need = kun.kun_prefill_workspace_bytes(dw.pool, len(ids), sh.Hq, total)
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dw.dev)
+
+        def call():
+            kun.kun_paged_prefill_chunk(dw.pool, q, o, q_start, prior, table, table.shape[1], len(ids), sh.Hq,
+                                        total, sh.scale, ws, ws.numel())
+        for _ in range(2):
+            call()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            call()
+        b.record()
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(b) / reps * 1e-3)
+        mbs.append([(i, combos[i][0], combos[i][1]) for i in ids])
+    dw.close()
+    order = rng.permutation(len(mbs))
+    test = set(order[: len(mbs) // 3].tolist())
+    train = [k for k in range(len(mbs)) if k not in test]
+    model = kun.kun_cost_fit([mbs[k] for k in train], [times[k] for k in train])
+    # token-count model: time = b * tokens + g, fitted on the same samples
+    X = np.array([[sum(c for _, _, c in mbs[k]), 1.0] for k in train])
+    tb, tg = np.linalg.lstsq(X, np.array([times[k] for k in train]), rcond=None)[0]
+    err, err_tok = [], []
+    for k in sorted(test):
+        pred = kun.kun_cost_microbatch(model, mbs[k])
+        err.append(abs(pred - times[k]) / times[k])
+        err_tok.append(abs(tb * sum(c for _, _, c in mbs[k]) + tg - times[k]) / times[k])
+    return {"alpha_s_per_pair": model[0], "beta_s_per_token": model[1], "gamma_s": model[2],
+            "fitted_on": len(train), "held_out": len(test),
+            "rel_err_mean": round(float(np.mean(err)), 4), "rel_err_max": round(float(np.max(err)), 4),
+            "token_count_model_rel_err_mean": round(float(np.mean(err_tok)), 4),
+            "token_count_model_rel_err_max": round(float(np.max(err_tok)), 4),
+            "shape": {"Hq": sh.Hq, "Hkv": sh.Hkv, "head_dim": sh.d}}
 
 
 def vmm_report(dw, steps):

@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=0, help="workload 2..5 (default: the largest supported)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mixed", action="store_true",
+                    help="skip the side-by-side prefill + decode measurement (keeps profiles to the K timed steps)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) to scale rocprofv3 --pmc counters")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -158,7 +160,7 @@ def main():
                           "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                           "new_tokens_per_s": round(dw.total_new / (t_pre * 1e-3), 1)}
 
-    if has_prefill and not args.pmc_calibration:
+    if has_prefill and not args.pmc_calibration and not args.no_mixed:
         out["mixed"] = mixed_batch(dw, args.steps)
 
     if args.vmm:
@@ -409,7 +411,7 @@ def prefill_check(dw, rows_per_chunk=6):
 DEFAULT_CONFIG = 5
 PREFILL_SUPPORTED = True
 ORACLE_TOKENS_PER_S = 80000.0      # rough speed of the numpy oracle, only used to size its sample
-TRAFFIC_BYTES = {5: 17111671427}                 # per-launch HBM bytes from rocprofv3 --pmc runs (see profiles/)
+TRAFFIC_BYTES = {5: 17113737830}                 # per-launch HBM bytes from rocprofv3 --pmc runs (see profiles/)
 
 if __name__ == "__main__":
     main()

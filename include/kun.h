@@ -212,8 +212,9 @@ KUN_API int kun_vmm_region_info(const kun_vmm_region* region, void** base, size_
                         size_t* reserved_bytes, size_t* granularity);
 /* Allocate `bytes` of device memory as one chunk and map it at the tail. */
 KUN_API int kun_vmm_region_grow(kun_vmm_region* region, size_t bytes);
-/* Unmap the last `bytes` of src and map the same physical chunks, in the same order, at the tail of
- * dst: the contents move with them, no copy is made. */
+/* Unmap the last `bytes` of src (whole chunks) and map the same physical chunks, in the same order,
+ * at the tail of dst: the contents move with them, no copy is made.  On KUN_ERR_HIP the chunks
+ * moved so far stay at dst and the others at src. */
 KUN_API int kun_vmm_region_move_tail(kun_vmm_region* src, kun_vmm_region* dst, size_t bytes);
 /* Unmap the last `bytes` and give the physical memory back to the driver. */
 KUN_API int kun_vmm_region_shrink(kun_vmm_region* region, size_t bytes);

@@ -1,8 +1,8 @@
 // Virtual-memory form of the KVCache region (Section 4.1, "Local instance memory management"): one
 // virtual address range is reserved for the largest KVCache the instance may ever hold, physical
 // memory is mapped at its tail when the pool grows, and the physical chunks behind dropped
-// parameters are moved there without copying (and moved back on restoration, Section 4.4).  Kernels
-// then see ONE contiguous range whose size changes; kun_kv_pool_resize_tail tells the pool.
+// parameters are remapped there without a copy (and back on restoration, Section 4.4).  Kernels then see ONE contiguous
+// range whose size changes; kun_kv_pool_resize_tail tells the pool.
 //
 // Host code only (HIP virtual memory management API); no kernels.
 #include <new>
@@ -48,7 +48,11 @@ int map_at_tail(kun_vmm_region* r, hipMemGenericAllocationHandle_t h, size_t byt
     acc.location.type = hipMemLocationTypeDevice;
     acc.location.id = r->device;
     acc.flags = hipMemAccessFlagsProtReadWrite;
-    if (failed("hipMemSetAccess", hipMemSetAccess(at, bytes, &acc, 1))) {
+    // Access is set for everything mapped so far, not for the new chunk alone: asked for a chunk that
+    // is not the first of its reservation, this driver answers "invalid argument" unless all chunks
+    // have the same size (measured: a call over [base, end of the new chunk) never failed, for fresh
+    // and for remapped allocation handles).
+    if (failed("hipMemSetAccess", hipMemSetAccess(r->base, r->mapped + bytes, &acc, 1))) {
         (void)hipMemUnmap(at, bytes);
         return KUN_ERR_HIP;
     }
@@ -82,8 +86,8 @@ int kun_vmm_region_create(kun_vmm_region** out, size_t reserve_bytes) {
         delete r;
         return KUN_ERR_HIP;
     }
-    // The driver reports 4 KiB here, but access to large chunks can only be set on 2 MiB-aligned
-    // spans: the region works in units of at least 2 MiB, base included.
+    // The driver reports 4 KiB here; the region works in units of at least 2 MiB, base included, so
+    // that chunks can be mapped with large pages.
     if (r->gran < kMinGranularity) r->gran = kMinGranularity;
     r->reserved = (reserve_bytes + r->gran - 1) / r->gran * r->gran;
     void* va = nullptr;

@@ -61,6 +61,13 @@ def test_regions_grow_move_their_tail_without_a_copy_and_shrink():
     assert kun.kun_vmm_region_info(par)[1] == 9 * g and kun.kun_vmm_region_info(kv)[1] == 6 * g
     assert bool((kun.device_bytes(pbase + 3 * g, 6 * g) == 99).all())
     assert torch.equal(kun.device_bytes(base, 6 * g), kv_bytes)
+    assert status_of(kun.kun_vmm_region_move_tail, par, kv, 4 * g) == -2       # chunks keep their sizes: 3 g each
+    # chunks of many different sizes next to each other
+    for k in (1, 5, 2, 7, 3):
+        kun.kun_vmm_region_grow(kv, k * g)
+    kun.device_bytes(base, 24 * g).fill_(5)
+    torch.cuda.synchronize()
+    kun.kun_vmm_region_shrink(kv, 18 * g)
     kun.kun_vmm_region_shrink(kv, 2 * g)
     assert kun.kun_vmm_region_info(kv)[1] == 4 * g
     torch.cuda.synchronize()

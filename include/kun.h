@@ -175,7 +175,9 @@ KUN_API size_t kun_prefill_workspace_bytes(const kun_kv_pool* pool, int n_chunks
  * back to back; q_start: device int32 [n_chunks + 1], row offsets with q_start[n_chunks] ==
  * total_new_tokens; prior_len: device int32 [n_chunks]; block_table: device int32
  * [n_chunks, max_blocks], row i covering the p_i + c_i tokens of chunk i's request.  Row r of
- * chunk i sees logical keys 0 .. p_i + r.  A chunk with c == 0 is skipped. */
+ * chunk i sees logical keys 0 .. p_i + r.  A chunk with c == 0 is skipped.  bf16 pools with
+ * head_dim 128 run on the matrix cores; fp32 and head_dim 64 pools are served row by row by the
+ * vector-ALU decode kernel (correct to the same bar, not tuned). */
 KUN_API int kun_paged_prefill_chunk(kun_kv_pool* pool, const void* q, void* out, const int32_t* q_start,
                             const int32_t* prior_len, const int32_t* block_table, int max_blocks,
                             int n_chunks, int num_q_heads, int total_new_tokens, float scale,

@@ -31,6 +31,7 @@ struct DecodeArgs {
     void* out;
     const int32_t* table;
     const int32_t* ctx_len;
+    const int32_t* row_of_seq;  // optional: block-table row of each request (NULL: request s uses row s)
     int32_t* n_items;        // workspace: number of work items (written by plan)
     int32_t* seq_first;      // workspace: [S + 1] first item of each request
     int2* items;             // workspace: (request, partition)
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
         for (int i = 0; i < DPL; ++i) acc[g][i] = 0.f;
     }
 
-    const int32_t* trow = a.table + (size_t)seq * a.max_blocks;
+    const int32_t* trow = a.table + (size_t)(a.row_of_seq ? a.row_of_seq[seq] : seq) * a.max_blocks;
     for (int b = t0 / kBlock + wave; b * kBlock < t1; b += NW) {
         const int blk = __builtin_amdgcn_readfirstlane(trow[b]);
         const char* page = kun_block_addr(a.rt, blk, a.block_bytes) + (size_t)kvh * a.page_bytes;
@@ -595,7 +596,61 @@ int launch_generic(const DecodeArgs& a, dim3 grid, hipStream_t st) {
     return KUN_OK;
 }
 
+// every row is its own request with one partition: item t = (t, 0)
+__global__ __launch_bounds__(256) void rows_plan_kernel(int T, int32_t* __restrict__ n_items,
+                                                        int32_t* __restrict__ seq_first, int2* __restrict__ items) {
+    for (int t = blockIdx.x * blockDim.x + threadIdx.x; t <= T; t += gridDim.x * blockDim.x) {
+        seq_first[t] = t;
+        if (t < T) items[t] = make_int2(t, 0);
+        if (t == 0) *n_items = T;
+    }
+}
+
 }  // namespace
+
+size_t kun_attend_rows_workspace_bytes(int T) {
+    return 256 + align256(sizeof(int32_t) * ((size_t)T + 1)) + align256(sizeof(int2) * (size_t)T);
+}
+
+int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, const int32_t* table, int max_blocks,
+                            const int32_t* ctx_len, const int32_t* row_of_seq, int T, int Hq, float scale,
+                            void* workspace, hipStream_t st) {
+    char* ws = (char*)workspace;
+    DecodeArgs a;
+    a.rt = p->ranges;
+    a.q = q;
+    a.out = out;
+    a.table = table;
+    a.ctx_len = ctx_len;
+    a.row_of_seq = row_of_seq;
+    a.n_items = (int32_t*)ws;
+    a.seq_first = (int32_t*)(ws + 256);
+    a.items = (int2*)(ws + 256 + align256(sizeof(int32_t) * ((size_t)T + 1)));
+    a.part_ml = nullptr;          // one partition per row: outputs are written directly
+    a.part_acc = nullptr;
+    a.max_blocks = max_blocks;
+    a.S = T;
+    a.Hkv = p->Hkv;
+    a.G = Hq / p->Hkv;
+    a.part_tokens = 1 << 30;
+    a.max_items = T;
+    a.scale_log2 = scale * kLog2e;
+    a.block_bytes = (unsigned)p->block_bytes;
+    a.page_bytes = (unsigned)p->page_bytes;
+    const int nb = (T + 256) / 256;
+    hipLaunchKernelGGL(rows_plan_kernel, dim3((unsigned)(nb < 1024 ? nb : 1024)), dim3(256), 0, st, T, a.n_items,
+                       a.seq_first, a.items);
+    KUN_HIP_CHECK_LAUNCH();
+    const dim3 grid((unsigned)((size_t)T * p->Hkv));
+    int rc;
+    if (p->dtype == KUN_BF16)
+        rc = p->d == 128 ? launch_generic<bf16_t, 128>(a, grid, st) : launch_generic<bf16_t, 64>(a, grid, st);
+    else
+        rc = p->d == 128 ? launch_generic<float, 128>(a, grid, st) : launch_generic<float, 64>(a, grid, st);
+    if (rc != KUN_OK) return rc;
+    KUN_HIP_CHECK_LAUNCH();
+    return KUN_OK;
+}
 
 extern "C" {
 
@@ -636,6 +691,7 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     a.out = out;
     a.table = block_table;
     a.ctx_len = ctx_len;
+    a.row_of_seq = nullptr;
     a.n_items = (int32_t*)ws;
     a.seq_first = (int32_t*)(ws + lay.off_first);
     a.items = (int2*)(ws + lay.off_items);

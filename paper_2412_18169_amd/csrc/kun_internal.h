@@ -33,6 +33,15 @@ __device__ __forceinline__ char* kun_block_addr(const KunRanges& rt, int blk, si
     return rt.base[r] + (size_t)(blk - rt.first[r]) * block_bytes;
 }
 
+// Attention of T independent query rows by the vector-ALU decode kernel, any supported dtype and
+// head_dim: row t has ctx_len[t] tokens (device int32 [T]) behind row row_of_seq[t] of the block
+// table (device int32 [T]); q, out: device [T, Hq, head_dim].  One workgroup per (row, kv head)
+// walks the whole context.  workspace: device, 256-byte aligned, kun_attend_rows_workspace_bytes(T).
+size_t kun_attend_rows_workspace_bytes(int T);
+int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, const int32_t* table, int max_blocks,
+                            const int32_t* ctx_len, const int32_t* row_of_seq, int T, int Hq, float scale,
+                            void* workspace, hipStream_t st);
+
 // Remembers which HIP call failed and how, per host thread, for kun_last_hip_error().
 void kun_note_hip_error(const char* call, hipError_t e);
 

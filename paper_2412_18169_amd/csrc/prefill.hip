@@ -774,6 +774,23 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Shapes the MFMA kernels do not cover (fp32, head_dim 64): row r of chunk i is the decode of a
+// request of p_i + r + 1 tokens behind table row i.
+__global__ __launch_bounds__(256) void prefill_rows_kernel(const int32_t* __restrict__ q_start,
+                                                           const int32_t* __restrict__ prior, int n_chunks,
+                                                           int32_t* __restrict__ ctx_len,
+                                                           int32_t* __restrict__ row_of_seq) {
+    for (int i = blockIdx.x; i < n_chunks; i += gridDim.x) {
+        const int qs = q_start[i], c = q_start[i + 1] - qs, p = prior[i];
+        for (int r = threadIdx.x; r < c; r += blockDim.x) {
+            ctx_len[qs + r] = p + r + 1;
+            row_of_seq[qs + r] = i;
+        }
+    }
+}
+
+bool mfma_shape(const kun_kv_pool* p) { return p->dtype == KUN_BF16 && p->d == 128 && p->B == 16; }
+
 // Tile shape: NW waves x 32 NQ rows per workgroup; `ring` selects prefill_ring_kernel, otherwise the
 // register-staged prefill_kernel runs; `persistent`: a fixed number of workgroups fetch the work
 // items (ring kernel, 8 waves) instead of one workgroup per item.  Default: ring kernel, 8 waves, one
@@ -822,6 +839,9 @@ void launch_prefill(const PrefillArgs& a, dim3 grid, TileShape t, hipStream_t st
 
 extern "C" size_t kun_prefill_workspace_bytes(const kun_kv_pool* p, int n_chunks, int Hq, int total_new_tokens) {
     if (!prefill_shape_ok(p, n_chunks, Hq, total_new_tokens)) return 0;
+    if (!mfma_shape(p))                                    // rows as decode requests: two int32 per row + its plan
+        return 256 + 2 * align256(sizeof(int32_t) * (size_t)total_new_tokens) +
+               kun_attend_rows_workspace_bytes(total_new_tokens);
     const int G = Hq / p->Hkv;
     const int pos_min = 128 / (G > 0 ? G : 1);             // smallest tile (NQ = 1)
     const size_t max_items = (size_t)total_new_tokens / (pos_min > 0 ? pos_min : 1) + n_chunks;
@@ -838,11 +858,21 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     if (!prefill_shape_ok(p, n_chunks, Hq, total_new_tokens) || max_workgroups < 0) return KUN_ERR_INVALID_ARG;
     if (n_chunks == 0 || total_new_tokens == 0) return KUN_OK;
     if (!q || !out || !q_start || !prior_len || !block_table || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
-    if (p->dtype != KUN_BF16 || p->d != 128 || p->B != 16) return KUN_ERR_UNSUPPORTED;
     const int G = Hq / p->Hkv;
     if (G != 1 && G != 2 && G != 4 && G != 8) return KUN_ERR_UNSUPPORTED;
     const size_t need = kun_prefill_workspace_bytes(p, n_chunks, Hq, total_new_tokens);
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < need) return KUN_ERR_WORKSPACE;
+    if (!mfma_shape(p)) {
+        const size_t col = align256(sizeof(int32_t) * (size_t)total_new_tokens);
+        int32_t* ctx_len = (int32_t*)((char*)workspace + 256);
+        int32_t* row_of_seq = (int32_t*)((char*)workspace + 256 + col);
+        hipStream_t st = (hipStream_t)stream;
+        hipLaunchKernelGGL(prefill_rows_kernel, dim3((unsigned)(n_chunks < 4096 ? n_chunks : 4096)), dim3(256), 0, st,
+                           q_start, prior_len, n_chunks, ctx_len, row_of_seq);
+        KUN_HIP_CHECK_LAUNCH();
+        return kun_attend_rows_generic(p, q, out, block_table, max_blocks, ctx_len, row_of_seq, total_new_tokens, Hq,
+                                       scale, (char*)workspace + 256 + 2 * col, st);
+    }
 
     const TileShape shape = max_workgroups > 0 ? TileShape{8, 1, true, true} : choose_shape();
     const bool persistent = shape.persistent;

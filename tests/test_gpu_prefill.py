@@ -159,6 +159,31 @@ def test_mixed_batch_on_two_streams_equals_the_calls_in_sequence():
     dw.close()
 
 
+@pytest.mark.parametrize("dtype,d,G", [("f32", 64, 4), ("f32", 128, 2), ("bf16", 64, 8), ("f32", 64, 1)])
+def test_shapes_outside_the_mfma_kernels(dtype, d, G):
+    # fp32 and head_dim 64 go through the vector-ALU kernel, row by row; fp32: 1e-5 against the oracle
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=16, dtype=dtype)
+    chunks = [(0, 1), (0, 17), (5, 1), (15, 16), (31, 64), (100, 70), (0, 130), (333, 40), (20, 0)]
+    w = synth.custom_workload("gen", sh, [3], chunks=chunks, extra_blocks=5, range_fracs=(0.4, 0.6))
+    dw = DeviceWorkload(w)
+    dw.out_pre.fill_(float("nan"))
+    out = dw.prefill()
+    torch.cuda.synchronize()
+    got = out.double().cpu().numpy()
+    assert np.isfinite(got).all()
+    tol = 1e-5 if dtype == "f32" else TOL
+    for i, (p, c) in enumerate(w.chunks):
+        if c == 0:
+            continue
+        q0 = int(dw.q_start_host[i])
+        pool, tab = bridge.compact_pool(dw.ranges, w.range_blocks, [w.block_tables[w.S + i]], [p + c], sh.Hkv, sh.d,
+                                        sh.B, sh.dtype)
+        ref, _ = O.paged_prefill_chunk(pool, bridge.host_bits(dw.q_pre[q0:q0 + c]), tab[0], p, c, sh.Hq, sh.scale)
+        err = np.abs(got[q0:q0 + c] - ref).max()
+        assert err <= tol, f"chunk {i} (p={p}, c={c}): max abs err {err}"
+    dw.close()
+
+
 def test_empty_chunk_is_skipped_and_first_row_returns_v():
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     w = synth.custom_workload("pre0", sh, [3], chunks=[(0, 5), (7, 0), (0, 40)], extra_blocks=2)

@@ -54,6 +54,12 @@ struct PrefillArgs {
     int32_t* n_items;     // workspace
     int32_t* next_item;   // workspace: 8 counters (one per XCD) for the workgroups that fetch their work
     int2* items;          // workspace: (chunk, position tile)
+    // Launches with too few items to fill the chip split the keys of an item over several workgroups:
+    const int2* split_info;   // workspace, NULL when the launch cannot need it: per item (split | nsplit << 16, slot)
+    int4* split_items;        // workspace: (chunk, position tile, nsplit, first slot) of every split item
+    int32_t* n_split_items;   // workspace
+    float* part_o;            // workspace: [slot, kvh, 256 rows, 128] unnormalised outputs of a key range
+    float* part_ml;           // workspace: [slot, kvh, 256 rows, 2]  (m in log2 units, l)
     int max_blocks;
     int n_chunks, Hkv, Hq;
     int max_items;
@@ -87,13 +93,21 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanSortMax = 4096;      // items beyond this stay in chunk order
 constexpr int kPlanBuckets = 1024;      // cost buckets (key tiles); longer ones share the first bucket
+constexpr int kSplitTarget = 256;       // split keys when a launch has fewer (item, kv head) workgroups than this
+constexpr int kMaxSplit = 16;           // key ranges per item at most
+constexpr int kMinTilesPerSplit = 8;    // ... of at least this many 64-key tiles each
+constexpr int kSplitRows = 256;         // rows of a workgroup of the kernels that can split (8 waves x 32)
 
 __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_t* __restrict__ q_start,
                                                                   const int32_t* __restrict__ prior, int n_chunks,
                                                                   int pos_per_tile, int max_items,
                                                                   int32_t* __restrict__ n_items,
                                                                   int32_t* __restrict__ next_item,
-                                                                  int2* __restrict__ items) {
+                                                                  int2* __restrict__ items, int Hkv, int split_target,
+                                                                  int max_entries,
+                                                                  int2* __restrict__ split_info,
+                                                                  int4* __restrict__ split_items,
+                                                                  int32_t* __restrict__ n_split_items) {
     __shared__ int base_s;
     __shared__ int cnt[kPlanThreads];
     __shared__ int cost[kPlanSortMax];
@@ -153,7 +167,62 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
     }
     __syncthreads();
     for (int i = tid; i < ns; i += kPlanThreads) items[atomicAdd(&hist[cost[i]], 1)] = tmp_item[i];
-    if (tid == 0) *n_items = total;
+    if (split_target == 0) {
+        if (tid == 0) *n_items = total;
+        return;
+    }
+    // Too few workgroups for the chip (the host only asks when that is possible): give every item up to
+    // `want` key ranges of at least kMinTilesPerSplit tiles each and rewrite the list with one entry per
+    // (item, key range).  total * Hkv < split_target here, so one thread per item does it.
+    __shared__ int nsp_s[kSplitTarget], off_s[kSplitTarget], slot_s[kSplitTarget], idx_s[kSplitTarget];
+    __shared__ int n_out_s, n_split_s;
+    __syncthreads();
+    const int wgs = total * Hkv;
+    int want = (wgs > 0 && wgs < split_target) ? (split_target + wgs - 1) / wgs : 1;
+    if (want > kMaxSplit) want = kMaxSplit;
+    const bool mine = want > 1 && tid < total;             // total < kSplitTarget <= kPlanThreads
+    int2 it = make_int2(0, 0);
+    if (mine) {
+        it = items[tid];                                   // sorted order, written by this workgroup
+        const int c = q_start[it.x + 1] - q_start[it.x];
+        const int tiles = (prior[it.x] + min(c, (it.y + 1) * pos_per_tile) - 1) / BN + 1;
+        nsp_s[tid] = max(1, min(want, tiles / kMinTilesPerSplit));
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int n_out = 0, n_split = 0, slot = 0;
+        if (want > 1) {
+            for (int i = 0; i < total; ++i) {
+                off_s[i] = n_out;
+                slot_s[i] = slot;
+                idx_s[i] = n_split;
+                n_out += nsp_s[i];
+                if (nsp_s[i] > 1) {
+                    slot += nsp_s[i];
+                    ++n_split;
+                }
+            }
+            // never beyond what the host sized (cannot happen with its bounds): then nothing is split
+            if (n_out > max_entries || slot * Hkv > 2 * split_target + Hkv) want = 1;
+        }
+        n_out_s = want > 1 ? n_out : total;
+        n_split_s = want > 1 ? n_split : 0;
+    }
+    __syncthreads();
+    if (n_split_s == 0 && n_out_s == total) {              // nothing split: every item is its own whole key range
+        for (int i = tid; i < total; i += kPlanThreads) split_info[i] = make_int2(1 << 16, -1);
+    } else if (mine) {
+        const int nsp = nsp_s[tid];
+        if (nsp > 1) split_items[idx_s[tid]] = make_int4(it.x, it.y, nsp, slot_s[tid]);
+        for (int sp = 0; sp < nsp; ++sp) {
+            items[off_s[tid] + sp] = it;
+            split_info[off_s[tid] + sp] = make_int2(sp | (nsp << 16), nsp > 1 ? slot_s[tid] + sp : -1);
+        }
+    }
+    if (tid == 0) {
+        *n_items = n_out_s;
+        *n_split_items = n_split_s;
+    }
 }
 
 // Staging of one 64-key tile (4 KV blocks): K rows XOR-swizzled by 16-byte chunk, V^T pages as stored.
@@ -466,13 +535,22 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     const int nblk_ctx = (ctx + kBlock - 1) / kBlock;
     const int wg_vis_max = p + min(pos0 + POS, c) - 1;
     const int n_tiles = wg_vis_max / BN + 1;
+    // this workgroup's share of the key tiles: all of them, or one of the item's key ranges
+    int kt0 = 0, nt = n_tiles, part_slot = -1;
+    if (a.split_info) {
+        const int2 si = a.split_info[item];
+        const int split = si.x & 0xffff, nsplit = si.x >> 16;
+        kt0 = split * n_tiles / nsplit;
+        nt = (split + 1) * n_tiles / nsplit - kt0;
+        part_slot = si.y;
+    }
 
     constexpr int TPB = 64 / LOADS;
     // Page addresses this wave stages, resolved a batch at a time in the vector lanes (lane LOADS*t + i
     // = tile batch_first + t, load i): one table gather and one walk over the range table per TPB
     // tiles, instead of dependent scalar loads in front of every tile's loads.
     auto load_pages = [&](int batch) -> unsigned long long {
-        const int t = batch * TPB + lane / LOADS, i = lane % LOADS;
+        const int t = kt0 + batch * TPB + lane / LOADS, i = lane % LOADS;
         int lb = t * kBlocksPerTile + (wave >> 2) + 2 * i;
         if (lb >= nblk_ctx) lb = nblk_ctx - 1;          // past the context: re-read the last block
         const int id = trow[lb];
@@ -503,11 +581,11 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     // sends load j (block j/2, K or V^T).
     unsigned iss_stage = 0;
     const char* iss_page[LOADS];
-    auto issue_begin = [&](int kt) {
-        const int rel = kt % TPB;
-        if (rel == 0 && kt > 0) pages_cur = pages_nxt;
-        if (rel == TPB / 2 && (kt / TPB + 1) * TPB < n_tiles) pages_nxt = load_pages(kt / TPB + 1);
-        iss_stage = ring_addr + (kt % NSTAGE) * (2 * kBlocksPerTile * 4096) + (wave_u & 3) * 1024;
+    auto issue_begin = [&](int j) {                    // j: tile index relative to kt0
+        const int rel = j % TPB;
+        if (rel == 0 && j > 0) pages_cur = pages_nxt;
+        if (rel == TPB / 2 && (j / TPB + 1) * TPB < nt) pages_nxt = load_pages(j / TPB + 1);
+        iss_stage = ring_addr + (j % NSTAGE) * (2 * kBlocksPerTile * 4096) + (wave_u & 3) * 1024;
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
             const unsigned lo = __builtin_amdgcn_readlane((unsigned)pages_cur, rel * LOADS + i);
@@ -521,8 +599,8 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
         if (j & 1) dma16(iss_page[i] + v_src, dk + V_OFF);
         else dma16(iss_page[i] + k_src, dk);
     };
-    auto issue = [&](int kt) {
-        issue_begin(kt);
+    auto issue = [&](int j) {
+        issue_begin(j);
 #pragma unroll
         for (int j = 0; j < 2 * LOADS; ++j) issue_part(j);
     };
@@ -531,8 +609,8 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     const bool stager = wave_u < NSTAGERS;
     if (stager) {
         issue(0);
-        if (n_tiles > 1) issue(1);
-        if (n_tiles > 2) issue(2);
+        if (nt > 1) issue(1);
+        if (nt > 2) issue(2);
     }
 
     Frag qf[8];
@@ -564,9 +642,9 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
 
     // all of this wave's work on the 64-key tile kt, which sits in `stage_base`
     auto compute = [&](int kt, const unsigned char* stage_base) {
-        if (kt > 0 && kt * BN + BN - 1 <= wave_vis_min) {
+        if (kt > kt0 && kt * BN + BN - 1 <= wave_vis_min) {
             // Fast path, the whole 64-key tile is visible to every row of the wave (no mask, no dead
-            // keys) and the rows have a reference maximum m from an earlier tile.  Both sub-tiles go
+            // keys) and the rows have a reference maximum m from an earlier tile of this key range.  Both sub-tiles go
             // through each phase together: 16 QK^T MFMAs in two independent chains, one softmax pass
             // over 32 values per lane, 16 PV MFMAs.  No maximum is taken: the row sums, needed anyway,
             // show when a row's scores have outgrown its reference (sum of 32 numerators above
@@ -696,8 +774,8 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
             const float mxs = mx * sl2;
             const bool grow = mxs > m + kLazy;         // also true on the first sub-tile (m = -inf)
             if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-                const float mn = grow ? mxs : m;       // finite: key 0 is visible to every row
-                const float alpha = __builtin_amdgcn_exp2f(m - mn);
+                const float mn = grow ? mxs : m;
+                const float alpha = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mn);   // o and l are 0 then
                 l *= alpha;
                 m = mn;
 #pragma unroll
@@ -705,10 +783,13 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
             }
             float ps0 = 0.f, ps1 = 0.f;
             union { bf16x2 h[8]; uint4 u[2]; } cv;
+            // a row that has seen no key yet (only possible in a key range that does not start at key 0)
+            // still has m = -inf and only -inf scores: keep -inf - (-inf) out of the exponent
+            const float mref = (m == -INFINITY) ? 0.f : m;
 #pragma unroll
             for (int i = 0; i < 16; i += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -m));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(s[i + 1], sl2, -m));
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s[i], sl2, -mref));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(s[i + 1], sl2, -mref));
                 ps0 += p0;
                 ps1 += p1;
                 cv.h[i >> 1] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
@@ -742,19 +823,30 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks].v));   // q landed before the loop
 
-    for (int kt = 0; kt < n_tiles; ++kt) {
-        // this thread's 4 loads of tile kt are older than those of tiles kt+1 and kt+2
-        if (kt + 2 < n_tiles) KUN_WAIT_VMCNT(8);
-        else if (kt + 1 < n_tiles) KUN_WAIT_VMCNT(4);
+    for (int j = 0; j < nt; ++j) {
+        // this thread's 4 loads of tile j are older than those of tiles j+1 and j+2
+        if (j + 2 < nt) KUN_WAIT_VMCNT(8);
+        else if (j + 1 < nt) KUN_WAIT_VMCNT(4);
         else KUN_WAIT_VMCNT(0);
-        __builtin_amdgcn_s_barrier();                  // tile kt complete in LDS; everybody has left tile kt-1
-        if (stager && kt + AHEAD < n_tiles) issue(kt + AHEAD);   // into the stage tile kt-1 used
-        compute(kt, &ring[kt % NSTAGE][0]);
+        __builtin_amdgcn_s_barrier();                  // tile j complete in LDS; everybody has left tile j-1
+        if (stager && j + AHEAD < nt) issue(j + AHEAD);          // into the stage tile j-1 used
+        compute(kt0 + j, &ring[j % NSTAGE][0]);
     }
 
     const float lt = l + __shfl_xor(l, 32);
+    if (part_slot >= 0) {
+        // one key range of a split item: unnormalised O^T ([dim][row]: a register's 32 lanes are 32
+        // consecutive rows) and the rows' (m, l), for prefill_merge_kernel
+        const size_t wg_rec = (size_t)part_slot * a.Hkv + kvh;
+        float* po = a.part_o + wg_rec * (D * kSplitRows) + wave * ROWS_W + n;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) po[(32 * dt + 8 * (i >> 2) + 4 * jh + (i & 3)) * kSplitRows] = o[dt][i];
+        if (jh == 0) *(float2*)(a.part_ml + (wg_rec * kSplitRows + wave * ROWS_W + n) * 2) = make_float2(m, lt);
+    }
     const float inv = 1.0f / lt;
-    if (live_row) {
+    if (live_row && part_slot < 0) {
         char* orow = (char*)a.out + (((size_t)(qs + pos)) * a.Hq + kvh * G + g_head) * (D * 2);
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
@@ -771,6 +863,56 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     }
 }
 
+
+// Rows of a split item from the partial results of its key ranges: m = max m_i, l = sum l_i 2^(m_i - m),
+// o = sum o_i 2^(m_i - m) / l.  One workgroup per (split item, kv head, 16 dims), one thread per row.
+constexpr int kMergeDims = 16;
+__global__ __launch_bounds__(kSplitRows) void prefill_merge_kernel(const PrefillArgs a, int G) {
+    constexpr int NDC = D / kMergeDims;
+    const int dc = blockIdx.x % NDC;
+    const int si = blockIdx.x / NDC / a.Hkv, kvh = blockIdx.x / NDC % a.Hkv;
+    if (si >= *a.n_split_items) return;
+    const int4 it = a.split_items[si];
+    const int chunk = it.x, qt = it.y, nsplit = it.z, slot0 = it.w;
+    const int qs = a.q_start[chunk];
+    const int c = a.q_start[chunk + 1] - qs;
+    const int row = threadIdx.x;
+    const int pos = qt * (kSplitRows / G) + row / G, head = row % G;
+    if (pos >= c) return;
+    float w[kMaxSplit];
+    float M = -INFINITY;
+    for (int sp = 0; sp < nsplit; ++sp)
+        M = fmaxf(M, a.part_ml[((((size_t)slot0 + sp) * a.Hkv + kvh) * kSplitRows + row) * 2]);
+    float l = 0.f;
+#pragma unroll
+    for (int sp = 0; sp < kMaxSplit; ++sp) {
+        w[sp] = 0.f;
+        if (sp < nsplit) {
+            const size_t rec = (((size_t)slot0 + sp) * a.Hkv + kvh) * kSplitRows + row;
+            const float mi = a.part_ml[rec * 2];
+            w[sp] = (mi == -INFINITY) ? 0.f : exp2f(mi - M);      // -inf: the row sees no key of this range
+            l += w[sp] * a.part_ml[rec * 2 + 1];
+        }
+    }
+    const float inv = 1.0f / l;
+    char* orow = (char*)a.out + (((size_t)(qs + pos)) * a.Hq + kvh * G + head) * (D * 2);
+    for (int d0 = dc * kMergeDims; d0 < (dc + 1) * kMergeDims; d0 += 8) {
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int sp = 0; sp < kMaxSplit; ++sp) {
+            if (sp < nsplit) {
+                const float* po = a.part_o + (((size_t)slot0 + sp) * a.Hkv + kvh) * (D * kSplitRows) + row;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] += w[sp] * po[(d0 + e) * kSplitRows];
+            }
+        }
+        union { bf16x2 h[4]; uint4 u; } v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            v.h[e] = __builtin_convertvector((f32x2){acc[2 * e] * inv, acc[2 * e + 1] * inv}, bf16x2);
+        *(uint4*)(orow + d0 * 2) = v.u;
+    }
+}
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -837,15 +979,46 @@ void launch_prefill(const PrefillArgs& a, dim3 grid, TileShape t, hipStream_t st
 
 }  // namespace
 
+namespace {
+
+// Workspace of the MFMA path: header (256 B: n_items, the 8 fetch counters at +64, n_split_items at
+// +128), the item list, and -- only when the launch is small enough to be split -- the per-item
+// split records, the list of split items and the partial results of the key ranges.
+struct PrefillLayout {
+    bool may_split;
+    int max_items, cap_entries;
+    size_t off_items, off_split_info, off_split_items, off_part_ml, off_part_o, total;
+};
+
+PrefillLayout prefill_layout(const kun_kv_pool* p, int n_chunks, int Hq, int total_new_tokens, int pos_per_tile) {
+    PrefillLayout lay;
+    const int G = Hq / p->Hkv;
+    const int pos_ring = kSplitRows / G;                   // positions per workgroup of the kernels that can split
+    // at least total / pos items exist, so a launch with that many workgroups or more is never split
+    lay.may_split = (int64_t)(total_new_tokens / pos_ring) * p->Hkv < kSplitTarget;
+    lay.max_items = total_new_tokens / pos_per_tile + n_chunks;
+    lay.cap_entries = lay.may_split ? 2 * lay.max_items + kSplitTarget / p->Hkv + 1 : lay.max_items;
+    size_t o = 256;
+    lay.off_items = o;        o += align256(sizeof(int2) * (size_t)lay.cap_entries);
+    lay.off_split_info = o;   if (lay.may_split) o += align256(sizeof(int2) * (size_t)lay.cap_entries);
+    lay.off_split_items = o;  if (lay.may_split) o += align256(sizeof(int4) * (size_t)(kSplitTarget + 1));
+    const size_t part_wgs = 2 * (size_t)kSplitTarget + p->Hkv;       // (key range, kv head) workgroups of split items
+    lay.off_part_ml = o;      if (lay.may_split) o += align256(sizeof(float) * 2 * kSplitRows * part_wgs);
+    lay.off_part_o = o;       if (lay.may_split) o += align256(sizeof(float) * D * kSplitRows * part_wgs);
+    lay.total = o;
+    return lay;
+}
+
+}  // namespace
+
 extern "C" size_t kun_prefill_workspace_bytes(const kun_kv_pool* p, int n_chunks, int Hq, int total_new_tokens) {
     if (!prefill_shape_ok(p, n_chunks, Hq, total_new_tokens)) return 0;
     if (!mfma_shape(p))                                    // rows as decode requests: two int32 per row + its plan
         return 256 + 2 * align256(sizeof(int32_t) * (size_t)total_new_tokens) +
                kun_attend_rows_workspace_bytes(total_new_tokens);
     const int G = Hq / p->Hkv;
-    const int pos_min = 128 / (G > 0 ? G : 1);             // smallest tile (NQ = 1)
-    const size_t max_items = (size_t)total_new_tokens / (pos_min > 0 ? pos_min : 1) + n_chunks;
-    return 256 + align256(sizeof(int2) * max_items);
+    const int pos_min = 128 / (G > 0 ? G : 1);             // smallest tile of any variant (4 waves, NQ = 1)
+    return prefill_layout(p, n_chunks, Hq, total_new_tokens, pos_min).total;
 }
 
 namespace {
@@ -878,6 +1051,9 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     const bool persistent = shape.persistent;
     if (persistent && max_workgroups == 0) max_workgroups = device_compute_units();
     const int pos_per_tile = rows_per_wg(shape) / G;
+    const PrefillLayout lay = prefill_layout(p, n_chunks, Hq, total_new_tokens, pos_per_tile);
+    const bool can_split = lay.may_split && shape.ring && shape.nw == 8;     // the 8-wave ring kernels only
+    char* ws = (char*)workspace;
     PrefillArgs a;
     a.rt = p->ranges;
     a.q = q;
@@ -885,23 +1061,30 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     a.q_start = q_start;
     a.prior = prior_len;
     a.table = block_table;
-    a.n_items = (int32_t*)workspace;
-    a.next_item = (int32_t*)workspace + 16;
-    a.items = (int2*)((char*)workspace + 256);
+    a.n_items = (int32_t*)ws;
+    a.next_item = (int32_t*)ws + 16;
+    a.n_split_items = (int32_t*)ws + 32;
+    a.items = (int2*)(ws + lay.off_items);
+    a.split_info = can_split ? (const int2*)(ws + lay.off_split_info) : nullptr;
+    a.split_items = (int4*)(ws + lay.off_split_items);
+    a.part_ml = (float*)(ws + lay.off_part_ml);
+    a.part_o = (float*)(ws + lay.off_part_o);
     a.max_blocks = max_blocks;
     a.n_chunks = n_chunks;
     a.Hkv = p->Hkv;
     a.Hq = Hq;
-    a.max_items = total_new_tokens / pos_per_tile + n_chunks;
+    a.max_items = lay.max_items;
     a.scale_log2 = scale * kLog2e;
     a.block_bytes = (unsigned)p->block_bytes;
     a.page_bytes = (unsigned)p->page_bytes;
     hipStream_t st = (hipStream_t)stream;
 
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, q_start, prior_len, n_chunks,
-                       pos_per_tile, a.max_items, a.n_items, a.next_item, a.items);
+                       pos_per_tile, a.max_items, a.n_items, a.next_item, a.items, p->Hkv,
+                       can_split ? kSplitTarget : 0, lay.cap_entries, (int2*)(ws + lay.off_split_info), a.split_items,
+                       a.n_split_items);
     KUN_HIP_CHECK_LAUNCH();
-    size_t wgs = (size_t)a.max_items * p->Hkv;
+    size_t wgs = (size_t)(can_split ? lay.cap_entries : lay.max_items) * p->Hkv;
     if (persistent) {
         const size_t lim = max_workgroups < 8 ? 8 : (size_t)(max_workgroups & ~7);
         if (wgs > lim) wgs = lim;
@@ -915,6 +1098,12 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
         default: launch_prefill<8>(a, grid, shape, st); break;
     }
     KUN_HIP_CHECK_LAUNCH();
+    if (can_split) {
+        hipLaunchKernelGGL(prefill_merge_kernel,
+                           dim3((unsigned)((kSplitTarget / p->Hkv + 1) * p->Hkv * (D / kMergeDims))), dim3(kSplitRows), 0,
+                           st, a, G);
+        KUN_HIP_CHECK_LAUNCH();
+    }
     return KUN_OK;
 }
 

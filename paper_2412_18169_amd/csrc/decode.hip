@@ -504,26 +504,40 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 // ---------------------------------------------------------------------------------------------
 // 3. merge: one workgroup per (request, kv head); only requests with more than one partition
 // ---------------------------------------------------------------------------------------------
+constexpr int kMergeSlices = 4;      // workgroups per (request, kv head): the chain of dependent loads per thread is short
 template <typename T>
 __global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a, int D) {
-    const int seq = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
+    const int slice = blockIdx.x % kMergeSlices;
+    const int seq = blockIdx.x / kMergeSlices / a.Hkv, kvh = blockIdx.x / kMergeSlices % a.Hkv;
     const int L = a.ctx_len[seq];
     const int nparts = (L + a.part_tokens - 1) / a.part_tokens;
     if (nparts <= 1) return;
     const int first = a.seq_first[seq];
     if (first + nparts > a.max_items) return;   // the caller's bound on sum(ctx_len) was too small
     const int G = a.G;
-    for (int idx = threadIdx.x; idx < G * D; idx += blockDim.x) {
+    for (int idx = slice * 256 + threadIdx.x; idx < G * D; idx += kMergeSlices * 256) {
         const int g = idx / D, j = idx - g * D;
+        const size_t rec0 = (((size_t)first) * a.Hkv + kvh) * G + g, step = (size_t)a.Hkv * G;
         float M = -INFINITY;
-        for (int p = 0; p < nparts; ++p)
-            M = fmaxf(M, a.part_ml[((((size_t)first + p) * a.Hkv + kvh) * G + g) * 2]);
+        for (int p = 0; p < nparts; ++p) M = fmaxf(M, a.part_ml[(rec0 + p * step) * 2]);
         float l = 0.f, acc = 0.f;
-        for (int p = 0; p < nparts; ++p) {
-            const size_t rec = (((size_t)first + p) * a.Hkv + kvh) * G + g;
-            const float f = exp2f(a.part_ml[rec * 2] - M);
-            l += f * a.part_ml[rec * 2 + 1];
-            acc += f * a.part_acc[rec * D + j];
+        int p = 0;
+        for (; p + 1 < nparts; p += 2) {                   // two independent records per step
+            const size_t r0 = rec0 + p * step, r1 = r0 + step;
+            const float m0 = a.part_ml[r0 * 2], m1 = a.part_ml[r1 * 2];
+            const float l0 = a.part_ml[r0 * 2 + 1], l1 = a.part_ml[r1 * 2 + 1];
+            const float a0 = a.part_acc[r0 * D + j], a1 = a.part_acc[r1 * D + j];
+            const float f0 = exp2f(m0 - M), f1 = exp2f(m1 - M);
+            l += f0 * l0;
+            acc += f0 * a0;
+            l += f1 * l1;
+            acc += f1 * a1;
+        }
+        if (p < nparts) {
+            const size_t r0 = rec0 + p * step;
+            const float f0 = exp2f(a.part_ml[r0 * 2] - M);
+            l += f0 * a.part_ml[r0 * 2 + 1];
+            acc += f0 * a.part_acc[r0 * D + j];
         }
         T* o = (T*)a.out + ((size_t)seq * a.Hkv * G + (size_t)kvh * G + g) * D + j;
         Elem<T>::store(o, acc / l);
@@ -730,7 +744,7 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     if (rc != KUN_OK) return rc;
     KUN_HIP_CHECK_LAUNCH();
 
-    const dim3 mgrid((unsigned)((size_t)S * p->Hkv));
+    const dim3 mgrid((unsigned)((size_t)S * p->Hkv * kMergeSlices));
     if (p->dtype == KUN_BF16)
         hipLaunchKernelGGL(decode_merge_kernel<bf16_t>, mgrid, dim3(256), 0, st, a, p->d);
     else

@@ -1,10 +1,11 @@
 // Stand-alone measurement of what the two rooflines of the paged-attention path can reach on the
 // GPU at hand: it is not part of libkun.so and shares nothing with it.
 //
-//   1. HBM streaming read: a 16 GiB buffer read with grid-stride 16-byte loads, and read as
-//      scattered 8 KiB pieces at 64 KiB granularity (the footprint of one KV head's K + V^T page
-//      inside a block of the pool).  This is the ceiling of the decode step, which the paper
-//      classes as memory-bound (section 2.1).
+//   1. HBM streaming read: 16 GiB read with grid-stride 16-byte loads, and 17 GB read as scattered
+//      8 KiB pieces at 64 KiB granularity (the footprint of one KV head's K + V^T page inside a
+//      block of the pool) out of a 16 GiB and out of a 150 GiB buffer, each with ordinary and with
+//      non-temporal loads.  This is the ceiling of the decode step, which the paper classes as
+//      memory-bound (section 2.1).
 //   2. MFMA issue rate of v_mfma_f32_32x32x16_bf16 at two waves per SIMD with constant and with
 //      random operands (the clock the chip sustains depends on how much the operands toggle).
 //   3. The skeleton of a chunked-prefill tile loop (compute-bound per section 2.1): per 64-key
@@ -62,45 +63,68 @@ static float time_ms(F launch, int reps) {
 }
 
 // ---------------------------------------------------------------- 1. HBM read
-__global__ __launch_bounds__(256) void read_linear(const uint4* __restrict__ p, size_t n, unsigned* sink) {
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool NT>     // NT: non-temporal loads (data that is read once)
+__global__ __launch_bounds__(256) void read_linear(const u32x4* __restrict__ p, size_t n, unsigned* sink) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     unsigned s = 0;
-    for (; i + 3 * stride < n; i += 4 * stride) {
-        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
-        s += a.x ^ b.y ^ c.z ^ d.w;
+    for (; i + 7 * stride < n; i += 8 * stride) {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = NT ? __builtin_nontemporal_load(p + i + u * stride) : p[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u].x ^ v[u].w;
     }
     for (; i < n; i += stride) s += p[i].x;
     if (s == 0x12345678u) sink[0] = s;
 }
 
-// one workgroup reads 8 KiB (two 4 KiB halves) of head `h` of the 64 KiB block with a hashed id
-__global__ __launch_bounds__(256) void read_pages(const uint4* __restrict__ p, size_t nblocks, unsigned* sink) {
+// The decode kernel's pattern: a workgroup of 4 waves walks `blocks_per_wg` hashed 64 KiB blocks of the
+// buffer for one of 8 KV heads; a wave takes two blocks per step and reads the head's 8 KiB page (K +
+// V^T) of each with sixteen 16-byte loads per lane.
+template <bool NT>
+__global__ __launch_bounds__(256) void read_pages(const u32x4* __restrict__ p, size_t nblocks, int blocks_per_wg,
+                                                  unsigned* sink) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int head = blockIdx.x & 7;
     unsigned s = 0;
-    for (size_t w = blockIdx.x; w < nblocks * 8; w += gridDim.x) {
-        const size_t blk = (w / 8 * 2654435761ull) % nblocks, head = w % 8;
-        const uint4* page = p + blk * 4096 + head * 512;
-        const uint4 a = page[threadIdx.x], c = page[threadIdx.x + 256];
-        s += a.x ^ c.y;
+    const size_t first = (size_t)(blockIdx.x >> 3) * blocks_per_wg;
+    for (int b = wave * 2; b < blocks_per_wg; b += 8) {
+        u32x4 v[16];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const size_t blk = ((first + b + h) * 2654435761ull) % nblocks;
+            const u32x4* page = p + blk * 4096 + head * 512 + lane;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[8 * h + u] = NT ? __builtin_nontemporal_load(page + u * 64) : page[u * 64];
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) s += v[u].x ^ v[u].w;
     }
     if (s == 0x12345678u) sink[0] = s;
 }
 
-static void run_hbm() {
-    const size_t bytes = (size_t)16 << 30, n = bytes / 16, nblocks = bytes / 65536;
-    uint4* buf;
+static void run_hbm(size_t gib) {
+    const size_t bytes = gib << 30, n = bytes / 16, nblocks = bytes / 65536;
+    u32x4* buf;
     unsigned* sink;
     CK(hipMalloc(&buf, bytes));
     CK(hipMalloc(&sink, 4));
     CK(hipMemset(buf, 1, bytes));
-    for (int grid : {2048, 8192, 16384}) {
-        const float ms = time_ms([&] { read_linear<<<grid, 256>>>(buf, n, sink); }, 5);
-        std::printf("hbm linear read, %5d workgroups:        %.0f GB/s\n", grid, bytes / ms / 1e6);
-    }
-    for (int grid : {2048, 8192, 32768}) {
-        const float ms = time_ms([&] { read_pages<<<grid, 256>>>(buf, nblocks, sink); }, 5);
-        std::printf("hbm scattered 8 KiB pages, %5d workgroups: %.0f GB/s\n", grid, bytes / ms / 1e6);
-    }
+    const size_t lin = bytes < ((size_t)16 << 30) ? bytes : (size_t)16 << 30;      // linear: the first 16 GiB
+    const float t0 = time_ms([&] { read_linear<false><<<16384, 256>>>(buf, lin / 16, sink); }, 5);
+    const float t1 = time_ms([&] { read_linear<true><<<16384, 256>>>(buf, lin / 16, sink); }, 5);
+    std::printf("hbm linear read of 16 GiB, %zu GiB buffer:              %.0f GB/s | non-temporal loads %.0f GB/s\n", gib,
+                lin / t0 / 1e6, lin / t1 / 1e6);
+    const int bpw = 64;                                    // 64 blocks = 1024 tokens per workgroup
+    const size_t wg_groups = 260000 / bpw;                 // about 17 GB, the 70B-shaped decode step
+    const double page_bytes = (double)wg_groups * bpw * 8 * 8192;
+    const float t2 = time_ms([&] { read_pages<false><<<(unsigned)(wg_groups * 8), 256>>>(buf, nblocks, bpw, sink); }, 3);
+    const float t3 = time_ms([&] { read_pages<true><<<(unsigned)(wg_groups * 8), 256>>>(buf, nblocks, bpw, sink); }, 3);
+    std::printf("hbm scattered 8 KiB pages (17 GB of a %zu GiB buffer):  %.0f GB/s | non-temporal loads %.0f GB/s\n", gib,
+                page_bytes / t2 / 1e6, page_bytes / t3 / 1e6);
     CK(hipFree(buf));
     CK(hipFree(sink));
 }
@@ -285,7 +309,10 @@ int main(int argc, char** argv) {
     CK(hipMalloc(&src, 1024 * 8192));
     if (all || !std::strcmp(what, "mfma")) run_mfma(out, src);
     if (all || !std::strcmp(what, "tile")) run_tile(out, src);
-    if (all || !std::strcmp(what, "hbm")) run_hbm();
+    if (all || !std::strcmp(what, "hbm")) {
+        run_hbm(16);
+        run_hbm(150);     // the size of the largest pool: scattered pages now also miss in the TLBs
+    }
     CK(hipFree(out));
     CK(hipFree(src));
     return 0;

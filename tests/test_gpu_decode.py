@@ -124,6 +124,48 @@ def test_batch_larger_than_one_pass_of_the_plan_kernel():
     dw.close()
 
 
+def test_empty_calls_and_refused_arguments_leave_outputs_alone():
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
+    w = synth.custom_workload("empty", sh, [0, 0, 0], chunks=[(5, 0)], extra_blocks=4)
+    dw = DeviceWorkload(w)
+    dw.out_dec.fill_(3.0)
+    out = dw.decode()                                   # every request has ctx_len 0
+    torch.cuda.synchronize()
+    assert torch.all(out == 3.0)
+    dev = dw.dev
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
+    z = torch.zeros(4, dtype=torch.int32, device=dev)
+    # S = 0, n_chunks = 0, T = 0: nothing is launched, nothing is dereferenced
+    kun.kun_paged_decode(dw.pool, None, None, None, 1, None, 0, sh.Hq, sh.scale, 0, None, 0)
+    kun.kun_paged_prefill_chunk(dw.pool, None, None, None, None, None, 1, 0, sh.Hq, 0, sh.scale, None, 0)
+    kun.kun_kv_append(dw.pool, None, None, None, None, 0, None, 1)
+    kun.kun_slot_map(dw.pool, None, None, 0, None, 1, 0, None, None, None)
+    dw.out_pre.fill_(5.0) if dw.n_chunks and dw.out_pre.numel() else None
+    dw.prefill()                                        # one chunk with c = 0
+    torch.cuda.synchronize()
+
+    def status(fn, *a):
+        with pytest.raises(kun.KunError) as e:
+            fn(*a)
+        return e.value.status
+    q, o, tab, ln = dw.q_dec, dw.out_dec, dw.dec_table, dw.dec_len
+    need = kun.kun_decode_workspace_bytes(dw.pool, 3, sh.Hq, 0)
+    assert need > 0 and need % 256 == 0
+    assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, sh.Hq, sh.scale, 0, ws, 256) == -6
+    assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, sh.Hq, sh.scale, 0, None, need) == -6
+    big = torch.empty(need + 512, dtype=torch.uint8, device=dev)
+    assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, sh.Hq, sh.scale, 0,
+                  big.data_ptr() + 8, need) == -6                                     # misaligned workspace
+    assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, 6, sh.scale, 0, big, need) == -8   # G = 3
+    assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, 7, sh.scale, 0, big, need) == -1   # 7 % 2
+    assert status(kun.kun_paged_decode, dw.pool, None, o, tab, tab.shape[1], ln, 3, sh.Hq, sh.scale, 0, big, need) == -1
+    assert status(kun.kun_paged_prefill_chunk, dw.pool, q, o, z, z, tab, tab.shape[1], 1, 6, 4, sh.scale, big, need) == -8
+    assert status(kun.kun_slot_map, dw.pool, z, z, 2, tab, tab.shape[1], 5, z, z, z) == -1           # kv head 5 of 2
+    torch.cuda.synchronize()
+    assert torch.all(dw.out_dec == 3.0)
+    dw.close()
+
+
 def test_length_one_returns_v_exactly_and_zero_length_is_skipped():
     for dtype, d in (("bf16", 128), ("f32", 64)):
         sh = synth.LayerShape(Hq=8, Hkv=2, d=d, B=16, dtype=dtype)

@@ -235,6 +235,35 @@ def test_pool_extension_keeps_resident_outputs_bit_identical():
     dw.close(); dw2.close()
 
 
+def test_extend_between_enqueued_calls_disturbs_neither():
+    # the range table travels with every launch: a call enqueued before kun_kv_pool_extend keeps the
+    # table it was given, a call enqueued after sees the new range, no synchronisation in between
+    os.environ["KUN_DECODE_PART"] = "256"
+    sh = synth.SHAPE_8B
+    rng = np.random.default_rng(8)
+    lens = synth.lognormal_lengths(rng, 48, median=600, sigma=0.7, lo=16, hi=4000)
+    w = synth.Workload("inflight", 0, 78, sh, lens, [], [])
+    n = int(synth.blocks_needed(lens, 16).sum())
+    w.range_blocks = [n // 2, n - n // 2]
+    resident = synth.assign_blocks_phased(w)
+    dw = DeviceWorkload(w, n_ranges_at_create=1)
+    ref_a = dw.decode(resident[0]).clone()
+    dw.extend_next()
+    ref_b = dw.decode(resident[1]).clone()
+    torch.cuda.synchronize()
+    dw2 = DeviceWorkload(w, n_ranges_at_create=1)
+    out_a = torch.empty_like(dw2.out_dec)
+    dw2.decode(resident[0])
+    out_a.copy_(dw2.out_dec, non_blocking=True)          # enqueued behind the first call
+    dw2.extend_next()                                    # host only; the first call may still be running
+    out_b = dw2.decode(resident[1])
+    torch.cuda.synchronize()
+    assert torch.equal(out_a[:resident[0]], ref_a[:resident[0]])
+    assert torch.equal(out_b[:resident[1]], ref_b[:resident[1]])
+    check_decode(dw2, seqs=resident[1], out=out_b)
+    dw.close(); dw2.close()
+
+
 def test_resolve_matches_oracle_on_device_pool():
     small = synth.Workload("r", 0, 1, synth.SHAPE_8B, np.array([100, 333, 20], dtype=np.int32), [], [50, 20, 30])
     synth.assign_blocks_scattered(small)

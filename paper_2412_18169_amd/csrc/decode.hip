@@ -34,7 +34,7 @@ struct DecodeArgs {
     const int32_t* row_of_seq;  // optional: block-table row of each request (NULL: request s uses row s)
     int32_t* n_items;        // workspace: number of work items (written by plan)
     int32_t* seq_first;      // workspace: [S + 1] first item of each request
-    int2* items;             // workspace: (request, partition)
+    int4* items;             // workspace: (request, partition, the request's context length, 0)
     float* part_ml;          // workspace: [item, kvh, G, 2]  (m in log2 units, l)
     float* part_acc;         // workspace: [item, kvh, G, d]
     int max_blocks;
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(1024) void decode_plan_kernel(const int32_t* __rest
                                                          int part_tokens, int max_items,
                                                          int32_t* __restrict__ n_items,
                                                          int32_t* __restrict__ seq_first,
-                                                         int2* __restrict__ items) {
+                                                         int4* __restrict__ items) {
     __shared__ int wave_tot[16];
     __shared__ int carry_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -60,9 +60,9 @@ __global__ __launch_bounds__(1024) void decode_plan_kernel(const int32_t* __rest
     __syncthreads();
     for (int s0 = 0; s0 < S; s0 += 1024) {
         const int s = s0 + tid;
-        int np = 0;
+        int np = 0, L = 0;
         if (s < S) {
-            int L = ctx_len[s];
+            L = ctx_len[s];
             np = L > 0 ? (L + part_tokens - 1) / part_tokens : 0;
         }
         int incl = np;                       // inclusive scan inside the wave
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(1024) void decode_plan_kernel(const int32_t* __rest
         if (s < S) {
             seq_first[s] = first;
             for (int p = 0; p < np; ++p)
-                if (first + p < max_items) items[first + p] = make_int2(s, p);
+                if (first + p < max_items) items[first + p] = make_int4(s, p, L, 0);
         }
         __syncthreads();
         if (tid == 1023) carry_s = first + np;
@@ -183,9 +183,9 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
 
     const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
     if (item >= *a.n_items) return;
-    const int2 it2 = a.items[item];
-    const int seq = it2.x, part = it2.y;
-    const int L = a.ctx_len[seq];
+    const int4 it4 = a.items[item];                    // the length rides along: one dependent load less
+    const int seq = it4.x, part = it4.y;
+    const int L = it4.z;
     const int nparts = (L + a.part_tokens - 1) / a.part_tokens;
     const int t0 = part * a.part_tokens;
     const int t1 = min(L, t0 + a.part_tokens);
@@ -327,10 +327,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
     const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
     if (item >= *a.n_items) return;
-    const int2 it2 = a.items[item];
-    const int seq = it2.x, part = it2.y;
+    const int4 it4 = a.items[item];                    // the length rides along: one dependent load less
+    const int seq = it4.x, part = it4.y;
     const int G = a.G;
-    const int L = a.ctx_len[seq];
+    const int L = it4.z;
     const int nparts = (L + a.part_tokens - 1) / a.part_tokens;
     const int t0 = part * a.part_tokens;
     const int t1 = min(L, t0 + a.part_tokens);
@@ -594,7 +594,7 @@ DecodeLayout layout_for(const kun_kv_pool* p, int S, int Hq, int64_t ub, int P) 
     lay.max_items = (int)(mi > INT32_MAX / 2 ? INT32_MAX / 2 : mi);
     size_t o = 256;
     lay.off_first = o; o += align256(sizeof(int32_t) * ((size_t)S + 1));
-    lay.off_items = o; o += align256(sizeof(int2) * (size_t)lay.max_items);
+    lay.off_items = o; o += align256(sizeof(int4) * (size_t)lay.max_items);
     lay.off_ml = o;    o += align256(sizeof(float) * 2 * (size_t)lay.max_items * p->Hkv * G);
     lay.off_acc = o;   o += align256(sizeof(float) * (size_t)lay.max_items * p->Hkv * G * p->d);
     lay.total = o;
@@ -620,10 +620,11 @@ int launch_generic(const DecodeArgs& a, dim3 grid, hipStream_t st) {
 
 // every row is its own request with one partition: item t = (t, 0)
 __global__ __launch_bounds__(256) void rows_plan_kernel(int T, int32_t* __restrict__ n_items,
-                                                        int32_t* __restrict__ seq_first, int2* __restrict__ items) {
+                                                        int32_t* __restrict__ seq_first, int4* __restrict__ items,
+                                                        const int32_t* __restrict__ ctx_len) {
     for (int t = blockIdx.x * blockDim.x + threadIdx.x; t <= T; t += gridDim.x * blockDim.x) {
         seq_first[t] = t;
-        if (t < T) items[t] = make_int2(t, 0);
+        if (t < T) items[t] = make_int4(t, 0, ctx_len[t], 0);
         if (t == 0) *n_items = T;
     }
 }
@@ -631,7 +632,7 @@ __global__ __launch_bounds__(256) void rows_plan_kernel(int T, int32_t* __restri
 }  // namespace
 
 size_t kun_attend_rows_workspace_bytes(int T) {
-    return 256 + align256(sizeof(int32_t) * ((size_t)T + 1)) + align256(sizeof(int2) * (size_t)T);
+    return 256 + align256(sizeof(int32_t) * ((size_t)T + 1)) + align256(sizeof(int4) * (size_t)T);
 }
 
 int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, const int32_t* table, int max_blocks,
@@ -647,7 +648,7 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
     a.row_of_seq = row_of_seq;
     a.n_items = (int32_t*)ws;
     a.seq_first = (int32_t*)(ws + 256);
-    a.items = (int2*)(ws + 256 + align256(sizeof(int32_t) * ((size_t)T + 1)));
+    a.items = (int4*)(ws + 256 + align256(sizeof(int32_t) * ((size_t)T + 1)));
     a.part_ml = nullptr;          // one partition per row: outputs are written directly
     a.part_acc = nullptr;
     a.max_blocks = max_blocks;
@@ -661,7 +662,7 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
     a.page_bytes = (unsigned)p->page_bytes;
     const int nb = (T + 256) / 256;
     hipLaunchKernelGGL(rows_plan_kernel, dim3((unsigned)(nb < 1024 ? nb : 1024)), dim3(256), 0, st, T, a.n_items,
-                       a.seq_first, a.items);
+                       a.seq_first, a.items, ctx_len);
     KUN_HIP_CHECK_LAUNCH();
     const dim3 grid((unsigned)((size_t)T * p->Hkv));
     int rc;
@@ -716,7 +717,7 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     a.row_of_seq = nullptr;
     a.n_items = (int32_t*)ws;
     a.seq_first = (int32_t*)(ws + lay.off_first);
-    a.items = (int2*)(ws + lay.off_items);
+    a.items = (int4*)(ws + lay.off_items);
     a.part_ml = (float*)(ws + lay.off_ml);
     a.part_acc = (float*)(ws + lay.off_acc);
     a.max_blocks = max_blocks;

@@ -182,8 +182,9 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
     __shared__ float sm_acc[NW * G * D];
 
     const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
-    if (item >= *a.n_items) return;
+    const int n_items = *a.n_items;                    // both loads go out together: the list is as long as the grid
     const int4 it4 = a.items[item];                    // the length rides along: one dependent load less
+    if (item >= n_items) return;
     const int seq = it4.x, part = it4.y;
     const int L = it4.z;
     const int nparts = (L + a.part_tokens - 1) / a.part_tokens;
@@ -326,8 +327,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     __shared__ float sm_acc[NW * 8 * D];      // G <= 8 heads kept (G <= 8 is enforced on the host)
 
     const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
-    if (item >= *a.n_items) return;
+    const int n_items = *a.n_items;                    // both loads go out together: the list is as long as the grid
     const int4 it4 = a.items[item];                    // the length rides along: one dependent load less
+    if (item >= n_items) return;
     const int seq = it4.x, part = it4.y;
     const int G = a.G;
     const int L = it4.z;

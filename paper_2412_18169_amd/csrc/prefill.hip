@@ -519,7 +519,7 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
         wi = s_next;
     }
     const int item = wi / a.Hkv, kvh = wi % a.Hkv;
-    if (item >= *a.n_items) return;
+    if (item >= *a.n_items) return;                    // (fetched indices can run past the list's capacity)
     const int2 it2 = a.items[item];
     const int chunk = it2.x, qt = it2.y;
     const int p = a.prior[chunk];

@@ -160,3 +160,37 @@ def test_slot_map_matches_oracle_for_every_token(dtype, d):
     for h in (0, 3):
         check_slot_map(dw, seqs, poss, kv_head=h)
     dw.close()
+
+
+def test_step_captured_in_a_hip_graph_replays_bit_identically():
+    # append + prefill + decode only enqueue kernels (no allocation, no memset nodes), so a step can be
+    # captured once and replayed; every replay, with eager work in between, gives the eager bits
+    sh = synth.SHAPE_8B
+    w = synth.custom_workload("graph", sh, [900, 3000, 17, 1500, 64] * 6, chunks=[(0, 300), (1024, 512), (300, 100)],
+                              extra_blocks=4, range_fracs=(0.5, 0.5))
+    dw = DeviceWorkload(w)
+    ref_p = dw.prefill().clone()                          # also sizes the workspaces before the capture
+    ref_d = dw.decode().clone()
+    k, v = synth.kv_logical(w, 0, 899, 900, dw.dev)
+    seq_of = torch.zeros(1, dtype=torch.int32, device=dw.dev)
+    pos_of = torch.full((1,), 899, dtype=torch.int32, device=dw.dev)
+    table = torch.from_numpy(w.table_array(range(len(w.seq_lens)))).to(dw.dev)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(g, stream=side):
+        kun.kun_kv_append(dw.pool, k, v, seq_of, pos_of, 1, table, table.shape[1])
+        dw.prefill()
+        dw.decode()
+    for rep in range(4):
+        dw.out_pre.fill_(float("nan"))
+        dw.out_dec.fill_(float("nan"))
+        if rep % 2:
+            dw.decode(5)                                  # eager work between replays, on the same buffers
+            dw.out_dec.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(dw.out_pre.view(torch.int16), ref_p.view(torch.int16)), rep
+        assert torch.equal(dw.out_dec.view(torch.int16), ref_d.view(torch.int16)), rep
+    dw.close()

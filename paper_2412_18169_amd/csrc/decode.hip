@@ -22,7 +22,7 @@
 
 namespace {
 
-constexpr int kBlock = 16;           // tokens per KV block (the only supported block size)
+constexpr int kBlock = 16;           // tokens per step of the kernels: a 16-token block, or a quarter of a 64-token block
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct DecodeArgs {
@@ -39,6 +39,7 @@ struct DecodeArgs {
     float* part_acc;         // workspace: [item, kvh, G, d]
     int max_blocks;
     int S, Hkv, G;
+    int B;                   // tokens per KV block: 16 or 64
     int part_tokens;         // tokens per partition, multiple of 32
     int max_items;
     float scale_log2;        // softmax scale * log2(e)
@@ -212,9 +213,14 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
     }
 
     const int32_t* trow = a.table + (size_t)(a.row_of_seq ? a.row_of_seq[seq] : seq) * a.max_blocks;
+    // b counts 16-token steps; with 64-token blocks a step is a quarter `sub` of block b / 4: its K rows
+    // are contiguous inside the page's K part, its V^T columns sit sub * 16 elements into every row
+    const int steps_per_block = a.B / kBlock;
     for (int b = t0 / kBlock + wave; b * kBlock < t1; b += NW) {
-        const int blk = __builtin_amdgcn_readfirstlane(trow[b]);
-        const char* page = kun_block_addr(a.rt, blk, a.block_bytes) + (size_t)kvh * a.page_bytes;
+        const int blk = __builtin_amdgcn_readfirstlane(trow[b / steps_per_block]);
+        const int sub = b % steps_per_block;
+        const char* page0 = kun_block_addr(a.rt, blk, a.block_bytes) + (size_t)kvh * a.page_bytes;
+        const char* page = page0 + (size_t)sub * kBlock * D * sizeof(T);
         const int tb = b * kBlock;
         // scores: s[g][it] for token tb + it * TPL + grp
         float s[G][NIT];
@@ -257,14 +263,14 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
             for (int i = 0; i < DPL; ++i) acc[g][i] *= alpha;
         }
         // acc[g][dim] += sum_t p[g][t] * V^T[dim][t]
-        const char* vpage = page + (size_t)kBlock * D * sizeof(T);
+        const char* vpage = page0 + ((size_t)a.B * D + sub * kBlock) * sizeof(T);
 #pragma unroll
         for (int i = 0; i < DPL; ++i) {
             const int dim = lane + 64 * i;
             float vrow[kBlock];
 #pragma unroll
             for (int c = 0; c < VLD; ++c) {
-                uint4 vv = load_stream16(vpage + ((size_t)dim * kBlock + c * EPL) * sizeof(T));
+                uint4 vv = load_stream16(vpage + ((size_t)dim * a.B + c * EPL) * sizeof(T));
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) {
                     const int t = c * EPL + e;
@@ -657,6 +663,7 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
     a.S = T;
     a.Hkv = p->Hkv;
     a.G = Hq / p->Hkv;
+    a.B = p->B;
     a.part_tokens = 1 << 30;
     a.max_items = T;
     a.scale_log2 = scale * kLog2e;
@@ -726,6 +733,7 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     a.S = S;
     a.Hkv = p->Hkv;
     a.G = G;
+    a.B = p->B;
     a.part_tokens = P;
     a.max_items = lay.max_items;
     a.scale_log2 = scale * kLog2e;
@@ -740,7 +748,7 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     const char* force = getenv("KUN_DECODE_KERNEL");     // "generic" forces the vector-ALU kernel
     const bool generic_only = force && force[0] == 'g';
     int rc = KUN_OK;
-    if (p->dtype == KUN_BF16 && p->d == 128 && !generic_only) {
+    if (p->dtype == KUN_BF16 && p->d == 128 && p->B == 16 && !generic_only) {
         int nw = 4;
         const char* e = getenv("KUN_DECODE_WAVES");
         if (e) nw = atoi(e);

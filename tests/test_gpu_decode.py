@@ -166,6 +166,41 @@ def test_empty_calls_and_refused_arguments_leave_outputs_alone():
     dw.close()
 
 
+@pytest.mark.parametrize("G,d,dtype", [(8, 128, "bf16"), (4, 128, "bf16"), (2, 64, "bf16"), (4, 64, "f32"), (1, 128, "f32")])
+def test_blocks_of_64_tokens(G, d, dtype):
+    # the paper's tuned block size (Section 5.1): decode, append and the slot map over 64-token blocks
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=64, dtype=dtype)
+    lens = [1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 511, 513, 777, 1024, 1500, 4100]
+    w = synth.custom_workload("b64", sh, lens, extra_blocks=3, range_fracs=(0.3, 0.2, 0.5))
+    dw = DeviceWorkload(w, fill=False)
+    # pages written by kun_kv_append (bit-exact against the oracle's append), then decode
+    seqs, poss, ks, vs = [], [], [], []
+    for s_ in range(len(lens)):
+        k, v = synth.kv_logical(w, s_, 0, lens[s_])
+        ks.append(k); vs.append(v)
+        seqs += [s_] * lens[s_]; poss += list(range(lens[s_]))
+    k_new, v_new = torch.cat(ks), torch.cat(vs)
+    seqs, poss = np.asarray(seqs, dtype=np.int32), np.asarray(poss, dtype=np.int32)
+    table = w.table_array(range(len(lens)))
+    opool = O.OraclePool([synth.to_host_bits(r).reshape(-1).copy() for r in dw.ranges], sh.Hkv, sh.d, sh.B, sh.dtype)
+    O.kv_append(opool, synth.to_host_bits(k_new), synth.to_host_bits(v_new), seqs, poss, table)
+    kun.kun_kv_append(dw.pool, k_new.cuda(), v_new.cuda(), torch.from_numpy(seqs).cuda(), torch.from_numpy(poss).cuda(),
+                      len(seqs), torch.from_numpy(table).cuda(), table.shape[1])
+    torch.cuda.synchronize()
+    for r in range(len(dw.ranges)):
+        assert np.array_equal(synth.to_host_bits(dw.ranges[r]).reshape(-1), opool.ranges[r], equal_nan=True)
+    for kernel in ("default", "generic"):
+        if kernel == "generic":
+            os.environ["KUN_DECODE_KERNEL"] = "generic"
+        for part in (None, "64", "256"):
+            if part:
+                os.environ["KUN_DECODE_PART"] = part
+            dw.out_dec.fill_(float("nan"))
+            check_decode(dw)
+            os.environ.pop("KUN_DECODE_PART", None)
+    dw.close()
+
+
 def test_length_one_returns_v_exactly_and_zero_length_is_skipped():
     for dtype, d in (("bf16", 128), ("f32", 64)):
         sh = synth.LayerShape(Hq=8, Hkv=2, d=d, B=16, dtype=dtype)

@@ -210,6 +210,29 @@ def test_few_query_tiles_after_long_contexts_split_their_keys(G, shape):
         dw.close()
 
 
+@pytest.mark.parametrize("G,d,dtype", [(8, 128, "bf16"), (4, 128, "bf16"), (1, 128, "bf16"), (2, 64, "f32")])
+def test_blocks_of_64_tokens(G, d, dtype):
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=64, dtype=dtype)
+    chunks = [(0, 1), (0, 17), (5, 1), (15, 16), (31, 64), (63, 65), (64, 129), (100, 200), (0, 300), (333, 77),
+              (700, 257), (1000, 31), (3000, 40)]
+    w = synth.custom_workload("b64", sh, [3], chunks=chunks, extra_blocks=3, range_fracs=(0.4, 0.6))
+    dw = DeviceWorkload(w)
+    dw.out_pre.fill_(float("nan"))
+    out = dw.prefill()
+    torch.cuda.synchronize()
+    got = out.double().cpu().numpy()
+    assert np.isfinite(got).all()
+    tol = 1e-5 if dtype == "f32" else TOL
+    for i, (p, c) in enumerate(w.chunks):
+        q0 = int(dw.q_start_host[i])
+        pool, tab = bridge.compact_pool(dw.ranges, w.range_blocks, [w.block_tables[w.S + i]], [p + c], sh.Hkv, sh.d,
+                                        sh.B, sh.dtype)
+        ref, _ = O.paged_prefill_chunk(pool, bridge.host_bits(dw.q_pre[q0:q0 + c]), tab[0], p, c, sh.Hq, sh.scale)
+        err = np.abs(got[q0:q0 + c] - ref).max()
+        assert err <= tol, f"chunk {i} (p={p}, c={c}): max abs err {err}"
+    dw.close()
+
+
 def test_empty_chunk_is_skipped_and_first_row_returns_v():
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     w = synth.custom_workload("pre0", sh, [3], chunks=[(0, 5), (7, 0), (0, 40)], extra_blocks=2)

@@ -43,6 +43,9 @@ def test_block_bytes_formula():
     p = kun.kun_kv_pool_create(BASE, 1 << 20, kun.KUN_F32, 2, 64, 16)
     assert kun.kun_kv_pool_block_bytes(p) == 16384 and kun.kun_kv_pool_num_blocks(p) == 64
     kun.kun_kv_pool_destroy(p)
+    p = kun.kun_kv_pool_create(BASE, 1 << 22, kun.KUN_BF16, 8, 128, 64)       # 64-token blocks
+    assert kun.kun_kv_pool_block_bytes(p) == 4 * BB and kun.kun_kv_pool_num_blocks(p) == 16
+    kun.kun_kv_pool_destroy(p)
 
 
 def test_growth_and_resolve_match_oracle_bit_exact():

@@ -299,7 +299,7 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
 }
 
 // ---------------------------------------------------------------------------------------------
-// 2b. MFMA partial kernel: bf16, head_dim 128, block 16, G <= 16.
+// 2b. MFMA partial kernel: bf16, head_dim 128, blocks of 16 or 64 tokens, G <= 8.
 //
 // Each wave walks PAIRS of blocks (32 tokens).  With lane = 16 * j + n:
 //   QK^T  S^T[token][head] = K[token][:] . Q[head][:]   as 2 tiles x 4 MFMA 16x16x32
@@ -325,9 +325,13 @@ struct PairLoads {
     uint4 v[8];      // [dim slice]
 };
 
-template <int NW>
+// R = 16-token steps per KV block (1: blocks of 16 tokens; 4: blocks of 64 tokens, where a pair is
+// two neighbouring quarters of one block: K rows of quarter s start s * 4 KiB into the page, its V^T
+// columns s * 32 bytes into every 128-byte row).
+template <int NW, int R>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_partial_mfma(const DecodeArgs a) {
     constexpr int D = 128;
+    constexpr int BT = kBlock * R;                     // tokens per block
     constexpr int GMAX = 16;
     __shared__ float sm_m[NW * GMAX], sm_l[NW * GMAX];
     __shared__ float sm_acc[NW * 8 * D];      // G <= 8 heads kept (G <= 8 is enforced on the host)
@@ -361,7 +365,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int krow_slot = ((n >> 2) & 1) * 8 + (n & 3);
     const unsigned k_off = (unsigned)krow_slot * (D * 2) + j * 16;      // + kk * 64, + 4 rows for tile 1
     const int v_blk = j >> 1;
-    const unsigned v_off = kBlock * D * 2 + (unsigned)n * (kBlock * 2) + (j & 1) * 16;  // + slice * 512
+    const unsigned v_off = BT * D * 2 + (unsigned)n * (BT * 2) + (j & 1) * 16;  // + slice * 16 rows, + quarter * 32
 
     f32x4 o[8];
 #pragma unroll
@@ -380,7 +384,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const int pr_l = first_pair + (lane >> 1) * NW;
         int b = 2 * pr_l + (lane & 1);
         if (b >= nblk) b = (2 * pr_l < nblk) ? 2 * pr_l : nblk - 1;   // odd tail / beyond the partition
-        const int id = trow[b];
+        const int id = trow[b / R];
         int first = a.rt.first[0];
         unsigned long long base = (unsigned long long)a.rt.base[0];
         for (int r = 1; r < a.rt.n; ++r) {
@@ -406,15 +410,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const unsigned bHi = __builtin_amdgcn_readlane((unsigned)(pages >> 32), 2 * k + 1);
         const char* pA = (const char*)(((unsigned long long)aHi << 32) | aLo);
         const char* pB = (const char*)(((unsigned long long)bHi << 32) | bLo);
-        const char* kp = (krow_blk ? pB : pA) + k_off;
-        const char* vp = (v_blk ? pB : pA) + v_off;
+        const unsigned quarter = R > 1 ? 2 * (pr & 1) : 0;                 // of the pair's first 16 tokens
+        const char* kp = (krow_blk ? pB : pA) + k_off + (R > 1 ? (quarter + krow_blk) * (kBlock * D * 2) : 0);
+        const char* vp = (v_blk ? pB : pA) + v_off + (R > 1 ? (quarter + v_blk) * (kBlock * 2) : 0);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             ld.k[0][kk] = load_stream16(kp + kk * 64);
             ld.k[1][kk] = load_stream16(kp + kk * 64 + 4 * D * 2);
         }
 #pragma unroll
-        for (int s = 0; s < 8; ++s) ld.v[s] = load_stream16(vp + s * 512);
+        for (int s = 0; s < 8; ++s) ld.v[s] = load_stream16(vp + s * (16 * BT * 2));
     };
 
     auto compute = [&](int pr, PairLoads& ld) {
@@ -748,13 +753,17 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     const char* force = getenv("KUN_DECODE_KERNEL");     // "generic" forces the vector-ALU kernel
     const bool generic_only = force && force[0] == 'g';
     int rc = KUN_OK;
-    if (p->dtype == KUN_BF16 && p->d == 128 && p->B == 16 && !generic_only) {
+    if (p->dtype == KUN_BF16 && p->d == 128 && !generic_only) {
         int nw = 4;
         const char* e = getenv("KUN_DECODE_WAVES");
         if (e) nw = atoi(e);
-        if (nw == 1) hipLaunchKernelGGL(decode_partial_mfma<1>, grid, dim3(64), 0, st, a);
-        else if (nw == 2) hipLaunchKernelGGL(decode_partial_mfma<2>, grid, dim3(128), 0, st, a);
-        else hipLaunchKernelGGL(decode_partial_mfma<4>, grid, dim3(256), 0, st, a);
+        if (p->B == 64) {
+            if (nw == 1) hipLaunchKernelGGL((decode_partial_mfma<1, 4>), grid, dim3(64), 0, st, a);
+            else if (nw == 2) hipLaunchKernelGGL((decode_partial_mfma<2, 4>), grid, dim3(128), 0, st, a);
+            else hipLaunchKernelGGL((decode_partial_mfma<4, 4>), grid, dim3(256), 0, st, a);
+        } else if (nw == 1) hipLaunchKernelGGL((decode_partial_mfma<1, 1>), grid, dim3(64), 0, st, a);
+        else if (nw == 2) hipLaunchKernelGGL((decode_partial_mfma<2, 1>), grid, dim3(128), 0, st, a);
+        else hipLaunchKernelGGL((decode_partial_mfma<4, 1>), grid, dim3(256), 0, st, a);
     } else if (p->dtype == KUN_BF16) {
         rc = p->d == 128 ? launch_generic<bf16_t, 128>(a, grid, st) : launch_generic<bf16_t, 64>(a, grid, st);
     } else {

@@ -493,7 +493,10 @@ typedef __attribute__((address_space(3))) void* kun_lptr;
 // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt = bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 #define KUN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
-template <int G, int NW, bool PERSIST>
+// R = 16-token steps per KV block (1 or 4).  The LDS image of a tile is the same for both: with
+// 64-token blocks a tile is ONE block, and the global->LDS loads pick the K rows of quarter s from
+// s * 4 KiB into the page and its V^T columns from s * 32 bytes into every 128-byte row.
+template <int G, int NW, bool PERSIST, int R>
 __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs a) {
     constexpr int NSTAGERS = 8;                        // waves that issue the tile loads (4 loads per lane and tile)
     constexpr int NT = 64 * NSTAGERS, LOADS = 2;
@@ -552,8 +555,8 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     auto load_pages = [&](int batch) -> unsigned long long {
         const int t = kt0 + batch * TPB + lane / LOADS, i = lane % LOADS;
         int lb = t * kBlocksPerTile + (wave >> 2) + 2 * i;
-        if (lb >= nblk_ctx) lb = nblk_ctx - 1;          // past the context: re-read the last block
-        const int id = trow[lb];
+        if (lb >= nblk_ctx) lb = nblk_ctx - 1;          // past the context: re-read the last (quarter) block
+        const int id = trow[lb / R];
         int first = a.rt.first[0];
         unsigned long long base = (unsigned long long)a.rt.base[0];
         for (int r = 1; r < a.rt.n; ++r) {
@@ -568,7 +571,8 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     // per-lane source offsets inside a page for the slot this lane fills (slot = (wave % 4) * 64 + lane)
     const int slot = (wave & 3) * 64 + lane;
     const unsigned k_src = (slot >> 4) * 256 + (((slot & 15) ^ (slot >> 4)) * 16);
-    const unsigned v_src = 4096 + ((slot ^ ((slot >> 4) & 1)) * 16);
+    const unsigned v_slot = slot ^ ((slot >> 4) & 1);   // (dim, half of the 16 tokens) = (v_slot >> 1, v_slot & 1)
+    const unsigned v_src = R == 1 ? 4096 + v_slot * 16 : 4 * 4096 + (v_slot >> 1) * 128 + (v_slot & 1) * 16;
 
     // The loads are issued through inline asm: the compiler then neither tracks them nor adds waits of
     // its own in front of LDS reads; completion is tracked by hand with vmcnt (see `iteration`).
@@ -595,9 +599,10 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     };
     auto issue_part = [&](int j) {
         const int i = j >> 1;
-        const unsigned dk = iss_stage + ((wave_u >> 2) + 2 * i) * 4096;
-        if (j & 1) dma16(iss_page[i] + v_src, dk + V_OFF);
-        else dma16(iss_page[i] + k_src, dk);
+        const unsigned q = (wave_u >> 2) + 2 * i;       // which 16 tokens of the tile
+        const unsigned dk = iss_stage + q * 4096;
+        if (j & 1) dma16(iss_page[i] + v_src + (R == 1 ? 0 : q * 32), dk + V_OFF);
+        else dma16(iss_page[i] + k_src + (R == 1 ? 0 : q * 4096), dk);
     };
     auto issue = [&](int j) {
         issue_begin(j);
@@ -931,7 +936,7 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(const int32_t* __rest
     }
 }
 
-bool mfma_shape(const kun_kv_pool* p) { return p->dtype == KUN_BF16 && p->d == 128 && p->B == 16; }
+bool mfma_shape(const kun_kv_pool* p) { return p->dtype == KUN_BF16 && p->d == 128; }
 
 // Tile shape: NW waves x 32 NQ rows per workgroup; `ring` selects prefill_ring_kernel, otherwise the
 // register-staged prefill_kernel runs; `persistent`: a fixed number of workgroups fetch the work
@@ -939,18 +944,18 @@ bool mfma_shape(const kun_kv_pool* p) { return p->dtype == KUN_BF16 && p->d == 1
 // workgroup per item (measured equal to one fetching workgroup per compute unit).
 // KUN_PREFILL_SHAPE picks another one for sweeps and cross-checks: "persistent" (one fetching
 // workgroup per compute unit), "12x1" (ring kernel, 12 waves), "8x1", "4x2", "4x1".
-struct TileShape { int nw, nq; bool ring, persistent; };
+struct TileShape { int nw, nq; bool ring, persistent, block64; };
 
 TileShape choose_shape() {
     const char* e = getenv("KUN_PREFILL_SHAPE");
     if (e) {
-        if (!strcmp(e, "persistent")) return TileShape{8, 1, true, true};
-        if (!strcmp(e, "12x1")) return TileShape{12, 1, true, false};
-        if (!strcmp(e, "8x1")) return TileShape{8, 1, false, false};
-        if (!strcmp(e, "4x2")) return TileShape{4, 2, false, false};
-        if (!strcmp(e, "4x1")) return TileShape{4, 1, false, false};
+        if (!strcmp(e, "persistent")) return TileShape{8, 1, true, true, false};
+        if (!strcmp(e, "12x1")) return TileShape{12, 1, true, false, false};
+        if (!strcmp(e, "8x1")) return TileShape{8, 1, false, false, false};
+        if (!strcmp(e, "4x2")) return TileShape{4, 2, false, false, false};
+        if (!strcmp(e, "4x1")) return TileShape{4, 1, false, false, false};
     }
-    return TileShape{8, 1, true, false};
+    return TileShape{8, 1, true, false, false};
 }
 
 // compute units of the current device (one persistent workgroup each)
@@ -969,9 +974,11 @@ bool prefill_shape_ok(const kun_kv_pool* p, int n_chunks, int Hq, int total_new)
 
 template <int G>
 void launch_prefill(const PrefillArgs& a, dim3 grid, TileShape t, hipStream_t st) {
-    if (t.persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, true>), grid, dim3(512), 0, st, a);
-    else if (t.nw == 12) hipLaunchKernelGGL((prefill_ring_kernel<G, 12, false>), grid, dim3(768), 0, st, a);
-    else if (t.nw == 8 && t.ring) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, false>), grid, dim3(512), 0, st, a);
+    if (t.block64 && t.persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, true, 4>), grid, dim3(512), 0, st, a);
+    else if (t.block64) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, false, 4>), grid, dim3(512), 0, st, a);
+    else if (t.persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, true, 1>), grid, dim3(512), 0, st, a);
+    else if (t.nw == 12) hipLaunchKernelGGL((prefill_ring_kernel<G, 12, false, 1>), grid, dim3(768), 0, st, a);
+    else if (t.nw == 8 && t.ring) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, false, 1>), grid, dim3(512), 0, st, a);
     else if (t.nw == 8) hipLaunchKernelGGL((prefill_kernel<G, 8, 1>), grid, dim3(512), 0, st, a);
     else if (t.nq == 2) hipLaunchKernelGGL((prefill_kernel<G, 4, 2>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((prefill_kernel<G, 4, 1>), grid, dim3(256), 0, st, a);
@@ -1047,7 +1054,8 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
                                        scale, (char*)workspace + 256 + 2 * col, st);
     }
 
-    const TileShape shape = max_workgroups > 0 ? TileShape{8, 1, true, true} : choose_shape();
+    TileShape shape = max_workgroups > 0 ? TileShape{8, 1, true, true, false} : choose_shape();
+    if (p->B == 64) shape = TileShape{8, 1, true, shape.persistent, true};     // 64-token blocks: the 8-wave ring kernels
     const bool persistent = shape.persistent;
     if (persistent && max_workgroups == 0) max_workgroups = device_compute_units();
     const int pos_per_tile = rows_per_wg(shape) / G;

@@ -233,6 +233,29 @@ def test_blocks_of_64_tokens(G, d, dtype):
     dw.close()
 
 
+@pytest.mark.parametrize("mode", ["persistent", "on16", "split"])
+@pytest.mark.parametrize("G", [8, 2])
+def test_blocks_of_64_tokens_other_launches(G, mode):
+    # the fetching kernel, a limited number of workgroups, and launches small enough to split the keys
+    if mode == "persistent":
+        os.environ["KUN_PREFILL_SHAPE"] = "persistent"
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=128, B=64, dtype="bf16")
+    sets = ([(3000, 40)], [(5000, 200), (17, 3)], [(1500, 64), (64, 64), (9000, 5)]) if mode == "split" else \
+        ([(0, 1), (63, 65), (64, 129), (100, 200), (0, 300), (700, 257), (1000, 31), (3000, 40), (0, 2100)],)
+    for chunks in sets:
+        w = synth.custom_workload("b64o", sh, [3], chunks=chunks, extra_blocks=3, range_fracs=(0.4, 0.6))
+        dw = DeviceWorkload(w)
+        dw.out_pre.fill_(float("nan"))
+        if mode == "on16":
+            ref = dw.prefill().clone()
+            dw.out_pre.fill_(float("nan"))
+            got = dw.prefill(max_workgroups=16)
+            torch.cuda.synchronize()
+            assert torch.equal(got.view(torch.int16), ref.view(torch.int16))
+        check_prefill(dw, rows_per_chunk=48)
+        dw.close()
+
+
 def test_empty_chunk_is_skipped_and_first_row_returns_v():
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     w = synth.custom_workload("pre0", sh, [3], chunks=[(0, 5), (7, 0), (0, 40)], extra_blocks=2)

@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=0, help="workload 2..5 (default: the largest supported)")
+    ap.add_argument("--block-size", type=int, default=0, choices=[0, 16, 64],
+                    help="tokens per KV block (default: the configuration's own, 16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mixed", action="store_true",
                     help="skip the side-by-side prefill + decode measurement (keeps profiles to the K timed steps)")
@@ -77,7 +79,7 @@ def main():
         sys.exit(2)
     cfg = args.config or DEFAULT_CONFIG
     t_setup = time.time()
-    w = synth.config(cfg)
+    w = synth.config(cfg, args.block_size)
     sh = w.shape
     dw = DeviceWorkload(w, poison=(cfg != 5))
     torch.cuda.synchronize()
@@ -139,7 +141,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype,
         "data": "synthetic",
-        "config": {"workload": f"cfg{cfg}:{w.name}", "decode_requests": w.S, "prefill_chunks": w.n_chunks if has_prefill else 0,
+        "config": {"workload": f"cfg{cfg}:{w.name}", "block_size": w.shape.B, "decode_requests": w.S, "prefill_chunks": w.n_chunks if has_prefill else 0,
                    "Hq": sh.Hq, "Hkv": sh.Hkv, "head_dim": sh.d, "block_size": sh.B,
                    "pool_ranges": len(w.range_blocks), "pool_GB": round(w.num_blocks * sh.block_bytes / 1e9, 2),
                    "decode_kv_tokens": w.decode_kv_tokens, "seed": w.seed},
@@ -149,7 +151,7 @@ def main():
                    "kv_tokens_per_s": round(w.decode_kv_tokens / (t_dec * 1e-3), 1)},
         "append": {"ms": round(t_app, 4), "tokens": T_new},
         "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC_BYTES.get(cfg),
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC_BYTES.get(cfg) if w.shape.B == 16 else None,
                      "kernel": "decode_partial_mfma (timed with its plan and merge launches)"},
         "setup_s": round(t_setup, 1),
     }

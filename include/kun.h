@@ -25,9 +25,11 @@
  *     valid: check tables with kun_validate_block_table when in doubt.
  *
  * Page layout (part of the ABI).  One block is num_kv_heads pages; page (block, kv head) is
- *     K  [block_size tokens][head_dim]      then
- *     V  [head_dim][block_size tokens]      (V is stored transposed inside a page)
- *   so block_bytes = 2 * num_kv_heads * block_size * head_dim * sizeof(element); with 8 KV heads
+ *   block_size / 16 tiles in token order, and the tile of tokens 16 i .. 16 i + 15 is
+ *     K  [16 tokens][head_dim]      then
+ *     V  [head_dim][16 tokens]      (V is stored transposed inside a tile)
+ *   (a page of 64 tokens is laid out as four pages of 16 tokens in a row: every kernel reads whole,
+ *   contiguous tiles whatever the block size), so block_bytes = 2 * num_kv_heads * block_size * head_dim * sizeof(element); with 8 KV heads
  *   of 128 dims in bf16 that is 4096 bytes per token per layer, the figure behind the 192 KB per
  *   token of a 48-layer model quoted in Section 2.2.
  *   Query heads h with the same h / (num_q_heads / num_kv_heads) share a KV head (GQA).
@@ -126,7 +128,7 @@ KUN_API int kun_validate_block_table(const kun_kv_pool* pool, const int32_t* hos
  *   range_out[i]  index of the range that holds the token's block          (device int32 [T])
  *   k_off_out[i]  byte offset inside that range of K[position][0]          (device int64 [T])
  *   v_off_out[i]  byte offset inside that range of V[position][0]; element j of the V row sits
- *                 j * block_size elements further on                       (device int64 [T])
+ *                 j * 16 elements further on (the tile's row stride)       (device int64 [T])
  * Integer outputs, exact.  T == 0 is a no-op. */
 KUN_API int kun_slot_map(const kun_kv_pool* pool, const int32_t* seq_of_tok, const int32_t* pos_of_tok,
                  int T, const int32_t* block_table, int max_blocks, int kv_head,

@@ -16,8 +16,9 @@ of a request gathered in logical order from its KV blocks:
   p*c + (c^2 + c)/2 (query, key) pairs (Section 4.3, Eq. 1).
 
 Readings where the paper is silent: consecutive query heads share a KV head (GQA); the context
-length counts the token being decoded; one page (block, kv head) stores K as [token][dim] then V
-as [dim][token]; table entries past ceil(L/B) and slots past L are never read.
+length counts the token being decoded; one page (block, kv head) is a row of tiles of min(B, 16)
+tokens, a tile storing K as [token][dim] then V as [dim][token] (the paper fixes no layout inside
+a block); table entries past ceil(L/B) and slots past L are never read.
 
 Every function has a pin in tests/test_oracle_pins.py (dense brute force, permutation invariance,
 rows summing to 1, length-1 context, closed forms, Eq. 1 pair count, chunking equivalence).
@@ -95,16 +96,27 @@ def token_slot(table_row: Sequence[int], t: int, B: int) -> Tuple[int, int]:
     return int(table_row[t // B]), t % B
 
 
+TILE_TOKENS = 16
+
+
+def tile_tokens(B: int) -> int:
+    """Tokens per tile: a page is a row of tiles of min(B, 16) tokens, each holding its K rows and
+    then its V columns (a page of 64 tokens is four pages of 16 tokens in a row)."""
+    return min(B, TILE_TOKENS)
+
+
 def k_elem_offset(pool: OraclePool, local_block: int, kvh: int, slot: int) -> int:
     """Element offset (inside a range) of K[slot][0] of page (local_block, kvh)."""
+    T = tile_tokens(pool.B)
     page = (local_block * pool.Hkv + kvh) * 2 * pool.B * pool.d
-    return page + slot * pool.d
+    return page + (slot // T) * 2 * T * pool.d + (slot % T) * pool.d
 
 
 def v_elem_offset(pool: OraclePool, local_block: int, kvh: int, slot: int, j: int) -> int:
-    """Element offset (inside a range) of V[slot][j]: V is stored as [dim][token] in a page."""
+    """Element offset (inside a range) of V[slot][j]: V is stored as [dim][token] inside a tile."""
+    T = tile_tokens(pool.B)
     page = (local_block * pool.Hkv + kvh) * 2 * pool.B * pool.d
-    return page + pool.B * pool.d + j * pool.B + slot
+    return page + (slot // T) * 2 * T * pool.d + T * pool.d + j * T + slot % T
 
 
 def widen(raw: np.ndarray, dtype: str) -> np.ndarray:
@@ -117,18 +129,19 @@ def widen(raw: np.ndarray, dtype: str) -> np.ndarray:
 def gather_kv(pool: OraclePool, table_row: Sequence[int], L: int, kvh: int):
     """K and V of tokens 0..L-1 of one request and KV head, in logical order: two [L, d] fp64."""
     B, d = pool.B, pool.d
+    T = tile_tokens(B)
     rb = pool.range_blocks
     K = np.empty((L, d), dtype=np.float64)
     V = np.empty((L, d), dtype=np.float64)
-    for b0 in range(0, L, B):
-        n = min(B, L - b0)
-        blk = int(table_row[b0 // B])
+    for b0 in range(0, L, T):                                         # one tile at a time
+        n = min(T, L - b0)
+        blk, slot = token_slot(table_row, b0, B)
         r, local = resolve_block(rb, blk)
         mem = pool.ranges[r]
-        ko = k_elem_offset(pool, local, kvh, 0)
+        ko = k_elem_offset(pool, local, kvh, slot)
         K[b0:b0 + n] = widen(mem[ko:ko + n * d], pool.dtype).reshape(n, d)
-        vo = v_elem_offset(pool, local, kvh, 0, 0)
-        vt = widen(mem[vo:vo + B * d], pool.dtype).reshape(d, B)      # [dim][slot]
+        vo = v_elem_offset(pool, local, kvh, slot, 0)
+        vt = widen(mem[vo:vo + T * d], pool.dtype).reshape(d, T)      # [dim][slot of the tile]
         V[b0:b0 + n] = vt[:, :n].T
     return K, V
 

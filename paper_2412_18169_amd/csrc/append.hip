@@ -1,9 +1,12 @@
 // KV append: scatter the K/V rows of new tokens into their page slots through the block table.
-// K rows are contiguous in a page; V is stored transposed ([dim][token]), so a token's V row
-// becomes head_dim strided element stores.  Pure copy: results are bit-exact.
+// A page is a row of tiles of 16 tokens; K rows are contiguous in a tile, V is stored transposed
+// ([dim][token]) behind them, so a token's V row becomes head_dim strided element stores.  Pure copy:
+// results are bit-exact.
 #include "kun_internal.h"
 
 namespace {
+
+constexpr int kTile = 16;       // tokens per tile of a page
 
 template <typename E>
 __global__ __launch_bounds__(256) void kv_append_kernel(const KunRanges rt, const E* __restrict__ k_new,
@@ -16,13 +19,13 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const KunRanges rt, cons
     for (int i = blockIdx.x; i < T; i += gridDim.x) {
         const int seq = seq_of_tok[i], pos = pos_of_tok[i];
         const int blk = table[(size_t)seq * max_blocks + pos / B];
-        const int slot = pos % B;
+        const int tile = (pos % B) / kTile, slot = pos % kTile;
         char* block = kun_block_addr(rt, blk, block_bytes);
         for (int x = threadIdx.x; x < Hkv * D; x += blockDim.x) {
             const int h = x / D, j = x - h * D;
-            E* page = (E*)(block + (size_t)h * page_bytes);
-            page[slot * D + j] = k_new[(size_t)i * Hkv * D + x];
-            page[B * D + j * B + slot] = v_new[(size_t)i * Hkv * D + x];
+            E* t = (E*)(block + (size_t)h * page_bytes) + (size_t)tile * (2 * kTile * D);
+            t[slot * D + j] = k_new[(size_t)i * Hkv * D + x];
+            t[kTile * D + j * kTile + slot] = v_new[(size_t)i * Hkv * D + x];
         }
     }
 }
@@ -37,14 +40,15 @@ __global__ __launch_bounds__(256) void slot_map_kernel(const KunRanges rt, const
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < T; i += gridDim.x * blockDim.x) {
         const int seq = seq_of_tok[i], pos = pos_of_tok[i];
         const int blk = table[(size_t)seq * max_blocks + pos / B];
-        const int slot = pos % B;
-        const char* page = kun_block_addr(rt, blk, block_bytes) + (size_t)h * page_bytes;
+        const int tile = (pos % B) / kTile, slot = pos % kTile;
+        const char* page = kun_block_addr(rt, blk, block_bytes) + (size_t)h * page_bytes +
+                           (size_t)tile * (2 * kTile * D) * elt;
         int r = 0;
         for (int j = 1; j < rt.n; ++j)
             if (blk >= rt.first[j]) r = j;
         range_out[i] = r;
         k_off[i] = (int64_t)(page + (size_t)slot * D * elt - rt.base[r]);
-        v_off[i] = (int64_t)(page + ((size_t)B * D + slot) * elt - rt.base[r]);
+        v_off[i] = (int64_t)(page + ((size_t)kTile * D + slot) * elt - rt.base[r]);
     }
 }
 

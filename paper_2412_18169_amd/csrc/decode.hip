@@ -99,8 +99,10 @@ __global__ __launch_bounds__(1024) void decode_plan_kernel(const int32_t* __rest
 // it streams past the caches (measured on a plain read of a 16 GiB buffer: 7.0 TB/s against 6.2 TB/s
 // for ordinary loads).
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+// The pointer is cast to the global address space: a load through a generic pointer is a flat load,
+// which may complete out of order with other loads, so every wait for one waits for all of them.
 __device__ __forceinline__ uint4 load_stream16(const void* p) {
-    const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+    const u32x4 v = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4*)p);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) {
@@ -213,14 +215,12 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
     }
 
     const int32_t* trow = a.table + (size_t)(a.row_of_seq ? a.row_of_seq[seq] : seq) * a.max_blocks;
-    // b counts 16-token steps; with 64-token blocks a step is a quarter `sub` of block b / 4: its K rows
-    // are contiguous inside the page's K part, its V^T columns sit sub * 16 elements into every row
-    const int steps_per_block = a.B / kBlock;
+    // b counts tiles of 16 tokens: tile b % (B / 16) of block b / (B / 16); a tile is K [16][D], then V^T [D][16]
+    const int tiles_per_block = a.B / kBlock;
     for (int b = t0 / kBlock + wave; b * kBlock < t1; b += NW) {
-        const int blk = __builtin_amdgcn_readfirstlane(trow[b / steps_per_block]);
-        const int sub = b % steps_per_block;
-        const char* page0 = kun_block_addr(a.rt, blk, a.block_bytes) + (size_t)kvh * a.page_bytes;
-        const char* page = page0 + (size_t)sub * kBlock * D * sizeof(T);
+        const int blk = __builtin_amdgcn_readfirstlane(trow[b / tiles_per_block]);
+        const char* page = kun_block_addr(a.rt, blk, a.block_bytes) + (size_t)kvh * a.page_bytes +
+                           (size_t)(b % tiles_per_block) * (2 * kBlock * D * sizeof(T));
         const int tb = b * kBlock;
         // scores: s[g][it] for token tb + it * TPL + grp
         float s[G][NIT];
@@ -263,14 +263,14 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
             for (int i = 0; i < DPL; ++i) acc[g][i] *= alpha;
         }
         // acc[g][dim] += sum_t p[g][t] * V^T[dim][t]
-        const char* vpage = page0 + ((size_t)a.B * D + sub * kBlock) * sizeof(T);
+        const char* vpage = page + (size_t)kBlock * D * sizeof(T);
 #pragma unroll
         for (int i = 0; i < DPL; ++i) {
             const int dim = lane + 64 * i;
             float vrow[kBlock];
 #pragma unroll
             for (int c = 0; c < VLD; ++c) {
-                uint4 vv = load_stream16(vpage + ((size_t)dim * a.B + c * EPL) * sizeof(T));
+                uint4 vv = load_stream16(vpage + ((size_t)dim * kBlock + c * EPL) * sizeof(T));
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) {
                     const int t = c * EPL + e;
@@ -325,13 +325,10 @@ struct PairLoads {
     uint4 v[8];      // [dim slice]
 };
 
-// R = 16-token steps per KV block (1: blocks of 16 tokens; 4: blocks of 64 tokens, where a pair is
-// two neighbouring quarters of one block: K rows of quarter s start s * 4 KiB into the page, its V^T
-// columns s * 32 bytes into every 128-byte row).
+// R = tiles of 16 tokens per KV block (1 or 4): tile i of a request is tile i % R of its block i / R.
 template <int NW, int R>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_partial_mfma(const DecodeArgs a) {
     constexpr int D = 128;
-    constexpr int BT = kBlock * R;                     // tokens per block
     constexpr int GMAX = 16;
     __shared__ float sm_m[NW * GMAX], sm_l[NW * GMAX];
     __shared__ float sm_acc[NW * 8 * D];      // G <= 8 heads kept (G <= 8 is enforced on the host)
@@ -360,13 +357,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
             qf[kk].u = v;
         }
     }
-    // tile row n -> token: rows 4jj + r; block jj / 2, slot 8 * (jj % 2) + r (+4 for tile 1)
-    const int krow_blk = n >> 3;                       // which block of the pair (0/1)
-    const int krow_slot = ((n >> 2) & 1) * 8 + (n & 3);
-    const unsigned k_off = (unsigned)krow_slot * (D * 2) + j * 16;      // + kk * 64, + 4 rows for tile 1
-    const int v_blk = j >> 1;
-    const unsigned v_off = BT * D * 2 + (unsigned)n * (BT * 2) + (j & 1) * 16;  // + slice * 16 rows, + quarter * 32
-
     f32x4 o[8];
 #pragma unroll
     for (int s = 0; s < 8; ++s) o[s] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -374,6 +364,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
     const int32_t* trow = a.table + (size_t)seq * a.max_blocks;
     const int nblk = (t1 + kBlock - 1) / kBlock;       // blocks of the request this item may touch
+    // tile row n -> token: rows 4jj + r; block jj / 2, slot 8 * (jj % 2) + r (+4 for tile 1)
+    const int krow_blk = n >> 3;                       // which block of the pair (0/1)
+    const int krow_slot = ((n >> 2) & 1) * 8 + (n & 3);
+    const unsigned k_off = (unsigned)krow_slot * (D * 2) + j * 16;      // + kk * 64, + 4 rows for tile 1
+    const int v_blk = j >> 1;
+    const unsigned v_off = kBlock * D * 2 + (unsigned)n * (kBlock * 2) + (j & 1) * 16;  // + slice * 16 rows
+
     const int pair0 = t0 / 32 + wave;
     const int pair_end = (t1 + 31) / 32;
 
@@ -392,7 +389,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
             first = in ? a.rt.first[r] : first;
             base = in ? (unsigned long long)a.rt.base[r] : base;
         }
-        return base + (unsigned long long)(id - first) * a.block_bytes + (unsigned long long)kvh * a.page_bytes;
+        return base + (unsigned long long)(id - first) * a.block_bytes + (unsigned long long)kvh * a.page_bytes +
+               (unsigned)(b % R) * (2 * kBlock * D * 2);
     };
     unsigned long long pages = load_pages(pair0);
     int pages_first = pair0;
@@ -410,16 +408,15 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const unsigned bHi = __builtin_amdgcn_readlane((unsigned)(pages >> 32), 2 * k + 1);
         const char* pA = (const char*)(((unsigned long long)aHi << 32) | aLo);
         const char* pB = (const char*)(((unsigned long long)bHi << 32) | bLo);
-        const unsigned quarter = R > 1 ? 2 * (pr & 1) : 0;                 // of the pair's first 16 tokens
-        const char* kp = (krow_blk ? pB : pA) + k_off + (R > 1 ? (quarter + krow_blk) * (kBlock * D * 2) : 0);
-        const char* vp = (v_blk ? pB : pA) + v_off + (R > 1 ? (quarter + v_blk) * (kBlock * 2) : 0);
+        const char* kp = (krow_blk ? pB : pA) + k_off;
+        const char* vp = (v_blk ? pB : pA) + v_off;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             ld.k[0][kk] = load_stream16(kp + kk * 64);
             ld.k[1][kk] = load_stream16(kp + kk * 64 + 4 * D * 2);
         }
 #pragma unroll
-        for (int s = 0; s < 8; ++s) ld.v[s] = load_stream16(vp + s * (16 * BT * 2));
+        for (int s = 0; s < 8; ++s) ld.v[s] = load_stream16(vp + s * (16 * kBlock * 2));
     };
 
     auto compute = [&](int pr, PairLoads& ld) {
@@ -507,6 +504,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
             pr = pr2;
         }
     }
+
 
     // l: sum over the 4 token groups j of this head
     l += __shfl_xor(l, 16);

@@ -65,6 +65,7 @@ struct PrefillArgs {
     int max_items;
     float scale_log2;
     unsigned block_bytes, page_bytes;
+    int sub_shift;           // log2 of the 16-token page tiles per KV block (0 or 2): page tile i of a request is tile i % 2^shift of block i >> shift
 };
 
 // max of three floats in one instruction.  Plain fmaxf makes the compiler canonicalise every MFMA
@@ -268,7 +269,7 @@ __global__ __launch_bounds__(64 * NW) void prefill_kernel(const PrefillArgs a) {
     auto load_ids = [&](int batch) -> int {
         const int t = batch * TPB + lane / LOADS, i = lane % LOADS;
         const int lb = t * kBlocksPerTile + ((wave * 64 + i * NT) >> 8);
-        return (lb < nblk_ctx) ? trow[lb] : 0;
+        return (lb < nblk_ctx) ? trow[lb >> a.sub_shift] : 0;
     };
     int ids_cur = load_ids(0), ids_nxt = 0;
 
@@ -284,7 +285,8 @@ __global__ __launch_bounds__(64 * NW) void prefill_kernel(const PrefillArgs a) {
             uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
             if (lb < nblk_ctx) {
                 const int id = __builtin_amdgcn_readlane(ids_cur, rel * LOADS + i);
-                const char* page = kun_block_addr(a.rt, id, a.block_bytes) + (size_t)kvh * a.page_bytes;
+                const char* page = kun_block_addr(a.rt, id, a.block_bytes) + (size_t)kvh * a.page_bytes +
+                                   (size_t)(lb & ((1 << a.sub_shift) - 1)) * 8192;
                 kv = *(const uint4*)(page + w * 16);
                 vv = *(const uint4*)(page + 4096 + w * 16);
             }
@@ -493,10 +495,7 @@ typedef __attribute__((address_space(3))) void* kun_lptr;
 // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt = bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 #define KUN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
-// R = 16-token steps per KV block (1 or 4).  The LDS image of a tile is the same for both: with
-// 64-token blocks a tile is ONE block, and the global->LDS loads pick the K rows of quarter s from
-// s * 4 KiB into the page and its V^T columns from s * 32 bytes into every 128-byte row.
-template <int G, int NW, bool PERSIST, int R>
+template <int G, int NW, bool PERSIST>
 __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs a) {
     constexpr int NSTAGERS = 8;                        // waves that issue the tile loads (4 loads per lane and tile)
     constexpr int NT = 64 * NSTAGERS, LOADS = 2;
@@ -555,8 +554,8 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     auto load_pages = [&](int batch) -> unsigned long long {
         const int t = kt0 + batch * TPB + lane / LOADS, i = lane % LOADS;
         int lb = t * kBlocksPerTile + (wave >> 2) + 2 * i;
-        if (lb >= nblk_ctx) lb = nblk_ctx - 1;          // past the context: re-read the last (quarter) block
-        const int id = trow[lb / R];
+        if (lb >= nblk_ctx) lb = nblk_ctx - 1;          // past the context: re-read the last tile
+        const int id = trow[lb >> a.sub_shift];
         int first = a.rt.first[0];
         unsigned long long base = (unsigned long long)a.rt.base[0];
         for (int r = 1; r < a.rt.n; ++r) {
@@ -564,15 +563,15 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
             first = in ? a.rt.first[r] : first;
             base = in ? (unsigned long long)a.rt.base[r] : base;
         }
-        return base + (unsigned long long)(id - first) * a.block_bytes + (unsigned long long)kvh * a.page_bytes;
+        return base + (unsigned long long)(id - first) * a.block_bytes + (unsigned long long)kvh * a.page_bytes +
+               (unsigned)(lb & ((1 << a.sub_shift) - 1)) * 8192u;
     };
     unsigned long long pages_cur = load_pages(0), pages_nxt = 0;
 
     // per-lane source offsets inside a page for the slot this lane fills (slot = (wave % 4) * 64 + lane)
     const int slot = (wave & 3) * 64 + lane;
     const unsigned k_src = (slot >> 4) * 256 + (((slot & 15) ^ (slot >> 4)) * 16);
-    const unsigned v_slot = slot ^ ((slot >> 4) & 1);   // (dim, half of the 16 tokens) = (v_slot >> 1, v_slot & 1)
-    const unsigned v_src = R == 1 ? 4096 + v_slot * 16 : 4 * 4096 + (v_slot >> 1) * 128 + (v_slot & 1) * 16;
+    const unsigned v_src = 4096 + ((slot ^ ((slot >> 4) & 1)) * 16);
 
     // The loads are issued through inline asm: the compiler then neither tracks them nor adds waits of
     // its own in front of LDS reads; completion is tracked by hand with vmcnt (see `iteration`).
@@ -599,10 +598,9 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     };
     auto issue_part = [&](int j) {
         const int i = j >> 1;
-        const unsigned q = (wave_u >> 2) + 2 * i;       // which 16 tokens of the tile
-        const unsigned dk = iss_stage + q * 4096;
-        if (j & 1) dma16(iss_page[i] + v_src + (R == 1 ? 0 : q * 32), dk + V_OFF);
-        else dma16(iss_page[i] + k_src + (R == 1 ? 0 : q * 4096), dk);
+        const unsigned dk = iss_stage + ((wave_u >> 2) + 2 * i) * 4096;
+        if (j & 1) dma16(iss_page[i] + v_src, dk + V_OFF);
+        else dma16(iss_page[i] + k_src, dk);
     };
     auto issue = [&](int j) {
         issue_begin(j);
@@ -944,18 +942,18 @@ bool mfma_shape(const kun_kv_pool* p) { return p->dtype == KUN_BF16 && p->d == 1
 // workgroup per item (measured equal to one fetching workgroup per compute unit).
 // KUN_PREFILL_SHAPE picks another one for sweeps and cross-checks: "persistent" (one fetching
 // workgroup per compute unit), "12x1" (ring kernel, 12 waves), "8x1", "4x2", "4x1".
-struct TileShape { int nw, nq; bool ring, persistent, block64; };
+struct TileShape { int nw, nq; bool ring, persistent; };
 
 TileShape choose_shape() {
     const char* e = getenv("KUN_PREFILL_SHAPE");
     if (e) {
-        if (!strcmp(e, "persistent")) return TileShape{8, 1, true, true, false};
-        if (!strcmp(e, "12x1")) return TileShape{12, 1, true, false, false};
-        if (!strcmp(e, "8x1")) return TileShape{8, 1, false, false, false};
-        if (!strcmp(e, "4x2")) return TileShape{4, 2, false, false, false};
-        if (!strcmp(e, "4x1")) return TileShape{4, 1, false, false, false};
+        if (!strcmp(e, "persistent")) return TileShape{8, 1, true, true};
+        if (!strcmp(e, "12x1")) return TileShape{12, 1, true, false};
+        if (!strcmp(e, "8x1")) return TileShape{8, 1, false, false};
+        if (!strcmp(e, "4x2")) return TileShape{4, 2, false, false};
+        if (!strcmp(e, "4x1")) return TileShape{4, 1, false, false};
     }
-    return TileShape{8, 1, true, false, false};
+    return TileShape{8, 1, true, false};
 }
 
 // compute units of the current device (one persistent workgroup each)
@@ -974,11 +972,9 @@ bool prefill_shape_ok(const kun_kv_pool* p, int n_chunks, int Hq, int total_new)
 
 template <int G>
 void launch_prefill(const PrefillArgs& a, dim3 grid, TileShape t, hipStream_t st) {
-    if (t.block64 && t.persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, true, 4>), grid, dim3(512), 0, st, a);
-    else if (t.block64) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, false, 4>), grid, dim3(512), 0, st, a);
-    else if (t.persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, true, 1>), grid, dim3(512), 0, st, a);
-    else if (t.nw == 12) hipLaunchKernelGGL((prefill_ring_kernel<G, 12, false, 1>), grid, dim3(768), 0, st, a);
-    else if (t.nw == 8 && t.ring) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, false, 1>), grid, dim3(512), 0, st, a);
+    if (t.persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, true>), grid, dim3(512), 0, st, a);
+    else if (t.nw == 12) hipLaunchKernelGGL((prefill_ring_kernel<G, 12, false>), grid, dim3(768), 0, st, a);
+    else if (t.nw == 8 && t.ring) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, false>), grid, dim3(512), 0, st, a);
     else if (t.nw == 8) hipLaunchKernelGGL((prefill_kernel<G, 8, 1>), grid, dim3(512), 0, st, a);
     else if (t.nq == 2) hipLaunchKernelGGL((prefill_kernel<G, 4, 2>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((prefill_kernel<G, 4, 1>), grid, dim3(256), 0, st, a);
@@ -1054,8 +1050,7 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
                                        scale, (char*)workspace + 256 + 2 * col, st);
     }
 
-    TileShape shape = max_workgroups > 0 ? TileShape{8, 1, true, true, false} : choose_shape();
-    if (p->B == 64) shape = TileShape{8, 1, true, shape.persistent, true};     // 64-token blocks: the 8-wave ring kernels
+    const TileShape shape = max_workgroups > 0 ? TileShape{8, 1, true, true} : choose_shape();
     const bool persistent = shape.persistent;
     if (persistent && max_workgroups == 0) max_workgroups = device_compute_units();
     const int pos_per_tile = rows_per_wg(shape) / G;
@@ -1085,6 +1080,7 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     a.scale_log2 = scale * kLog2e;
     a.block_bytes = (unsigned)p->block_bytes;
     a.page_bytes = (unsigned)p->page_bytes;
+    a.sub_shift = p->B == 64 ? 2 : 0;
     hipStream_t st = (hipStream_t)stream;
 
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, q_start, prior_len, n_chunks,

@@ -279,22 +279,27 @@ SHAPE_8B = LayerShape(Hq=32, Hkv=8, d=128, B=16, dtype="bf16")
 SHAPE_70B = LayerShape(Hq=64, Hkv=8, d=128, B=16, dtype="bf16")
 
 
-def config(cfg: int) -> Workload:
-    """The five benchmark configurations (1-based). Seeds are 1000 + cfg."""
+def config(cfg: int, block_size: int = 0) -> Workload:
+    """The five benchmark configurations (1-based). Seeds are 1000 + cfg.  `block_size` (0 = the
+    configuration's own, 16) builds the same requests over KV blocks of another size."""
+    import dataclasses
     seed = 1000 + cfg
+    sh = {1: SHAPE_TINY, 2: SHAPE_8B, 3: SHAPE_8B, 4: SHAPE_8B, 5: SHAPE_70B}.get(cfg, SHAPE_8B)
+    if block_size:
+        sh = dataclasses.replace(sh, B=block_size)
     if cfg == 1:
-        w = Workload("tiny-decode-f32", 1, seed, SHAPE_TINY,
-                     np.array([17, 64, 200, 513], dtype=np.int32), [], [64])
+        w = Workload("tiny-decode-f32", 1, seed, sh,
+                     np.array([17, 64, 200, 513], dtype=np.int32), [], [64 * 16 // sh.B])
         assign_blocks_scattered(w)
     elif cfg == 2:
         lens = _rng(seed, 1).integers(512, 4097, size=64).astype(np.int32)
-        w = Workload("8b-decode-bf16", 2, seed, SHAPE_8B, lens, [], [])
-        w.range_blocks = [int(blocks_needed(lens, 16).sum())]
+        w = Workload("8b-decode-bf16", 2, seed, sh, lens, [], [])
+        w.range_blocks = [int(blocks_needed(lens, sh.B).sum())]
         assign_blocks_scattered(w)
     elif cfg == 3:
         lens = lognormal_lengths(_rng(seed, 1), 512)
-        w = Workload("overload-decode-bf16", 3, seed, SHAPE_8B, lens, [], [])
-        n = int(blocks_needed(lens, 16).sum())
+        w = Workload("overload-decode-bf16", 3, seed, sh, lens, [], [])
+        n = int(blocks_needed(lens, sh.B).sum())
         r0, r1 = int(0.4 * n), int(0.3 * n)
         w.range_blocks = [r0, r1, n - r0 - r1]
         w.phase_resident = assign_blocks_phased(w)
@@ -302,14 +307,14 @@ def config(cfg: int) -> Workload:
         r = _rng(seed, 1)
         lens = lognormal_lengths(r, 256)
         chunks = [(int(p), 512) for p in r.integers(0, 3585, size=8)]
-        w = Workload("mixed-prefill-decode-bf16", 4, seed, SHAPE_8B, lens, chunks, [])
-        w.range_blocks = [int(blocks_needed(w.seq_lens, 16).sum())]
+        w = Workload("mixed-prefill-decode-bf16", 4, seed, sh, lens, chunks, [])
+        w.range_blocks = [int(blocks_needed(w.seq_lens, sh.B).sum())]
         assign_blocks_scattered(w)
     elif cfg == 5:
         r = _rng(seed, 1)
         lens = r.integers(1024, 32769, size=256).astype(np.int32)
         chunks = [(int(p), 1024) for p in r.integers(0, 8193, size=4)]
-        w = Workload("70b-stage-bf16", 5, seed, SHAPE_70B, lens, chunks, [])
+        w = Workload("70b-stage-bf16", 5, seed, sh, lens, chunks, [])
         per_range = (30 * 10**9) // w.shape.block_bytes      # 30 GB ranges: base + 4 extensions
         w.range_blocks = [per_range] * 5
         assign_blocks_scattered(w)
@@ -358,7 +363,7 @@ def range_of_blocks(range_blocks: Sequence[int], ids: np.ndarray):
 
 
 def alloc_ranges(w: Workload, device="cpu", poison: bool = True) -> List[torch.Tensor]:
-    """One buffer per pool range, shaped [n_blocks, Hkv, 2, B*d]; unused space NaN-poisoned."""
+    """One buffer per pool range, [n_blocks, Hkv, 2, B*d] elements; unused space NaN-poisoned."""
     sh = w.shape
     out = []
     for nb in w.range_blocks:
@@ -375,29 +380,32 @@ def write_pages(w: Workload, ranges: List[torch.Tensor], seq: int, t0: int, t1: 
                 k: Optional[torch.Tensor] = None, v: Optional[torch.Tensor] = None) -> None:
     """Copy tokens t0..t1-1 of sequence `seq` into its pages.
 
-    Page layout of one (block, kv head): K as [B tokens][d], then V as [d][B tokens] (V is stored
-    transposed inside a page). Slots of the last block beyond the context are left as they are.
+    Page layout of one (block, kv head): a row of tiles of min(B, 16) tokens; a tile holds K as
+    [tokens][d], then V as [d][tokens] (V is stored transposed inside a tile). Slots of the last
+    block beyond the context are left as they are.
     """
     sh = w.shape
     B, d = sh.B, sh.d
+    T = min(B, 16)
     dev = ranges[0].device
     if k is None:
         k, v = kv_logical(w, seq, t0, t1, dev)
     bt = w.block_tables[seq]
     toks = np.arange(t0, t1, dtype=np.int64)
     blk = bt[toks // B].astype(np.int64)
-    slot = torch.from_numpy(toks % B).to(dev)
+    tile = torch.from_numpy((toks % B) // T).to(dev)
+    slot = torch.from_numpy(toks % T).to(dev)
     r_idx, local = range_of_blocks(w.range_blocks, blk)
     for r in np.unique(r_idx):
         sel = np.nonzero(r_idx == r)[0]
         selt = torch.from_numpy(sel).to(dev)
         lb = torch.from_numpy(local[sel]).to(dev)
-        sl = slot[selt]
-        buf = ranges[int(r)]
-        kview = buf[:, :, 0, :].view(-1, sh.Hkv, B, d)       # [blk, h, token, d]
-        vview = buf[:, :, 1, :].view(-1, sh.Hkv, d, B)       # [blk, h, d, token]
-        kview[lb, :, sl, :] = k[selt]                        # [n, Hkv, d]
-        vview[lb, :, :, sl] = v[selt]
+        sl, tl = slot[selt], tile[selt]
+        buf = ranges[int(r)].view(-1, sh.Hkv, B // T, 2, T * d)
+        kview = buf[:, :, :, 0, :].view(-1, sh.Hkv, B // T, T, d)     # [blk, h, tile, token, d]
+        vview = buf[:, :, :, 1, :].view(-1, sh.Hkv, B // T, d, T)     # [blk, h, tile, d, token]
+        kview[lb, :, tl, sl, :] = k[selt]                             # [n, Hkv, d]
+        vview[lb, :, tl, :, sl] = v[selt]
 
 
 def fill_pool(w: Workload, ranges: List[torch.Tensor], seqs: Optional[Sequence[int]] = None,

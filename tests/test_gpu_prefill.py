@@ -233,12 +233,13 @@ def test_blocks_of_64_tokens(G, d, dtype):
     dw.close()
 
 
-@pytest.mark.parametrize("mode", ["persistent", "on16", "split"])
+@pytest.mark.parametrize("mode", ["persistent", "on16", "split", "12x1", "8x1", "4x2", "4x1"])
 @pytest.mark.parametrize("G", [8, 2])
 def test_blocks_of_64_tokens_other_launches(G, mode):
-    # the fetching kernel, a limited number of workgroups, and launches small enough to split the keys
-    if mode == "persistent":
-        os.environ["KUN_PREFILL_SHAPE"] = "persistent"
+    # the fetching kernel, a limited number of workgroups, launches small enough to split the keys,
+    # and the other tile shapes
+    if mode not in ("on16", "split"):
+        os.environ["KUN_PREFILL_SHAPE"] = mode
     sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=128, B=64, dtype="bf16")
     sets = ([(3000, 40)], [(5000, 200), (17, 3)], [(1500, 64), (64, 64), (9000, 5)]) if mode == "split" else \
         ([(0, 1), (63, 65), (64, 129), (100, 200), (0, 300), (700, 257), (1000, 31), (3000, 40), (0, 2100)],)

@@ -354,6 +354,32 @@ def test_kv_append_slot_map_and_layout():
         assert np.array_equal(synth.to_host_bits(a), synth.to_host_bits(b), equal_nan=True)
 
 
+def test_page_of_64_tokens_is_four_pages_of_16_tokens_in_a_row():
+    # the layout inside a block (this library's ABI): tiles of 16 tokens.  With one KV head a block of
+    # 64 tokens must be byte-identical to blocks 0..3 of a pool of 16-token blocks holding the same
+    # tokens; two offsets worked out by hand pin the page and tile strides with two KV heads.
+    rng = np.random.default_rng(5)
+    d, L = 8, 150
+    k = rng.standard_normal((L, 1, d)).astype(np.float32)
+    v = rng.standard_normal((L, 1, d)).astype(np.float32)
+    seqs, poss = [0] * L, list(range(L))
+    p64 = O.OraclePool([np.zeros(3 * 2 * 64 * d, np.float32)], 1, d, 64, "f32")
+    p16 = O.OraclePool([np.zeros(12 * 2 * 16 * d, np.float32)], 1, d, 16, "f32")
+    O.kv_append(p64, k, v, seqs, poss, np.array([[0, 1, 2]]))
+    O.kv_append(p16, k, v, seqs, poss, np.arange(12)[None, :])
+    assert np.array_equal(p64.ranges[0], p16.ranges[0])
+    K, V = O.gather_kv(p64, [0, 1, 2], L, 0)
+    assert np.array_equal(K, k[:, 0].astype(np.float64)) and np.array_equal(V, v[:, 0].astype(np.float64))
+    # two KV heads, d = 8: block 1, head 1 starts at (1*2+1) * 2*64*8 = 3072; slot 37 is slot 5 of tile 2,
+    # tiles are 2*16*8 = 256 elements: K[37][3] at 3072 + 512 + 5*8 + 3, V[37][3] at 3072 + 512 + 128 + 3*16 + 5
+    p2 = O.OraclePool([np.zeros(2 * 2 * 2 * 64 * d, np.float32)], 2, d, 64, "f32")
+    assert O.k_elem_offset(p2, 1, 1, 37) + 3 == 3627
+    assert O.v_elem_offset(p2, 1, 1, 37, 3) == 3765
+    # blocks of at most 16 tokens are one tile: K rows, then V columns
+    p4 = O.OraclePool([np.zeros(2 * 2 * 4 * d, np.float32)], 2, d, 4, "f32")
+    assert O.k_elem_offset(p4, 0, 1, 3) == 64 + 24 and O.v_elem_offset(p4, 0, 1, 3, 2) == 64 + 32 + 2 * 4 + 3
+
+
 # ------------------------------------------------------------------------------------------
 # the generator itself
 # ------------------------------------------------------------------------------------------

@@ -34,7 +34,7 @@ struct DecodeArgs {
     const int32_t* row_of_seq;  // optional: block-table row of each request (NULL: request s uses row s)
     int32_t* n_items;        // workspace: number of work items (written by plan)
     int32_t* seq_first;      // workspace: [S + 1] first item of each request
-    int4* items;             // workspace: (request, partition, the request's context length, 0)
+    int4* items;             // workspace: (request, partition, the request's context length, record slot)
     float* part_ml;          // workspace: [item, kvh, G, 2]  (m in log2 units, l)
     float* part_acc;         // workspace: [item, kvh, G, d]
     int max_blocks;
@@ -49,46 +49,73 @@ struct DecodeArgs {
 // ---------------------------------------------------------------------------------------------
 // 1. plan
 // ---------------------------------------------------------------------------------------------
+// Record slots (where a partition's partial result goes) count through the requests in order:
+// request s owns slots seq_first[s] .. seq_first[s + 1] - 1.  The work list is ordered for the
+// launch instead: first every full partition (all the same length), then the requests' last,
+// shorter partitions from long to short (counting sort over kLenBuckets length classes), so that
+// the workgroups that start last are the shortest ones.  An entry is (request, partition, context
+// length, record slot).
+constexpr int kLenBuckets = 32;
 __global__ __launch_bounds__(1024) void decode_plan_kernel(const int32_t* __restrict__ ctx_len, int S,
                                                          int part_tokens, int max_items,
                                                          int32_t* __restrict__ n_items,
                                                          int32_t* __restrict__ seq_first,
                                                          int4* __restrict__ items) {
-    __shared__ int wave_tot[16];
-    __shared__ int carry_s;
+    __shared__ int wave_tot[16], wave_full[16];
+    __shared__ int carry_s, carry_full;
+    __shared__ int bucket[kLenBuckets];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) carry_s = 0;
+    if (tid == 0) { carry_s = 0; carry_full = 0; }
+    if (tid < kLenBuckets) bucket[tid] = 0;
     __syncthreads();
     for (int s0 = 0; s0 < S; s0 += 1024) {
         const int s = s0 + tid;
-        int np = 0, L = 0;
+        int np = 0, nfull = 0, L = 0;
         if (s < S) {
             L = ctx_len[s];
-            np = L > 0 ? (L + part_tokens - 1) / part_tokens : 0;
+            if (L < 0) L = 0;
+            nfull = L / part_tokens;
+            np = (L + part_tokens - 1) / part_tokens;
         }
-        int incl = np;                       // inclusive scan inside the wave
+        int incl = np, incl_f = nfull;       // inclusive scans inside the wave
         for (int o = 1; o < 64; o <<= 1) {
-            int y = __shfl_up(incl, o);
-            if (lane >= o) incl += y;
+            const int y = __shfl_up(incl, o), yf = __shfl_up(incl_f, o);
+            if (lane >= o) { incl += y; incl_f += yf; }
         }
-        if (lane == 63) wave_tot[wave] = incl;
+        if (lane == 63) { wave_tot[wave] = incl; wave_full[wave] = incl_f; }
         __syncthreads();
-        int before = carry_s;
-        for (int w = 0; w < wave; ++w) before += wave_tot[w];
-        const int first = before + incl - np;
+        int before = carry_s, before_f = carry_full;
+        for (int w = 0; w < wave; ++w) { before += wave_tot[w]; before_f += wave_full[w]; }
+        const int first = before + incl - np, first_f = before_f + incl_f - nfull;
         if (s < S) {
             seq_first[s] = first;
-            for (int p = 0; p < np; ++p)
-                if (first + p < max_items) items[first + p] = make_int4(s, p, L, 0);
+            for (int p = 0; p < nfull; ++p)
+                if (first_f + p < max_items) items[first_f + p] = make_int4(s, p, L, first + p);
+            if (np > nfull) atomicAdd(&bucket[(part_tokens - (L - nfull * part_tokens)) * kLenBuckets / part_tokens], 1);
         }
         __syncthreads();
-        if (tid == 1023) carry_s = first + np;
+        if (tid == 1023) { carry_s = first + np; carry_full = first_f + nfull; }
         __syncthreads();
     }
     if (tid == 0) {
-        int tot = carry_s;
+        int at = carry_full;                 // the shorter partitions follow the full ones, bucket 0 (longest) first
+        for (int b = 0; b < kLenBuckets; ++b) {
+            const int n = bucket[b];
+            bucket[b] = at;
+            at += n;
+        }
+        const int tot = carry_s;
         seq_first[S] = tot;
         *n_items = tot < max_items ? tot : max_items;
+    }
+    __syncthreads();
+    for (int s = tid; s < S; s += 1024) {
+        const int L = ctx_len[s];
+        if (L <= 0) continue;
+        const int nfull = L / part_tokens, rem = L - nfull * part_tokens;
+        if (rem == 0) continue;
+        const int pos = atomicAdd(&bucket[(part_tokens - rem) * kLenBuckets / part_tokens], 1);
+        if (pos < max_items) items[pos] = make_int4(s, nfull, L, seq_first[s] + nfull);
     }
 }
 
@@ -136,7 +163,7 @@ template <> struct Elem<bf16_t> {
 // Combine the per-wave partial results held in LDS and write either the final output row (request
 // with one partition) or the item's partial record.  sm_m/sm_l: [NW][G]; sm_acc: [NW][G][D].
 template <typename T, int D, int NW>
-__device__ __forceinline__ void finish_item(const DecodeArgs& a, int item, int kvh, int seq, int nparts,
+__device__ __forceinline__ void finish_item(const DecodeArgs& a, int slot, int kvh, int seq, int nparts,
                                             int G, const float* sm_m, const float* sm_l,
                                             const float* sm_acc) {
     for (int idx = threadIdx.x; idx < G * D; idx += blockDim.x) {
@@ -156,7 +183,7 @@ __device__ __forceinline__ void finish_item(const DecodeArgs& a, int item, int k
             T* o = (T*)a.out + ((size_t)seq * a.Hkv * G + (size_t)kvh * G + g) * D + j;
             Elem<T>::store(o, acc / l);
         } else {
-            const size_t rec = ((size_t)item * a.Hkv + kvh) * G + g;
+            const size_t rec = ((size_t)slot * a.Hkv + kvh) * G + g;
             a.part_acc[rec * D + j] = acc;
             if (j == 0) {
                 a.part_ml[rec * 2 + 0] = M;
@@ -187,7 +214,7 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
     const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
     const int n_items = *a.n_items;                    // both loads go out together: the list is as long as the grid
     const int4 it4 = a.items[item];                    // the length rides along: one dependent load less
-    if (item >= n_items) return;
+    if (item >= n_items || it4.w >= a.max_items) return;   // (a record slot beyond the workspace: the caller's bound was too small)
     const int seq = it4.x, part = it4.y;
     const int L = it4.z;
     const int nparts = (L + a.part_tokens - 1) / a.part_tokens;
@@ -295,7 +322,7 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
         for (int i = 0; i < DPL; ++i) sm_acc[(wave * G + g) * D + lane + 64 * i] = acc[g][i];
     }
     __syncthreads();
-    finish_item<T, D, NW>(a, item, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
+    finish_item<T, D, NW>(a, it4.w, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -336,7 +363,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
     const int n_items = *a.n_items;                    // both loads go out together: the list is as long as the grid
     const int4 it4 = a.items[item];                    // the length rides along: one dependent load less
-    if (item >= n_items) return;
+    if (item >= n_items || it4.w >= a.max_items) return;   // (a record slot beyond the workspace: the caller's bound was too small)
     const int seq = it4.x, part = it4.y;
     const int G = a.G;
     const int L = it4.z;
@@ -517,7 +544,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
             for (int i = 0; i < 4; ++i) sm_acc[(wave * G + n) * D + s * 16 + 4 * j + i] = o[s][i];
     }
     __syncthreads();
-    finish_item<bf16_t, D, NW>(a, item, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
+    finish_item<bf16_t, D, NW>(a, it4.w, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -73,15 +73,28 @@ def test_config3_pool_extended_twice_mid_run():
     dw.close()
 
 
-def test_config4_mixed_batch_decode_part():
-    w = synth.config(4)
+@pytest.mark.parametrize("block_size", [16, 64])
+def test_config4_mixed_batch_decode_part(block_size):
+    w = synth.config(4, block_size)
     dw = DeviceWorkload(w)
-    dw.prefill()                                         # mixed batch: both calls on one stream
+    pre = dw.prefill().clone()                           # mixed batch: both calls on one stream
     out = dw.decode().clone()
     torch.cuda.synchronize()
     err = decode_err(dw, out, list(range(w.S)))
     print("cfg4 decode max err", err)
     assert err <= TOL
+    if block_size == 64:                                 # (blocks of 16 tokens: the prefill tests and cfg5 below)
+        sh = w.shape
+        rng = np.random.default_rng(4)
+        got = pre.double().cpu().numpy()
+        for i, (p, c) in enumerate(w.chunks):
+            q0 = int(dw.q_start_host[i])
+            rws = sorted(set([0, c - 1] + rng.choice(c, size=12, replace=False).tolist()))
+            pool, tab = bridge.compact_pool(dw.ranges, w.range_blocks, [w.block_tables[w.S + i]], [p + c], sh.Hkv,
+                                            sh.d, sh.B, sh.dtype)
+            ref, _ = O.paged_prefill_chunk(pool, bridge.host_bits(dw.q_pre[q0:q0 + c]), tab[0], p, c, sh.Hq,
+                                           sh.scale, rows=rws)
+            assert float(np.abs(got[q0:q0 + c][rws] - ref).max()) <= TOL
     dw.close()
 
 

@@ -157,7 +157,9 @@ KUN_API size_t kun_decode_workspace_bytes(const kun_kv_pool* pool, int S, int nu
  * out[s] = softmax(scale * q K^T) V over those tokens.  ctx_len: device int32 [S]; a request with
  * ctx_len 0 is skipped and its output row left untouched.  block_table: device int32
  * [S, max_blocks].  total_ctx_upper_bound: host-known bound on sum(ctx_len) (0 = full pool); it
- * sizes the launch and must be the value used for kun_decode_workspace_bytes or smaller.
+ * sizes the launch and must be the value used for kun_decode_workspace_bytes or smaller.  If
+ * sum(ctx_len) is above it, the requests whose partial results no longer fit the workspace are
+ * left out as a whole (their rows of out stay untouched); nothing is read or written out of bounds.
  * workspace: device, 256-byte aligned, holds the split-K partial results; contents are scratch. */
 KUN_API int kun_paged_decode(kun_kv_pool* pool, const void* q, void* out, const int32_t* block_table,
                      int max_blocks, const int32_t* ctx_len, int S, int num_q_heads, float scale,

@@ -109,13 +109,24 @@ __global__ __launch_bounds__(1024) void decode_plan_kernel(const int32_t* __rest
         *n_items = tot < max_items ? tot : max_items;
     }
     __syncthreads();
+    if (carry_s > max_items) {
+        // More partitions than the caller's bound allows for: list position = record slot, in request
+        // order, so that exactly the requests whose slots all fit are computed, and completely.
+        for (int s = tid; s < S; s += 1024) {
+            const int L = ctx_len[s], first = seq_first[s];
+            const int np = L > 0 ? (L + part_tokens - 1) / part_tokens : 0;
+            for (int p = 0; p < np && first + p < max_items; ++p)
+                items[first + p] = make_int4(s, p, L, first + np <= max_items ? first + p : max_items);
+        }
+        return;
+    }
     for (int s = tid; s < S; s += 1024) {
         const int L = ctx_len[s];
         if (L <= 0) continue;
         const int nfull = L / part_tokens, rem = L - nfull * part_tokens;
         if (rem == 0) continue;
         const int pos = atomicAdd(&bucket[(part_tokens - rem) * kLenBuckets / part_tokens], 1);
-        if (pos < max_items) items[pos] = make_int4(s, nfull, L, seq_first[s] + nfull);
+        items[pos] = make_int4(s, nfull, L, seq_first[s] + nfull);
     }
 }
 

@@ -44,6 +44,7 @@ struct DecodeArgs {
     int max_items;
     float scale_log2;        // softmax scale * log2(e)
     unsigned block_bytes, page_bytes;
+    int xcd_map;             // MFMA kernel: the KV heads of a work item run on one XCD
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -371,9 +372,20 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     __shared__ float sm_m[NW * GMAX], sm_l[NW * GMAX];
     __shared__ float sm_acc[NW * 8 * D];      // G <= 8 heads kept (G <= 8 is enforced on the host)
 
-    const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
-    const int n_items = *a.n_items;                    // both loads go out together: the list is as long as the grid
-    const int4 it4 = a.items[item];                    // the length rides along: one dependent load less
+    // Workgroups are handed to the 8 XCDs round-robin.  The KV heads of one work item read the same
+    // blocks (one page each), so they are given consecutive slots of ONE XCD: they then run side by
+    // side behind one L2 and one set of address translations (xcd_map; otherwise item-major order).
+    int item, kvh;
+    if (a.xcd_map) {
+        const int x = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        kvh = slot % a.Hkv;
+        item = (slot / a.Hkv) * 8 + x;
+    } else {
+        item = blockIdx.x / a.Hkv;
+        kvh = blockIdx.x % a.Hkv;
+    }
+    const int n_items = *a.n_items;                    // both loads go out together
+    const int4 it4 = a.items[item < a.max_items ? item : a.max_items - 1];   // the length rides along: one dependent load less
     if (item >= n_items || it4.w >= a.max_items) return;   // (a record slot beyond the workspace: the caller's bound was too small)
     const int seq = it4.x, part = it4.y;
     const int G = a.G;
@@ -710,6 +722,7 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
     a.scale_log2 = scale * kLog2e;
     a.block_bytes = (unsigned)p->block_bytes;
     a.page_bytes = (unsigned)p->page_bytes;
+    a.xcd_map = 0;
     const int nb = (T + 256) / 256;
     hipLaunchKernelGGL(rows_plan_kernel, dim3((unsigned)(nb < 1024 ? nb : 1024)), dim3(256), 0, st, T, a.n_items,
                        a.seq_first, a.items, ctx_len);
@@ -780,12 +793,13 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     a.scale_log2 = scale * kLog2e;
     a.block_bytes = (unsigned)p->block_bytes;
     a.page_bytes = (unsigned)p->page_bytes;
+    a.xcd_map = 0;
 
     hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(1024), 0, st, ctx_len, S, P, lay.max_items,
                        a.n_items, a.seq_first, a.items);
     KUN_HIP_CHECK_LAUNCH();
 
-    const dim3 grid((unsigned)((size_t)lay.max_items * p->Hkv));
+    dim3 grid((unsigned)((size_t)lay.max_items * p->Hkv));
     const char* force = getenv("KUN_DECODE_KERNEL");     // "generic" forces the vector-ALU kernel
     const bool generic_only = force && force[0] == 'g';
     int rc = KUN_OK;
@@ -793,6 +807,9 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
         int nw = 4;
         const char* e = getenv("KUN_DECODE_WAVES");
         if (e) nw = atoi(e);
+        const char* map = getenv("KUN_DECODE_MAP");      // "flat": item-major workgroup order
+        a.xcd_map = !(map && map[0] == 'f');
+        if (a.xcd_map) grid = dim3((unsigned)(((size_t)lay.max_items + 7) / 8 * 8 * p->Hkv));
         if (p->B == 64) {
             if (nw == 1) hipLaunchKernelGGL((decode_partial_mfma<1, 4>), grid, dim3(64), 0, st, a);
             else if (nw == 2) hipLaunchKernelGGL((decode_partial_mfma<2, 4>), grid, dim3(128), 0, st, a);

@@ -22,7 +22,7 @@
 
 namespace {
 
-constexpr int kBlock = 16;           // tokens per step of the kernels: a 16-token block, or a quarter of a 64-token block
+constexpr int kBlock = 16;           // tokens per page tile: a 16-token block, or one of the four tiles of a 64-token block
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct DecodeArgs {
@@ -340,7 +340,7 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
 // ---------------------------------------------------------------------------------------------
 // 2b. MFMA partial kernel: bf16, head_dim 128, blocks of 16 or 64 tokens, G <= 8.
 //
-// Each wave walks PAIRS of blocks (32 tokens).  With lane = 16 * j + n:
+// Each wave walks PAIRS of 16-token page tiles (32 tokens).  With lane = 16 * j + n:
 //   QK^T  S^T[token][head] = K[token][:] . Q[head][:]   as 2 tiles x 4 MFMA 16x16x32
 //         A = K rows (lane n picks the tile row's token, j picks the 16-byte chunk 4*kk + j of
 //         the row), B = Q (lane n = head, same chunk).  Tile rows are mapped to tokens so that

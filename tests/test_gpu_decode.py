@@ -46,6 +46,7 @@ def _announce(request):
     os.environ.pop("KUN_DECODE_KERNEL", None)
     os.environ.pop("KUN_DECODE_PART", None)
     os.environ.pop("KUN_DECODE_WAVES", None)
+    os.environ.pop("KUN_DECODE_MAP", None)
 
 
 def test_config1_tiny_fp32():
@@ -152,6 +153,27 @@ def test_bound_below_the_real_context_sum_computes_whole_requests_or_none(part):
         if bound > 1000:
             assert done > 0
     os.environ.pop("KUN_DECODE_PART", None)
+    dw.close()
+
+
+@pytest.mark.parametrize("B", [16, 64])
+def test_workgroup_order_does_not_change_a_bit(B):
+    # XCD-aware order (default) against item-major order, with a number of work items that is not a
+    # multiple of 8 and requests of one and of many partitions
+    sh = synth.LayerShape(Hq=16, Hkv=2, d=128, B=B, dtype="bf16")
+    lens = [700, 33, 1500, 64, 900, 2100, 5, 1200, 300, 800, 4100]
+    w = synth.custom_workload("order", sh, lens, extra_blocks=3, range_fracs=(0.5, 0.5))
+    dw = DeviceWorkload(w)
+    outs = {}
+    for mode in ("xcd", "flat"):
+        os.environ["KUN_DECODE_MAP"] = mode
+        dw.out_dec.fill_(float("nan"))
+        outs[mode] = dw.decode().clone()
+        torch.cuda.synchronize()
+    os.environ.pop("KUN_DECODE_MAP")
+    assert torch.isfinite(outs["xcd"].float()).all()
+    assert torch.equal(outs["xcd"].view(torch.int16), outs["flat"].view(torch.int16))
+    check_decode(dw)
     dw.close()
 
 

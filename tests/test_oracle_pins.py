@@ -323,19 +323,20 @@ def test_kv_bytes_match_papers_per_token_figure():
     assert synth.SHAPE_8B.block_bytes == 65536 and synth.SHAPE_TINY.block_bytes == 16384
 
 
-def test_kv_append_slot_map_and_layout():
-    sh = tiny_shape("f32", Hq=2, Hkv=2, d=4, B=4)
-    w = synth.custom_workload("t", sh, [6, 3], extra_blocks=2, range_fracs=(0.5, 0.5))
+@pytest.mark.parametrize("B,lens", [(4, [6, 3]), (16, [40, 16, 1]), (64, [150, 64, 65, 3])])
+def test_kv_append_slot_map_and_layout(B, lens):
+    sh = tiny_shape("f32", Hq=2, Hkv=2, d=4, B=B)
+    w = synth.custom_workload("t", sh, lens, extra_blocks=2, range_fracs=(0.5, 0.5))
     ranges = synth.alloc_ranges(w, "cpu")
     pool = O.OraclePool([synth.to_host_bits(r).reshape(-1) for r in ranges], sh.Hkv, sh.d, sh.B,
                         sh.dtype)
     seqs, poss, ks, vs = [], [], [], []
-    for s in range(2):
+    for s in range(len(lens)):
         L = int(w.decode_lens[s])
         k, v = synth.kv_logical(w, s, 0, L)
         ks.append(k); vs.append(v)
         seqs += [s] * L; poss += list(range(L))
-    tab = w.table_array([0, 1])
+    tab = w.table_array(range(len(lens)))
     slots = O.kv_append(pool, torch.cat(ks).numpy(), torch.cat(vs).numpy(), seqs, poss, tab)
     # expected slot map by direct enumeration
     firsts = np.concatenate([[0], np.cumsum(w.range_blocks)])
@@ -343,7 +344,7 @@ def test_kv_append_slot_map_and_layout():
         blk = int(w.block_tables[s][t // sh.B])
         assert firsts[r] + local == blk and slot == t % sh.B
     # the appended pages read back as the logical K/V, and agree with the generator's own writer
-    for s in range(2):
+    for s in range(len(lens)):
         for kvh in range(sh.Hkv):
             K, V = O.gather_kv(pool, tab[s], int(w.decode_lens[s]), kvh)
             assert np.array_equal(K, ks[s][:, kvh].double().numpy())

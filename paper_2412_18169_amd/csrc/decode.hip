@@ -616,9 +616,9 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a, i
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-constexpr int kPartChoices[] = {256, 512, 1024, 2048, 4096};
-constexpr int kNumPartChoices = 5;
-constexpr int kPartDivisor = 2048;    // aim at >= this many (partition, kv head) workgroups
+constexpr int kPartChoices[] = {256, 512, 1024, 2048, 4096, 8192};
+constexpr int kNumPartChoices = 6;
+constexpr int kPartDivisor = 1024;    // aim at >= this many (partition, kv head) workgroups
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -628,8 +628,9 @@ int64_t default_bound(const kun_kv_pool* p, int S, int64_t ub) {
     return ub;
 }
 
-// Partition size: the largest choice that still leaves a few thousand workgroups (256 CUs, several
-// workgroups each); measured best on the 8B/70B-shaped batches.
+// Partition size: the largest choice that still leaves about a thousand workgroups (256 CUs, two
+// resident workgroups each, and a work list that starts the long partitions first); measured best
+// on the 8B/70B-shaped batches.
 int choose_part_tokens(const kun_kv_pool* p, int64_t ub) {
     const char* e = getenv("KUN_DECODE_PART");
     if (e) {

@@ -101,14 +101,24 @@ def main():
     T_new = len(seqs)
     has_prefill = w.n_chunks > 0 and PREFILL_SUPPORTED
 
+    # A working set below 1 GB could be served in part by the 256 MB last-level cache when the same
+    # pool is read step after step: such configurations alternate between two pools (same requests and
+    # contents, separate buffers), so every step reads pages that the step before did not touch.
+    dws = [dw]
+    if decode_bytes(w) < 10**9:
+        dws.append(DeviceWorkload(w, poison=True))
+    step_no = [0]
+
     def step(ev=None):
+        d = dws[step_no[0] % len(dws)]
+        step_no[0] += 1
         if ev: ev[0].record()
-        kun.kun_kv_append(dw.pool, k_new, v_new, seq_of, pos_of, T_new, all_table, all_table.shape[1])
+        kun.kun_kv_append(d.pool, k_new, v_new, seq_of, pos_of, T_new, all_table, all_table.shape[1])
         if ev: ev[1].record()
         if has_prefill:
-            dw.prefill()
+            d.prefill()
         if ev: ev[2].record()
-        dw.decode()
+        d.decode()
         if ev: ev[3].record()
 
     if args.pmc_calibration:
@@ -141,7 +151,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype,
         "data": "synthetic",
-        "config": {"workload": f"cfg{cfg}:{w.name}", "block_size": w.shape.B, "decode_requests": w.S, "prefill_chunks": w.n_chunks if has_prefill else 0,
+        "config": {"workload": f"cfg{cfg}:{w.name}", "block_size": w.shape.B, "pools_alternated": len(dws), "decode_requests": w.S, "prefill_chunks": w.n_chunks if has_prefill else 0,
                    "Hq": sh.Hq, "Hkv": sh.Hkv, "head_dim": sh.d, "block_size": sh.B,
                    "pool_ranges": len(w.range_blocks), "pool_GB": round(w.num_blocks * sh.block_bytes / 1e9, 2),
                    "decode_kv_tokens": w.decode_kv_tokens, "seed": w.seed},
@@ -174,7 +184,8 @@ def main():
         out["cpu_baseline"], out["max_abs_err_vs_oracle"] = cpu_baseline(dw, args.cpu_seconds)
         if has_prefill:
             out["prefill_max_abs_err_vs_oracle"] = prefill_check(dw)
-    dw.close()
+    for d in dws:
+        d.close()
     print(json.dumps(out), flush=True)
 
 

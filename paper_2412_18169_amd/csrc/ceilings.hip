@@ -83,13 +83,17 @@ __global__ __launch_bounds__(256) void read_linear(const u32x4* __restrict__ p, 
 // The decode kernel's pattern: a workgroup of 4 waves walks `blocks_per_wg` hashed 64 KiB blocks of the
 // buffer for one of 8 KV heads; a wave takes two blocks per step and reads the head's 8 KiB page (K +
 // V^T) of each with sixteen 16-byte loads per lane.
-template <bool NT>
+// XCD: the 8 heads of a group of blocks take consecutive slots of one XCD (workgroups go to the 8
+// XCDs round-robin) instead of one slot on each.
+template <bool NT, bool XCD>
 __global__ __launch_bounds__(256) void read_pages(const u32x4* __restrict__ p, size_t nblocks, int blocks_per_wg,
                                                   unsigned* sink) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int head = blockIdx.x & 7;
+    const unsigned slot = blockIdx.x >> 3;
+    const int head = XCD ? (slot & 7) : (blockIdx.x & 7);
+    const size_t group = XCD ? (size_t)(slot >> 3) * 8 + (blockIdx.x & 7) : slot;
     unsigned s = 0;
-    const size_t first = (size_t)(blockIdx.x >> 3) * blocks_per_wg;
+    const size_t first = group * blocks_per_wg;
     for (int b = wave * 2; b < blocks_per_wg; b += 8) {
         u32x4 v[16];
 #pragma unroll
@@ -118,12 +122,13 @@ static void run_hbm(size_t gib) {
     std::printf("hbm linear read of 16 GiB, %zu GiB buffer:              %.0f GB/s | non-temporal loads %.0f GB/s\n", gib,
                 lin / t0 / 1e6, lin / t1 / 1e6);
     const int bpw = 64;                                    // 64 blocks = 1024 tokens per workgroup
-    const size_t wg_groups = 260000 / bpw;                 // about 17 GB, the 70B-shaped decode step
+    const size_t wg_groups = 260000 / bpw / 8 * 8;         // about 17 GB, the 70B-shaped decode step
     const double page_bytes = (double)wg_groups * bpw * 8 * 8192;
-    const float t2 = time_ms([&] { read_pages<false><<<(unsigned)(wg_groups * 8), 256>>>(buf, nblocks, bpw, sink); }, 3);
-    const float t3 = time_ms([&] { read_pages<true><<<(unsigned)(wg_groups * 8), 256>>>(buf, nblocks, bpw, sink); }, 3);
-    std::printf("hbm scattered 8 KiB pages (17 GB of a %zu GiB buffer):  %.0f GB/s | non-temporal loads %.0f GB/s\n", gib,
-                page_bytes / t2 / 1e6, page_bytes / t3 / 1e6);
+    const float t2 = time_ms([&] { read_pages<false, false><<<(unsigned)(wg_groups * 8), 256>>>(buf, nblocks, bpw, sink); }, 3);
+    const float t3 = time_ms([&] { read_pages<true, false><<<(unsigned)(wg_groups * 8), 256>>>(buf, nblocks, bpw, sink); }, 3);
+    const float t4 = time_ms([&] { read_pages<true, true><<<(unsigned)(wg_groups * 8), 256>>>(buf, nblocks, bpw, sink); }, 3);
+    std::printf("hbm scattered 8 KiB pages (17 GB of a %zu GiB buffer):  %.0f GB/s | non-temporal loads %.0f GB/s | and the 8 heads"
+                " of a block on one XCD %.0f GB/s\n", gib, page_bytes / t2 / 1e6, page_bytes / t3 / 1e6, page_bytes / t4 / 1e6);
     CK(hipFree(buf));
     CK(hipFree(sink));
 }

@@ -184,3 +184,19 @@ def test_resize_of_the_last_range_matches_oracle_bit_exact():
         kun.kun_kv_pool_resize_tail(p, BB * 101)
     assert e.value.status == -9
     kun.kun_kv_pool_destroy(p)
+
+
+def test_header_and_host_entry_points_from_plain_c(tmp_path):
+    # include/kun.h compiles as C99 with warnings as errors, and a C program linked against the
+    # library gets the documented results from the host-only calls (tests/c_abi_client.c)
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    libdir = os.path.join(ROOT, "paper_2412_18169_amd")
+    exe = str(tmp_path / "c_abi_client")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "c_abi_client.c"), "-o", exe, "-L", libdir, "-lkun", "-lm",
+                    "-Wl,-rpath," + libdir], check=True, capture_output=True, text=True)
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert run.returncode == 0 and "c abi ok" in run.stdout, run.stdout + run.stderr

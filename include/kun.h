@@ -29,8 +29,9 @@
  *     K  [16 tokens][head_dim]      then
  *     V  [head_dim][16 tokens]      (V is stored transposed inside a tile)
  *   (a page of 64 tokens is laid out as four pages of 16 tokens in a row: every kernel reads whole,
- *   contiguous tiles whatever the block size), so block_bytes = 2 * num_kv_heads * block_size * head_dim * sizeof(element); with 8 KV heads
- *   of 128 dims in bf16 that is 4096 bytes per token per layer, the figure behind the 192 KB per
+ *   contiguous tiles whatever the block size), so
+ *   block_bytes = 2 * num_kv_heads * block_size * head_dim * sizeof(element); with 8 KV heads of
+ *   128 dims in bf16 that is 4096 bytes per token per layer, the figure behind the 192 KB per
  *   token of a 48-layer model quoted in Section 2.2.
  *   Query heads h with the same h / (num_q_heads / num_kv_heads) share a KV head (GQA).
  *

@@ -424,7 +424,7 @@ def prefill_check(dw, rows_per_chunk=6):
 DEFAULT_CONFIG = 5
 PREFILL_SUPPORTED = True
 ORACLE_TOKENS_PER_S = 80000.0      # rough speed of the numpy oracle, only used to size its sample
-TRAFFIC_BYTES = {5: 17334426202}                 # per-launch HBM bytes from rocprofv3 --pmc runs (see profiles/)
+TRAFFIC_BYTES = {5: 17322737541}                 # per-launch HBM bytes from rocprofv3 --pmc runs (see profiles/)
 
 if __name__ == "__main__":
     main()

@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--config", type=int, default=0, help="workload 2..5 (default: the largest supported)")
     ap.add_argument("--block-size", type=int, default=0, choices=[0, 16, 64],
                     help="tokens per KV block (default: the configuration's own, 16)")
+    ap.add_argument("--q-heads", type=int, default=0,
+                    help="query heads (default: the configuration's own); e.g. 40 over the 8 KV heads of cfg 2-4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mixed", action="store_true",
                     help="skip the side-by-side prefill + decode measurement (keeps profiles to the K timed steps)")
@@ -79,7 +81,7 @@ def main():
         sys.exit(2)
     cfg = args.config or DEFAULT_CONFIG
     t_setup = time.time()
-    w = synth.config(cfg, args.block_size)
+    w = synth.config(cfg, args.block_size, args.q_heads)
     sh = w.shape
     dw = DeviceWorkload(w, poison=(cfg != 5))
     torch.cuda.synchronize()

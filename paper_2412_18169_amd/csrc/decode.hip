@@ -673,7 +673,11 @@ int launch_generic(const DecodeArgs& a, dim3 grid, hipStream_t st) {
     switch (a.G) {
         case 1: hipLaunchKernelGGL((decode_partial_generic<T, D, 1>), grid, dim3(256), 0, st, a); break;
         case 2: hipLaunchKernelGGL((decode_partial_generic<T, D, 2>), grid, dim3(256), 0, st, a); break;
+        case 3: hipLaunchKernelGGL((decode_partial_generic<T, D, 3>), grid, dim3(256), 0, st, a); break;
         case 4: hipLaunchKernelGGL((decode_partial_generic<T, D, 4>), grid, dim3(256), 0, st, a); break;
+        case 5: hipLaunchKernelGGL((decode_partial_generic<T, D, 5>), grid, dim3(256), 0, st, a); break;
+        case 6: hipLaunchKernelGGL((decode_partial_generic<T, D, 6>), grid, dim3(256), 0, st, a); break;
+        case 7: hipLaunchKernelGGL((decode_partial_generic<T, D, 7>), grid, dim3(256), 0, st, a); break;
         case 8: hipLaunchKernelGGL((decode_partial_generic<T, D, 8>), grid, dim3(256), 0, st, a); break;
         default: return KUN_ERR_UNSUPPORTED;
     }
@@ -763,7 +767,7 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     if (S == 0) return KUN_OK;
     if (!q || !out || !block_table || !ctx_len || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
     const int G = Hq / p->Hkv;
-    if (G != 1 && G != 2 && G != 4 && G != 8) return KUN_ERR_UNSUPPORTED;
+    if (G < 1 || G > 8) return KUN_ERR_UNSUPPORTED;
     ub = default_bound(p, S, ub);
     const int P = choose_part_tokens(p, ub);
     const DecodeLayout lay = layout_for(p, S, Hq, ub, P);

@@ -500,9 +500,11 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     constexpr int NSTAGERS = 8;                        // waves that issue the tile loads (4 loads per lane and tile)
     constexpr int NT = 64 * NSTAGERS, LOADS = 2;
     static_assert(NW >= NSTAGERS, "the first 8 waves stage the tiles");
-    constexpr int ROWS_W = 32, ROWS = NW * ROWS_W, POS = ROWS / G, POS_W = ROWS_W / G;
+    // A wave holds POS_W whole positions = POS_W * G rows; when G does not divide 32 its last rows
+    // (32 - POS_W * G of them: 2 for G = 3, 5, 6 and 4 for G = 7) are dead.
+    constexpr int ROWS_W = 32, POS_W = ROWS_W / G, POS = NW * POS_W, LIVE_W = POS_W * G;
     constexpr int NSTAGE = 4, AHEAD = 3;
-    static_assert(ROWS_W % G == 0, "a wave must hold whole positions");
+    static_assert(G >= 1 && G <= 8, "1 to 8 query heads per KV head");
 
     __shared__ __attribute__((aligned(16))) unsigned char ring[NSTAGE][2 * kBlocksPerTile * 4096];
     constexpr int V_OFF = kBlocksPerTile * 4096;       // V^T pages follow the K pages inside a stage
@@ -617,10 +619,10 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     }
 
     Frag qf[8];
-    int pos = pos0 + (wave * ROWS_W + n) / G;
-    const int g_head = (wave * ROWS_W + n) % G;
-    const bool live_row = pos < c;
-    if (!live_row) pos = c - 1;
+    int pos = wpos0 + n / G;
+    const int g_head = n % G;
+    const bool live_row = n < LIVE_W && pos < c;
+    if (!live_row) pos = min(wpos0, c - 1);            // a dead row repeats a row the wave (or the chunk) does have
     const int vis = p + pos;                           // last key this lane's row sees
     {
         const char* qrow = (const char*)a.q + (((size_t)(qs + pos)) * a.Hq + kvh * G + g_head) * (D * 2);
@@ -880,8 +882,9 @@ __global__ __launch_bounds__(kSplitRows) void prefill_merge_kernel(const Prefill
     const int qs = a.q_start[chunk];
     const int c = a.q_start[chunk + 1] - qs;
     const int row = threadIdx.x;
-    const int pos = qt * (kSplitRows / G) + row / G, head = row % G;
-    if (pos >= c) return;
+    const int pos_w = 32 / G, rw = row & 31;           // the ring kernel's rows: wave row / 32 holds pos_w positions
+    const int pos = qt * (kSplitRows / 32 * pos_w) + (row >> 5) * pos_w + rw / G, head = rw % G;
+    if (rw >= pos_w * G || pos >= c) return;
     float w[kMaxSplit];
     float M = -INFINITY;
     for (int sp = 0; sp < nsplit; ++sp)
@@ -965,6 +968,14 @@ int device_compute_units() {
 }
 
 int rows_per_wg(TileShape t) { return t.nw * 32 * t.nq; }
+// query positions per workgroup: every 32 rows hold floor(32 / G) whole positions
+int pos_per_wg(TileShape t, int G) { return rows_per_wg(t) / 32 * (32 / G); }
+
+template <int G>
+void launch_ring(const PrefillArgs& a, dim3 grid, bool persistent, hipStream_t st) {
+    if (persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, true>), grid, dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((prefill_ring_kernel<G, 8, false>), grid, dim3(512), 0, st, a);
+}
 
 bool prefill_shape_ok(const kun_kv_pool* p, int n_chunks, int Hq, int total_new) {
     return p && n_chunks >= 0 && Hq > 0 && Hq % p->Hkv == 0 && total_new >= 0;
@@ -996,7 +1007,7 @@ struct PrefillLayout {
 PrefillLayout prefill_layout(const kun_kv_pool* p, int n_chunks, int Hq, int total_new_tokens, int pos_per_tile) {
     PrefillLayout lay;
     const int G = Hq / p->Hkv;
-    const int pos_ring = kSplitRows / G;                   // positions per workgroup of the kernels that can split
+    const int pos_ring = kSplitRows / 32 * (32 / G);       // positions per workgroup of the kernels that can split
     // at least total / pos items exist, so a launch with that many workgroups or more is never split
     lay.may_split = (int64_t)(total_new_tokens / pos_ring) * p->Hkv < kSplitTarget;
     lay.max_items = total_new_tokens / pos_per_tile + n_chunks;
@@ -1020,7 +1031,8 @@ extern "C" size_t kun_prefill_workspace_bytes(const kun_kv_pool* p, int n_chunks
         return 256 + 2 * align256(sizeof(int32_t) * (size_t)total_new_tokens) +
                kun_attend_rows_workspace_bytes(total_new_tokens);
     const int G = Hq / p->Hkv;
-    const int pos_min = 128 / (G > 0 ? G : 1);             // smallest tile of any variant (4 waves, NQ = 1)
+    if (G < 1 || G > 8) return 0;
+    const int pos_min = 4 * (32 / G);                      // smallest tile of any variant (4 waves, NQ = 1)
     return prefill_layout(p, n_chunks, Hq, total_new_tokens, pos_min).total;
 }
 
@@ -1035,7 +1047,7 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     if (n_chunks == 0 || total_new_tokens == 0) return KUN_OK;
     if (!q || !out || !q_start || !prior_len || !block_table || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
     const int G = Hq / p->Hkv;
-    if (G != 1 && G != 2 && G != 4 && G != 8) return KUN_ERR_UNSUPPORTED;
+    if (G < 1 || G > 8) return KUN_ERR_UNSUPPORTED;
     const size_t need = kun_prefill_workspace_bytes(p, n_chunks, Hq, total_new_tokens);
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < need) return KUN_ERR_WORKSPACE;
     if (!mfma_shape(p)) {
@@ -1050,10 +1062,12 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
                                        scale, (char*)workspace + 256 + 2 * col, st);
     }
 
-    const TileShape shape = max_workgroups > 0 ? TileShape{8, 1, true, true} : choose_shape();
+    TileShape shape = max_workgroups > 0 ? TileShape{8, 1, true, true} : choose_shape();
+    if ((G & (G - 1)) != 0 && !(shape.ring && shape.nw == 8))
+        shape = TileShape{8, 1, true, false};              // 3, 5, 6, 7 heads per KV head: the 8-wave ring kernels only
     const bool persistent = shape.persistent;
     if (persistent && max_workgroups == 0) max_workgroups = device_compute_units();
-    const int pos_per_tile = rows_per_wg(shape) / G;
+    const int pos_per_tile = pos_per_wg(shape, G);
     const PrefillLayout lay = prefill_layout(p, n_chunks, Hq, total_new_tokens, pos_per_tile);
     const bool can_split = lay.may_split && shape.ring && shape.nw == 8;     // the 8-wave ring kernels only
     char* ws = (char*)workspace;
@@ -1099,7 +1113,11 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
         case 1: launch_prefill<1>(a, grid, shape, st); break;
         case 2: launch_prefill<2>(a, grid, shape, st); break;
         case 4: launch_prefill<4>(a, grid, shape, st); break;
-        default: launch_prefill<8>(a, grid, shape, st); break;
+        case 8: launch_prefill<8>(a, grid, shape, st); break;
+        case 3: launch_ring<3>(a, grid, shape.persistent, st); break;
+        case 5: launch_ring<5>(a, grid, shape.persistent, st); break;
+        case 6: launch_ring<6>(a, grid, shape.persistent, st); break;
+        default: launch_ring<7>(a, grid, shape.persistent, st); break;
     }
     KUN_HIP_CHECK_LAUNCH();
     if (can_split) {

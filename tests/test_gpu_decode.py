@@ -177,6 +177,23 @@ def test_workgroup_order_does_not_change_a_bit(B):
     dw.close()
 
 
+@pytest.mark.parametrize("dtype,d,G,B", [("bf16", 128, 5, 16), ("bf16", 128, 3, 64), ("bf16", 128, 6, 16), ("bf16", 128, 7, 16),
+                                         ("f32", 64, 5, 16), ("f32", 128, 3, 16), ("bf16", 64, 7, 64)])
+def test_any_number_of_query_heads_per_kv_head_up_to_8(dtype, d, G, B):
+    # e.g. 40 query heads over 8 KV heads (G = 5)
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=B, dtype=dtype)
+    lens = [1, 15, 16, 17, 33, 64, 200, 513, 700, 1500, 2100]
+    w = synth.custom_workload("gany", sh, lens, extra_blocks=3, range_fracs=(0.5, 0.5))
+    dw = DeviceWorkload(w)
+    for part in (None, "64"):
+        if part:
+            os.environ["KUN_DECODE_PART"] = part
+        dw._ws_dec = None
+        dw.out_dec.fill_(float("nan"))
+        check_decode(dw)
+    dw.close()
+
+
 def test_empty_calls_and_refused_arguments_leave_outputs_alone():
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     w = synth.custom_workload("empty", sh, [0, 0, 0], chunks=[(5, 0)], extra_blocks=4)
@@ -209,10 +226,10 @@ def test_empty_calls_and_refused_arguments_leave_outputs_alone():
     big = torch.empty(need + 512, dtype=torch.uint8, device=dev)
     assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, sh.Hq, sh.scale, 0,
                   big.data_ptr() + 8, need) == -6                                     # misaligned workspace
-    assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, 6, sh.scale, 0, big, need) == -8   # G = 3
+    assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, 18, sh.scale, 0, big, need) == -8  # G = 9
     assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, 7, sh.scale, 0, big, need) == -1   # 7 % 2
     assert status(kun.kun_paged_decode, dw.pool, None, o, tab, tab.shape[1], ln, 3, sh.Hq, sh.scale, 0, big, need) == -1
-    assert status(kun.kun_paged_prefill_chunk, dw.pool, q, o, z, z, tab, tab.shape[1], 1, 6, 4, sh.scale, big, need) == -8
+    assert status(kun.kun_paged_prefill_chunk, dw.pool, q, o, z, z, tab, tab.shape[1], 1, 18, 4, sh.scale, big, need) == -8
     assert status(kun.kun_slot_map, dw.pool, z, z, 2, tab, tab.shape[1], 5, z, z, z) == -1           # kv head 5 of 2
     torch.cuda.synchronize()
     assert torch.all(dw.out_dec == 3.0)

@@ -257,6 +257,54 @@ def test_blocks_of_64_tokens_other_launches(G, mode):
         dw.close()
 
 
+@pytest.mark.parametrize("mode", ["ring", "persistent", "on16", "split", "8x1"])
+@pytest.mark.parametrize("G", [5, 3, 6, 7])
+def test_group_sizes_that_do_not_divide_32(G, mode):
+    # e.g. 40 query heads over 8 KV heads (G = 5): a wave holds floor(32 / G) whole positions and its last
+    # rows are dead; the register-staged shapes ("8x1") hand such shapes to the ring kernel
+    if mode in ("persistent", "8x1"):
+        os.environ["KUN_PREFILL_SHAPE"] = mode
+    B = 64 if G == 6 else 16
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=128, B=B, dtype="bf16")
+    sets = ([(3000, 40)], [(5000, 200), (17, 3)], [(1500, 64), (64, 64), (9000, 5)]) if mode == "split" else \
+        ([(0, 1), (0, 17), (5, 1), (15, 16), (31, 64), (63, 65), (64, 129), (100, 200), (0, 300), (333, 77), (700, 257),
+          (1000, 31), (0, 1100)],)
+    for chunks in sets:
+        w = synth.custom_workload("godd", sh, [3], chunks=chunks, extra_blocks=3, range_fracs=(0.4, 0.6))
+        dw = DeviceWorkload(w)
+        dw.out_pre.fill_(float("nan"))
+        if mode == "on16":
+            ref = dw.prefill().clone()
+            dw.out_pre.fill_(float("nan"))
+            got = dw.prefill(max_workgroups=16)
+            torch.cuda.synchronize()
+            assert torch.equal(got.view(torch.int16), ref.view(torch.int16))
+        err = check_prefill(dw, rows_per_chunk=64)
+        print(chunks[:2], "max err", err)
+        dw.close()
+
+
+@pytest.mark.parametrize("dtype,d,G", [("f32", 64, 5), ("f32", 128, 3), ("bf16", 64, 7)])
+def test_group_sizes_outside_the_mfma_kernels(dtype, d, G):
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=16, dtype=dtype)
+    chunks = [(0, 1), (5, 1), (15, 16), (63, 65), (100, 40), (333, 20)]
+    w = synth.custom_workload("godd2", sh, [3], chunks=chunks, extra_blocks=3)
+    dw = DeviceWorkload(w)
+    dw.out_pre.fill_(float("nan"))
+    out = dw.prefill()
+    torch.cuda.synchronize()
+    got = out.double().cpu().numpy()
+    assert np.isfinite(got).all()
+    tol = 1e-5 if dtype == "f32" else TOL
+    for i, (p, c) in enumerate(w.chunks):
+        q0 = int(dw.q_start_host[i])
+        pool, tab = bridge.compact_pool(dw.ranges, w.range_blocks, [w.block_tables[w.S + i]], [p + c], sh.Hkv, sh.d,
+                                        sh.B, sh.dtype)
+        ref, _ = O.paged_prefill_chunk(pool, bridge.host_bits(dw.q_pre[q0:q0 + c]), tab[0], p, c, sh.Hq, sh.scale)
+        assert np.abs(got[q0:q0 + c] - ref).max() <= tol
+    dw.close()
+
+
 def test_empty_chunk_is_skipped_and_first_row_returns_v():
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     w = synth.custom_workload("pre0", sh, [3], chunks=[(0, 5), (7, 0), (0, 40)], extra_blocks=2)

@@ -111,7 +111,7 @@ def test_error_paths():
     # decode argument checks happen before any launch
     assert kun.kun_decode_workspace_bytes(p, 4, 30, 0) == 0                                    # 30 % 8 != 0
     assert status(kun.kun_paged_decode, p, BASE, BASE, BASE, 4, BASE, 2, 30, 1.0, 0, BASE, 1 << 30, 0) == -1
-    assert status(kun.kun_paged_decode, p, BASE, BASE, BASE, 4, BASE, 2, 24, 1.0, 0, BASE, 1 << 30, 0) == -8  # G = 3
+    assert status(kun.kun_paged_decode, p, BASE, BASE, BASE, 4, BASE, 2, 72, 1.0, 0, BASE, 1 << 30, 0) == -8  # G = 9
     assert status(kun.kun_paged_decode, p, BASE, BASE, BASE, 4, BASE, 2, 32, 1.0, 0, BASE, 16, 0) == -6       # workspace small
     assert status(kun.kun_paged_decode, p, BASE, BASE, BASE, 4, BASE, 2, 32, 1.0, 0, BASE + 4, 1 << 30, 0) == -6
     assert status(kun.kun_paged_decode, p, 0, BASE, BASE, 4, BASE, 2, 32, 1.0, 0, BASE, 1 << 30, 0) == -1

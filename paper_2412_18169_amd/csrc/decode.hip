@@ -338,7 +338,7 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
 }
 
 // ---------------------------------------------------------------------------------------------
-// 2b. MFMA partial kernel: bf16, head_dim 128, blocks of 16 or 64 tokens, G <= 8.
+// 2b. MFMA partial kernel: bf16, head_dim 128, blocks of 16 or 64 tokens, G <= 16.
 //
 // Each wave walks PAIRS of 16-token page tiles (32 tokens).  With lane = 16 * j + n:
 //   QK^T  S^T[token][head] = K[token][:] . Q[head][:]   as 2 tiles x 4 MFMA 16x16x32
@@ -370,7 +370,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int D = 128;
     constexpr int GMAX = 16;
     __shared__ float sm_m[NW * GMAX], sm_l[NW * GMAX];
-    __shared__ float sm_acc[NW * 8 * D];      // G <= 8 heads kept (G <= 8 is enforced on the host)
+    __shared__ float sm_acc[NW * GMAX * D];   // G <= 16 is enforced on the host
 
     // Workgroups are handed to the 8 XCDs round-robin.  The KV heads of one work item read the same
     // blocks (one page each), so they are given consecutive slots of ONE XCD: they then run side by
@@ -767,7 +767,10 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     if (S == 0) return KUN_OK;
     if (!q || !out || !block_table || !ctx_len || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
     const int G = Hq / p->Hkv;
-    if (G < 1 || G > 8) return KUN_ERR_UNSUPPORTED;
+    const char* force = getenv("KUN_DECODE_KERNEL");     // "generic" forces the vector-ALU kernel
+    const bool generic_only = force && force[0] == 'g';
+    const bool mfma = p->dtype == KUN_BF16 && p->d == 128 && !generic_only;
+    if (G < 1 || (G > 8 && !(G == 16 && mfma))) return KUN_ERR_UNSUPPORTED;   // 16 heads per KV head: the MFMA kernel only
     ub = default_bound(p, S, ub);
     const int P = choose_part_tokens(p, ub);
     const DecodeLayout lay = layout_for(p, S, Hq, ub, P);
@@ -805,10 +808,8 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     KUN_HIP_CHECK_LAUNCH();
 
     dim3 grid((unsigned)((size_t)lay.max_items * p->Hkv));
-    const char* force = getenv("KUN_DECODE_KERNEL");     // "generic" forces the vector-ALU kernel
-    const bool generic_only = force && force[0] == 'g';
     int rc = KUN_OK;
-    if (p->dtype == KUN_BF16 && p->d == 128 && !generic_only) {
+    if (mfma) {
         int nw = 4;
         const char* e = getenv("KUN_DECODE_WAVES");
         if (e) nw = atoi(e);

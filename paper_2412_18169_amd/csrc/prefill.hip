@@ -504,7 +504,7 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     // (32 - POS_W * G of them: 2 for G = 3, 5, 6 and 4 for G = 7) are dead.
     constexpr int ROWS_W = 32, POS_W = ROWS_W / G, POS = NW * POS_W, LIVE_W = POS_W * G;
     constexpr int NSTAGE = 4, AHEAD = 3;
-    static_assert(G >= 1 && G <= 8, "1 to 8 query heads per KV head");
+    static_assert(G >= 1 && G <= 16, "1 to 8 or 16 query heads per KV head");
 
     __shared__ __attribute__((aligned(16))) unsigned char ring[NSTAGE][2 * kBlocksPerTile * 4096];
     constexpr int V_OFF = kBlocksPerTile * 4096;       // V^T pages follow the K pages inside a stage
@@ -1031,7 +1031,7 @@ extern "C" size_t kun_prefill_workspace_bytes(const kun_kv_pool* p, int n_chunks
         return 256 + 2 * align256(sizeof(int32_t) * (size_t)total_new_tokens) +
                kun_attend_rows_workspace_bytes(total_new_tokens);
     const int G = Hq / p->Hkv;
-    if (G < 1 || G > 8) return 0;
+    if (G < 1 || (G > 8 && G != 16)) return 0;
     const int pos_min = 4 * (32 / G);                      // smallest tile of any variant (4 waves, NQ = 1)
     return prefill_layout(p, n_chunks, Hq, total_new_tokens, pos_min).total;
 }
@@ -1047,7 +1047,7 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     if (n_chunks == 0 || total_new_tokens == 0) return KUN_OK;
     if (!q || !out || !q_start || !prior_len || !block_table || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
     const int G = Hq / p->Hkv;
-    if (G < 1 || G > 8) return KUN_ERR_UNSUPPORTED;
+    if (G < 1 || (G > 8 && !(G == 16 && mfma_shape(p)))) return KUN_ERR_UNSUPPORTED;   // 16: the MFMA kernels only
     const size_t need = kun_prefill_workspace_bytes(p, n_chunks, Hq, total_new_tokens);
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < need) return KUN_ERR_WORKSPACE;
     if (!mfma_shape(p)) {
@@ -1063,8 +1063,8 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     }
 
     TileShape shape = max_workgroups > 0 ? TileShape{8, 1, true, true} : choose_shape();
-    if ((G & (G - 1)) != 0 && !(shape.ring && shape.nw == 8))
-        shape = TileShape{8, 1, true, false};              // 3, 5, 6, 7 heads per KV head: the 8-wave ring kernels only
+    if (((G & (G - 1)) != 0 || G == 16) && !(shape.ring && shape.nw == 8))
+        shape = TileShape{8, 1, true, false};              // 3, 5, 6, 7, 16 heads per KV head: the 8-wave ring kernels only
     const bool persistent = shape.persistent;
     if (persistent && max_workgroups == 0) max_workgroups = device_compute_units();
     const int pos_per_tile = pos_per_wg(shape, G);
@@ -1117,7 +1117,8 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
         case 3: launch_ring<3>(a, grid, shape.persistent, st); break;
         case 5: launch_ring<5>(a, grid, shape.persistent, st); break;
         case 6: launch_ring<6>(a, grid, shape.persistent, st); break;
-        default: launch_ring<7>(a, grid, shape.persistent, st); break;
+        case 7: launch_ring<7>(a, grid, shape.persistent, st); break;
+        default: launch_ring<16>(a, grid, shape.persistent, st); break;
     }
     KUN_HIP_CHECK_LAUNCH();
     if (can_split) {

@@ -178,9 +178,10 @@ def test_workgroup_order_does_not_change_a_bit(B):
 
 
 @pytest.mark.parametrize("dtype,d,G,B", [("bf16", 128, 5, 16), ("bf16", 128, 3, 64), ("bf16", 128, 6, 16), ("bf16", 128, 7, 16),
-                                         ("f32", 64, 5, 16), ("f32", 128, 3, 16), ("bf16", 64, 7, 64)])
+                                         ("f32", 64, 5, 16), ("f32", 128, 3, 16), ("bf16", 64, 7, 64),
+                                         ("bf16", 128, 16, 16), ("bf16", 128, 16, 64)])
 def test_any_number_of_query_heads_per_kv_head_up_to_8(dtype, d, G, B):
-    # e.g. 40 query heads over 8 KV heads (G = 5)
+    # e.g. 40 query heads over 8 KV heads (G = 5); also 16 (64 over 4), on the MFMA kernel only
     sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=B, dtype=dtype)
     lens = [1, 15, 16, 17, 33, 64, 200, 513, 700, 1500, 2100]
     w = synth.custom_workload("gany", sh, lens, extra_blocks=3, range_fracs=(0.5, 0.5))
@@ -230,6 +231,9 @@ def test_empty_calls_and_refused_arguments_leave_outputs_alone():
     assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, 7, sh.scale, 0, big, need) == -1   # 7 % 2
     assert status(kun.kun_paged_decode, dw.pool, None, o, tab, tab.shape[1], ln, 3, sh.Hq, sh.scale, 0, big, need) == -1
     assert status(kun.kun_paged_prefill_chunk, dw.pool, q, o, z, z, tab, tab.shape[1], 1, 18, 4, sh.scale, big, need) == -8
+    os.environ["KUN_DECODE_KERNEL"] = "generic"            # 16 heads per KV head: not on the vector-ALU kernel
+    assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, 32, sh.scale, 0, big, need) == -8
+    os.environ.pop("KUN_DECODE_KERNEL")
     assert status(kun.kun_slot_map, dw.pool, z, z, 2, tab, tab.shape[1], 5, z, z, z) == -1           # kv head 5 of 2
     torch.cuda.synchronize()
     assert torch.all(dw.out_dec == 3.0)

@@ -258,10 +258,11 @@ def test_blocks_of_64_tokens_other_launches(G, mode):
 
 
 @pytest.mark.parametrize("mode", ["ring", "persistent", "on16", "split", "8x1"])
-@pytest.mark.parametrize("G", [5, 3, 6, 7])
+@pytest.mark.parametrize("G", [5, 3, 6, 7, 16])
 def test_group_sizes_that_do_not_divide_32(G, mode):
     # e.g. 40 query heads over 8 KV heads (G = 5): a wave holds floor(32 / G) whole positions and its last
-    # rows are dead; the register-staged shapes ("8x1") hand such shapes to the ring kernel
+    # rows are dead; the register-staged shapes ("8x1") hand such shapes to the ring kernel.  Also G = 16
+    # (64 query heads over 4 KV heads), which only the ring kernels take.
     if mode in ("persistent", "8x1"):
         os.environ["KUN_PREFILL_SHAPE"] = mode
     B = 64 if G == 6 else 16

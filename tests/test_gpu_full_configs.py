@@ -98,6 +98,31 @@ def test_config4_mixed_batch_decode_part(block_size):
     dw.close()
 
 
+@pytest.mark.parametrize("Hkv,G", [(1, 8), (1, 16), (3, 4), (5, 5)])
+def test_other_numbers_of_kv_heads(Hkv, G):
+    # one KV head (a tensor-parallel shard of an 8-KV-head model), and counts that are not powers of two
+    sh = synth.LayerShape(Hq=Hkv * G, Hkv=Hkv, d=128, B=16, dtype="bf16")
+    w = synth.custom_workload("hkv", sh, [1, 17, 64, 700, 1500, 2100, 33], chunks=[(0, 70), (100, 200), (3000, 40)],
+                              extra_blocks=3, range_fracs=(0.5, 0.5))
+    dw = DeviceWorkload(w)
+    dw.out_dec.fill_(float("nan"))
+    dw.out_pre.fill_(float("nan"))
+    pre = dw.prefill().clone()
+    out = dw.decode().clone()
+    torch.cuda.synchronize()
+    assert decode_err(dw, out, list(range(w.S))) <= TOL
+    got = pre.double().cpu().numpy()
+    assert np.isfinite(got).all()
+    for i, (p, c) in enumerate(w.chunks):
+        q0 = int(dw.q_start_host[i])
+        pool, tab = bridge.compact_pool(dw.ranges, w.range_blocks, [w.block_tables[w.S + i]], [p + c], sh.Hkv, sh.d,
+                                        sh.B, sh.dtype)
+        ref, _ = O.paged_prefill_chunk(pool, bridge.host_bits(dw.q_pre[q0:q0 + c]), tab[0], p, c, sh.Hq, sh.scale)
+        assert float(np.abs(got[q0:q0 + c] - ref).max()) <= TOL
+    check_slot_map(dw, [0, 3, 5, 7], [0, 699, 2099, 50], kv_head=Hkv - 1)
+    dw.close()
+
+
 def test_config5_150GB_pool_sampled():
     w = synth.config(5)
     dw = DeviceWorkload(w, poison=False)

@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=0, help="workload 2..5 (default: the largest supported)")
-    ap.add_argument("--block-size", type=int, default=0, choices=[0, 16, 64],
+    ap.add_argument("--block-size", type=int, default=0, choices=[0, 16, 32, 64, 128],
                     help="tokens per KV block (default: the configuration's own, 16)")
     ap.add_argument("--q-heads", type=int, default=0,
                     help="query heads (default: the configuration's own); e.g. 40 over the 8 KV heads of cfg 2-4")

@@ -35,7 +35,7 @@
  *   token of a 48-layer model quoted in Section 2.2.
  *   Query heads h with the same h / (num_q_heads / num_kv_heads) share a KV head (GQA).
  *
- * Supported shapes: block_size 16 or 64 (Section 5.1 tunes it to 64); head_dim 64 or 128;
+ * Supported shapes: block_size 16, 32, 64 or 128 (Section 5.1 tunes it to 64); head_dim 64 or 128;
  *   num_q_heads / num_kv_heads = 1 .. 8 (e.g. 40 query heads over 8 KV heads), or 16 with bf16 and
  *   head_dim 128 (e.g. 64 over 4); dtype f32 or bf16 (accumulation is always fp32).
  *   Anything else is KUN_ERR_UNSUPPORTED.  bf16 with head_dim 128 runs on the matrix cores, the

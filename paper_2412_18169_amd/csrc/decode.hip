@@ -39,7 +39,8 @@ struct DecodeArgs {
     float* part_acc;         // workspace: [item, kvh, G, d]
     int max_blocks;
     int S, Hkv, G;
-    int B;                   // tokens per KV block: 16 or 64
+    int B;                   // tokens per KV block: 16, 32, 64 or 128
+    int tile_shift;          // log2(B / 16)
     int part_tokens;         // tokens per partition, multiple of 32
     int max_items;
     float scale_log2;        // softmax scale * log2(e)
@@ -364,8 +365,9 @@ struct PairLoads {
     uint4 v[8];      // [dim slice]
 };
 
-// R = tiles of 16 tokens per KV block (1 or 4): tile i of a request is tile i % R of its block i / R.
-template <int NW, int R>
+// a.tile_shift = log2 of the 16-token tiles per KV block: tile i of a request is tile i % 2^shift of
+// its block i >> shift.
+template <int NW>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_partial_mfma(const DecodeArgs a) {
     constexpr int D = 128;
     constexpr int GMAX = 16;
@@ -431,7 +433,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const int pr_l = first_pair + (lane >> 1) * NW;
         int b = 2 * pr_l + (lane & 1);
         if (b >= nblk) b = (2 * pr_l < nblk) ? 2 * pr_l : nblk - 1;   // odd tail / beyond the partition
-        const int id = trow[b / R];
+        const int id = trow[b >> a.tile_shift];
         int first = a.rt.first[0];
         unsigned long long base = (unsigned long long)a.rt.base[0];
         for (int r = 1; r < a.rt.n; ++r) {
@@ -440,7 +442,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
             base = in ? (unsigned long long)a.rt.base[r] : base;
         }
         return base + (unsigned long long)(id - first) * a.block_bytes + (unsigned long long)kvh * a.page_bytes +
-               (unsigned)(b % R) * (2 * kBlock * D * 2);
+               (unsigned)(b & ((1 << a.tile_shift) - 1)) * (2 * kBlock * D * 2);
     };
     unsigned long long pages = load_pages(pair0);
     int pages_first = pair0;
@@ -722,6 +724,7 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
     a.Hkv = p->Hkv;
     a.G = Hq / p->Hkv;
     a.B = p->B;
+    a.tile_shift = p->B == 128 ? 3 : p->B == 64 ? 2 : p->B == 32 ? 1 : 0;
     a.part_tokens = 1 << 30;
     a.max_items = T;
     a.scale_log2 = scale * kLog2e;
@@ -796,6 +799,7 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     a.Hkv = p->Hkv;
     a.G = G;
     a.B = p->B;
+    a.tile_shift = p->B == 128 ? 3 : p->B == 64 ? 2 : p->B == 32 ? 1 : 0;
     a.part_tokens = P;
     a.max_items = lay.max_items;
     a.scale_log2 = scale * kLog2e;
@@ -816,13 +820,9 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
         const char* map = getenv("KUN_DECODE_MAP");      // "flat": item-major workgroup order
         a.xcd_map = !(map && map[0] == 'f');
         if (a.xcd_map) grid = dim3((unsigned)(((size_t)lay.max_items + 7) / 8 * 8 * p->Hkv));
-        if (p->B == 64) {
-            if (nw == 1) hipLaunchKernelGGL((decode_partial_mfma<1, 4>), grid, dim3(64), 0, st, a);
-            else if (nw == 2) hipLaunchKernelGGL((decode_partial_mfma<2, 4>), grid, dim3(128), 0, st, a);
-            else hipLaunchKernelGGL((decode_partial_mfma<4, 4>), grid, dim3(256), 0, st, a);
-        } else if (nw == 1) hipLaunchKernelGGL((decode_partial_mfma<1, 1>), grid, dim3(64), 0, st, a);
-        else if (nw == 2) hipLaunchKernelGGL((decode_partial_mfma<2, 1>), grid, dim3(128), 0, st, a);
-        else hipLaunchKernelGGL((decode_partial_mfma<4, 1>), grid, dim3(256), 0, st, a);
+        if (nw == 1) hipLaunchKernelGGL((decode_partial_mfma<1>), grid, dim3(64), 0, st, a);
+        else if (nw == 2) hipLaunchKernelGGL((decode_partial_mfma<2>), grid, dim3(128), 0, st, a);
+        else hipLaunchKernelGGL((decode_partial_mfma<4>), grid, dim3(256), 0, st, a);
     } else if (p->dtype == KUN_BF16) {
         rc = p->d == 128 ? launch_generic<bf16_t, 128>(a, grid, st) : launch_generic<bf16_t, 64>(a, grid, st);
     } else {

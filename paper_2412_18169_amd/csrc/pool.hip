@@ -60,7 +60,8 @@ int kun_kv_pool_create(kun_kv_pool** out, void* base, size_t bytes, int dtype, i
     *out = nullptr;
     if (dtype != KUN_F32 && dtype != KUN_BF16) return KUN_ERR_INVALID_ARG;
     if (num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0) return KUN_ERR_INVALID_ARG;
-    if ((block_size != 16 && block_size != 64) || (head_dim != 64 && head_dim != 128)) return KUN_ERR_UNSUPPORTED;
+    if ((block_size != 16 && block_size != 32 && block_size != 64 && block_size != 128) || (head_dim != 64 && head_dim != 128))
+        return KUN_ERR_UNSUPPORTED;
     kun_kv_pool* p = new (std::nothrow) kun_kv_pool();
     if (!p) return KUN_ERR_INVALID_ARG;
     p->dtype = dtype;

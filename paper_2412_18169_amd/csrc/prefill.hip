@@ -65,7 +65,7 @@ struct PrefillArgs {
     int max_items;
     float scale_log2;
     unsigned block_bytes, page_bytes;
-    int sub_shift;           // log2 of the 16-token page tiles per KV block (0 or 2): page tile i of a request is tile i % 2^shift of block i >> shift
+    int sub_shift;           // log2 of the 16-token page tiles per KV block (0 .. 3): page tile i of a request is tile i % 2^shift of block i >> shift
 };
 
 // max of three floats in one instruction.  Plain fmaxf makes the compiler canonicalise every MFMA
@@ -1094,7 +1094,7 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     a.scale_log2 = scale * kLog2e;
     a.block_bytes = (unsigned)p->block_bytes;
     a.page_bytes = (unsigned)p->page_bytes;
-    a.sub_shift = p->B == 64 ? 2 : 0;
+    a.sub_shift = p->B == 128 ? 3 : p->B == 64 ? 2 : p->B == 32 ? 1 : 0;
     hipStream_t st = (hipStream_t)stream;
 
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, q_start, prior_len, n_chunks,

@@ -281,7 +281,7 @@ SHAPE_70B = LayerShape(Hq=64, Hkv=8, d=128, B=16, dtype="bf16")
 
 def config(cfg: int, block_size: int = 0, q_heads: int = 0) -> Workload:
     """The five benchmark configurations (1-based). Seeds are 1000 + cfg.  `block_size` (0 = the
-    configuration's own, 16) builds the same requests over KV blocks of another size, `q_heads`
+    configuration's own, 16) builds the same requests over KV blocks of another size (32, 64, 128), `q_heads`
     (0 = the configuration's own) with another number of query heads over the same KV heads."""
     import dataclasses
     seed = 1000 + cfg

@@ -240,10 +240,11 @@ def test_empty_calls_and_refused_arguments_leave_outputs_alone():
     dw.close()
 
 
+@pytest.mark.parametrize("B", [64, 32, 128])
 @pytest.mark.parametrize("G,d,dtype", [(8, 128, "bf16"), (4, 128, "bf16"), (2, 64, "bf16"), (4, 64, "f32"), (1, 128, "f32")])
-def test_blocks_of_64_tokens(G, d, dtype):
-    # the paper's tuned block size (Section 5.1): decode, append and the slot map over 64-token blocks
-    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=64, dtype=dtype)
+def test_blocks_of_64_tokens(G, d, dtype, B):
+    # the paper's tuned block size (Section 5.1), and 32 and 128: decode, append and the slot map
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=B, dtype=dtype)
     lens = [1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 511, 513, 777, 1024, 1500, 4100]
     w = synth.custom_workload("b64", sh, lens, extra_blocks=3, range_fracs=(0.3, 0.2, 0.5))
     dw = DeviceWorkload(w, fill=False)

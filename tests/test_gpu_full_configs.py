@@ -186,7 +186,7 @@ def check_slot_map(dw, seqs, poss, kv_head):
 
 
 @pytest.mark.parametrize("dtype,d,B", [("bf16", 128, 16), ("f32", 64, 16), ("bf16", 64, 16), ("f32", 128, 16),
-                                       ("bf16", 128, 64), ("f32", 64, 64)])
+                                       ("bf16", 128, 64), ("f32", 64, 64), ("bf16", 128, 32), ("f32", 128, 128)])
 def test_slot_map_matches_oracle_for_every_token(dtype, d, B):
     sh = synth.LayerShape(Hq=8, Hkv=4, d=d, B=B, dtype=dtype)
     w = synth.custom_workload("slots", sh, [37, 1, 16, 250, 1000], chunks=[(20, 70)], extra_blocks=5,

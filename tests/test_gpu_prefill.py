@@ -210,9 +210,10 @@ def test_few_query_tiles_after_long_contexts_split_their_keys(G, shape):
         dw.close()
 
 
+@pytest.mark.parametrize("B", [64, 32, 128])
 @pytest.mark.parametrize("G,d,dtype", [(8, 128, "bf16"), (4, 128, "bf16"), (1, 128, "bf16"), (2, 64, "f32")])
-def test_blocks_of_64_tokens(G, d, dtype):
-    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=64, dtype=dtype)
+def test_blocks_of_64_tokens(G, d, dtype, B):
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=B, dtype=dtype)
     chunks = [(0, 1), (0, 17), (5, 1), (15, 16), (31, 64), (63, 65), (64, 129), (100, 200), (0, 300), (333, 77),
               (700, 257), (1000, 31), (3000, 40)]
     w = synth.custom_workload("b64", sh, [3], chunks=chunks, extra_blocks=3, range_fracs=(0.4, 0.6))
@@ -240,7 +241,7 @@ def test_blocks_of_64_tokens_other_launches(G, mode):
     # and the other tile shapes
     if mode not in ("on16", "split"):
         os.environ["KUN_PREFILL_SHAPE"] = mode
-    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=128, B=64, dtype="bf16")
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=128, B=(64 if G == 8 else 128), dtype="bf16")
     sets = ([(3000, 40)], [(5000, 200), (17, 3)], [(1500, 64), (64, 64), (9000, 5)]) if mode == "split" else \
         ([(0, 1), (63, 65), (64, 129), (100, 200), (0, 300), (700, 257), (1000, 31), (3000, 40), (0, 2100)],)
     for chunks in sets:

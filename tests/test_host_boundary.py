@@ -97,7 +97,7 @@ def test_error_paths():
     assert status(kun.kun_kv_pool_create, BASE, BB - 1, kun.KUN_BF16, 8, 128, 16) == -3        # too small
     assert status(kun.kun_kv_pool_create, 0, BB * 4, kun.KUN_BF16, 8, 128, 16) == -1           # null base
     assert status(kun.kun_kv_pool_create, BASE, BB * 4, 7, 8, 128, 16) == -1                   # bad dtype
-    assert status(kun.kun_kv_pool_create, BASE, BB * 4, kun.KUN_BF16, 8, 128, 32) == -8        # block size
+    assert status(kun.kun_kv_pool_create, BASE, BB * 4, kun.KUN_BF16, 8, 128, 48) == -8        # block size
     assert status(kun.kun_kv_pool_create, BASE, BB * 4, kun.KUN_BF16, 8, 96, 16) == -8         # head dim
     p = make_pool()
     assert status(kun.kun_kv_pool_extend, p, BASE + 17, BB * 2) == -2

@@ -500,9 +500,10 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     constexpr int NSTAGERS = 8;                        // waves that issue the tile loads (4 loads per lane and tile)
     constexpr int NT = 64 * NSTAGERS, LOADS = 2;
     static_assert(NW >= NSTAGERS, "the first 8 waves stage the tiles");
-    // A wave holds POS_W whole positions = POS_W * G rows; when G does not divide 32 its last rows
-    // (32 - POS_W * G of them: 2 for G = 3, 5, 6 and 4 for G = 7) are dead.
-    constexpr int ROWS_W = 32, POS_W = ROWS_W / G, POS = NW * POS_W, LIVE_W = POS_W * G;
+    // Row r of the workgroup is (position r / G, head r % G).  The workgroup holds POS whole positions;
+    // when G does not divide its row count the last rows (1 of 256 for G = 3, 5; 4 for G = 6, 7) are
+    // dead, and a wave's 32 rows may begin and end in the middle of a position.
+    constexpr int ROWS_W = 32, ROWS = NW * ROWS_W, POS = ROWS / G, LIVE = POS * G;
     constexpr int NSTAGE = 4, AHEAD = 3;
     static_assert(G >= 1 && G <= 16, "1 to 8 or 16 query heads per KV head");
 
@@ -533,7 +534,8 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, jh = lane >> 5;
     const int pos0 = qt * POS;
-    const int wpos0 = pos0 + wave * POS_W;
+    const int wpos0 = pos0 + wave * ROWS_W / G;                                  // first position the wave touches
+    const int wpos_end = pos0 + min((wave * ROWS_W + ROWS_W - 1) / G, POS - 1) + 1;  // one past its last live one
 
     const int32_t* trow = a.table + (size_t)chunk * a.max_blocks;
     const int nblk_ctx = (ctx + kBlock - 1) / kBlock;
@@ -619,9 +621,9 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     }
 
     Frag qf[8];
-    int pos = wpos0 + n / G;
-    const int g_head = n % G;
-    const bool live_row = n < LIVE_W && pos < c;
+    int pos = pos0 + (wave * ROWS_W + n) / G;
+    const int g_head = (wave * ROWS_W + n) % G;
+    const bool live_row = wave * ROWS_W + n < LIVE && pos < c;
     if (!live_row) pos = min(wpos0, c - 1);            // a dead row repeats a row the wave (or the chunk) does have
     const int vis = p + pos;                           // last key this lane's row sees
     {
@@ -629,7 +631,7 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qf[ks].u = *(const uint4*)(qrow + (2 * ks + jh) * 16);
     }
-    const int wave_vis_max = p + min(wpos0 + POS_W, c) - 1;
+    const int wave_vis_max = p + min(wpos_end, c) - 1;
     const int wave_vis_min = p + min(wpos0, c - 1);
 
     f32x16 o[4];
@@ -882,9 +884,8 @@ __global__ __launch_bounds__(kSplitRows) void prefill_merge_kernel(const Prefill
     const int qs = a.q_start[chunk];
     const int c = a.q_start[chunk + 1] - qs;
     const int row = threadIdx.x;
-    const int pos_w = 32 / G, rw = row & 31;           // the ring kernel's rows: wave row / 32 holds pos_w positions
-    const int pos = qt * (kSplitRows / 32 * pos_w) + (row >> 5) * pos_w + rw / G, head = rw % G;
-    if (rw >= pos_w * G || pos >= c) return;
+    const int pos = qt * (kSplitRows / G) + row / G, head = row % G;
+    if (row >= kSplitRows / G * G || pos >= c) return;      // (the workgroup's last rows are dead when G does not divide 256)
     float w[kMaxSplit];
     float M = -INFINITY;
     for (int sp = 0; sp < nsplit; ++sp)
@@ -968,8 +969,7 @@ int device_compute_units() {
 }
 
 int rows_per_wg(TileShape t) { return t.nw * 32 * t.nq; }
-// query positions per workgroup: every 32 rows hold floor(32 / G) whole positions
-int pos_per_wg(TileShape t, int G) { return rows_per_wg(t) / 32 * (32 / G); }
+int pos_per_wg(TileShape t, int G) { return rows_per_wg(t) / G; }    // whole query positions per workgroup
 
 template <int G>
 void launch_ring(const PrefillArgs& a, dim3 grid, bool persistent, hipStream_t st) {
@@ -1007,7 +1007,7 @@ struct PrefillLayout {
 PrefillLayout prefill_layout(const kun_kv_pool* p, int n_chunks, int Hq, int total_new_tokens, int pos_per_tile) {
     PrefillLayout lay;
     const int G = Hq / p->Hkv;
-    const int pos_ring = kSplitRows / 32 * (32 / G);       // positions per workgroup of the kernels that can split
+    const int pos_ring = kSplitRows / G;                   // positions per workgroup of the kernels that can split
     // at least total / pos items exist, so a launch with that many workgroups or more is never split
     lay.may_split = (int64_t)(total_new_tokens / pos_ring) * p->Hkv < kSplitTarget;
     lay.max_items = total_new_tokens / pos_per_tile + n_chunks;
@@ -1032,7 +1032,7 @@ extern "C" size_t kun_prefill_workspace_bytes(const kun_kv_pool* p, int n_chunks
                kun_attend_rows_workspace_bytes(total_new_tokens);
     const int G = Hq / p->Hkv;
     if (G < 1 || (G > 8 && G != 16)) return 0;
-    const int pos_min = 4 * (32 / G);                      // smallest tile of any variant (4 waves, NQ = 1)
+    const int pos_min = 128 / G;                           // smallest tile of any variant (4 waves, NQ = 1)
     return prefill_layout(p, n_chunks, Hq, total_new_tokens, pos_min).total;
 }
 

@@ -1,4 +1,5 @@
-// Chunked prefill over paged K/V: bf16, head_dim 128, block 16, MFMA 32x32x16 with fp32 accumulation.
+// Chunked prefill over paged K/V: bf16, head_dim 128, pages of 16-token tiles (blocks of 16 to 128
+// tokens), MFMA 32x32x16 with fp32 accumulation.
 //
 // A chunk of c new tokens after p prior tokens attends to keys 0 .. p + r for its row r
 // (Section 4.3, Eq. 1: prefix attention p*c plus causal self attention (c*c + c)/2 pairs).  This is
@@ -7,7 +8,7 @@
 // Work item = (chunk, tile of query positions, kv head).  The G query heads that share the kv head
 // are stacked into the row dimension (row = position * G + head), so a K/V tile staged in LDS
 // serves all of them.  A workgroup has 8 waves (4 or 12 in the variants); each wave owns 32 (* NQ)
-// rows and walks the keys in tiles of 64 (four KV blocks), flash-attention style:
+// rows and walks the keys in tiles of 64 (four page tiles), flash-attention style:
 //
 //   S^T[key][row]  = K[key][:] . Q[row][:]          A = K fragment from LDS, B = Q in registers
 //   online softmax over keys, per row: each lane column holds one row, so max/sum are in-lane
@@ -17,7 +18,7 @@
 //                                                    accumulator registers, rounded to bf16
 //
 // S^T tile rows are mapped to keys so that the 8 accumulator values a lane feeds to one PV MFMA
-// are 8 consecutive keys of one KV block, i.e. one 16-byte LDS read of V^T.
+// are 8 consecutive keys of one page tile, i.e. one 16-byte LDS read of V^T.
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>

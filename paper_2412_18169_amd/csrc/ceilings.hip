@@ -13,8 +13,8 @@
 //      a reference maximum that is checked through the row sums, 16 MFMAs
 //      for O^T += V^T P^T, operands read from a 4-stage LDS ring, one barrier per tile, four
 //      direct global->LDS loads per lane and tile; every wave does the same work, nothing is
-//      masked, the source stays in L2.  Constant and random operands; variants leave out one cost
-//      at a time (half of the LDS fragment reads, the softmax arithmetic, barrier and loads).
+//      masked, the source stays in L2.  Constant and random operands; variants add one cost at a
+//      time to the bare MFMA loop (barrier, global->LDS loads, LDS fragment reads, softmax).
 //
 // Build: python -m paper_2412_18169_amd.build   (writes paper_2412_18169_amd/kun_ceilings)
 // Run:   ./paper_2412_18169_amd/kun_ceilings [hbm|mfma|tile|all]
@@ -183,12 +183,15 @@ static void run_mfma(float* out, uint4* src) {
 }
 
 // ---------------------------------------------------------------- 3. attention tile loop
-// HALF: every K / V^T fragment read from LDS feeds two MFMAs (a second Q fragment, a repeated V^T
-//       fragment: wrong results, the same number of MFMAs and softmax instructions) -- what fewer
-//       fragment reads would buy.
+// One cost at a time on top of the bare MFMA loop (32 MFMAs per tile and wave, operands in registers):
+// LD:   0 = every K / V^T fragment is read from LDS (32 ds_read_b128 per tile and wave), 1 = every
+//       fragment read feeds two MFMAs (16 reads; a second Q fragment, a repeated V^T fragment: wrong
+//       results, the same number of MFMAs and softmax instructions), 2 = none (fragments read once
+//       before the loop).
 // SM:   the softmax numerators (fma, exp2, row sums, conversion to bf16) or only the conversion.
-// SYNC: the barrier and the four global->LDS loads per lane and tile, or neither.
-template <bool HALF, bool SM, bool SYNC>
+// SYNC: 0 = none, 1 = the barrier and the four global->LDS loads per lane and tile, 2 = the barrier
+//       only, 3 = the loads (and the wait for the tile loaded three iterations earlier) only.
+template <int LD, bool SM, int SYNC>
 __global__ __launch_bounds__(512) void tile_loop(float* out, const uint4* gsrc, int iters, float sl2) {
     __shared__ __attribute__((aligned(16))) unsigned char ring[4][32768];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, jh = lane >> 5;
@@ -209,20 +212,21 @@ __global__ __launch_bounds__(512) void tile_loop(float* out, const uint4* gsrc, 
     const unsigned v_lane = 16384 + n * 32 + ((jh ^ ((n >> 3) & 1)) * 16);
     const unsigned ring_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)&ring[0][0];
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    Frag ka[8];
+    for (int ks = 0; ks < 8; ++ks) ka[ks].u = *(const uint4*)(&ring[0][0] + k_lane + (((2 * ks + jh) ^ krow_in) * 16));
     for (int it = 0; it < iters; ++it) {
         if (SYNC) {
-            __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8): the tile read below has landed
-            __builtin_amdgcn_s_barrier();
-            const unsigned st = ring_addr + ((it + 3) & 3) * 32768 + (wave_u & 3) * 1024;
+            if (SYNC != 2) __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
+            if (SYNC != 3) __builtin_amdgcn_s_barrier();
+            if (SYNC != 2) {
+                const unsigned st = ring_addr + ((it + 3) & 3) * 32768 + (wave_u & 3) * 1024;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const char* page = (const char*)(gsrc + ((size_t)((it * 7 + wave_u * 2 + i) & 1023)) * 512);
-                const unsigned dk = st + ((wave_u >> 2) + 2 * i) * 4096;
-                asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(page + lane * 16), "s"(dk)
-                             : "memory", "m0");
-                asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(page + 4096 + lane * 16),
-                             "s"(dk + 16384)
-                             : "memory", "m0");
+                for (int i = 0; i < 2; ++i) {
+                    const char* page = (const char*)(gsrc + ((size_t)((it * 7 + wave_u * 2 + i) & 1023)) * 512);
+                    const unsigned dk = st + ((wave_u >> 2) + 2 * i) * 4096;
+                    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(page + lane * 16), "s"(dk) : "memory", "m0");
+                    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(page + 4096 + lane * 16), "s"(dk + 16384) : "memory", "m0");
+                }
             }
         }
         const unsigned char* stage_base = &ring[it & 3][0];
@@ -232,18 +236,20 @@ __global__ __launch_bounds__(512) void tile_loop(float* out, const uint4* gsrc, 
             sb[i] = 0.f;
         }
         const unsigned char* kbase = stage_base + k_lane;
-        Frag ka[8], kb[8];
+        Frag kb[8];
+        if (LD != 2) {
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const unsigned off = ((2 * ks + jh) ^ krow_in) * 16;
-            ka[ks].u = *(const uint4*)(kbase + off);
-            if (!HALF) kb[ks].u = *(const uint4*)(kbase + 8192 + off);
+            for (int ks = 0; ks < 8; ++ks) {
+                const unsigned off = ((2 * ks + jh) ^ krow_in) * 16;
+                ka[ks].u = *(const uint4*)(kbase + off);
+                if (LD == 0) kb[ks].u = *(const uint4*)(kbase + 8192 + off);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks].v, q.v, sa, 0, 0, 0);
-            if (HALF) sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks].v, q2.v, sb, 0, 0, 0);
+            if (LD != 0) sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks].v, q2.v, sb, 0, 0, 0);
             else sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[ks].v, q.v, sb, 0, 0, 0);
         }
         const unsigned char* vbase = stage_base + v_lane;
@@ -252,7 +258,8 @@ __global__ __launch_bounds__(512) void tile_loop(float* out, const uint4* gsrc, 
         for (int h = 0; h < 4; ++h)
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
-                if (HALF && h >= 2) vf[4 * h + d].u = vf[4 * (h - 2) + d].u;
+                if (LD == 2) vf[4 * h + d].u = ka[(4 * h + d) & 7].u;
+                else if (LD == 1 && h >= 2) vf[4 * h + d].u = vf[4 * (h - 2) + d].u;
                 else vf[4 * h + d].u = *(const uint4*)(vbase + h * 4096 + d * 1024);
             }
         __builtin_amdgcn_sched_barrier(0);
@@ -295,7 +302,8 @@ __global__ __launch_bounds__(512) void tile_loop(float* out, const uint4* gsrc, 
     out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
-#define KUN_TILE(HALF, SM, SYNC) time_ms([&] { tile_loop<HALF, SM, SYNC><<<256, 512>>>(out, src, iters, 0.01f); }, 1)
+
+#define KUN_TILE(LD, SM, SYNC) time_ms([&] { tile_loop<LD, SM, SYNC><<<256, 512>>>(out, src, iters, 0.01f); }, 1)
 static void run_tile(float* out, uint4* src) {
     const int iters = 4000;
     const double flops = 256.0 * 8 * iters * 32 * 32768.0;
@@ -304,16 +312,19 @@ static void run_tile(float* out, uint4* src) {
         CK(hipMemcpy(src, h.data(), 1024 * 8192, hipMemcpyHostToDevice));
         // the variants take turns and the best of five rounds counts: the clock drifts by several
         // percent over the first launches of a session
-        float best[5] = {1e9f, 1e9f, 1e9f, 1e9f, 1e9f};
+        const int N = 9;
+        float best[N];
+        for (int i = 0; i < N; ++i) best[i] = 1e9f;
         for (int round = 0; round < 5; ++round) {
-            const float t[5] = {KUN_TILE(false, true, true), KUN_TILE(true, true, true), KUN_TILE(false, false, true),
-                                KUN_TILE(true, false, true), KUN_TILE(false, true, false)};
-            for (int i = 0; i < 5; ++i) best[i] = t[i] < best[i] ? t[i] : best[i];
+            const float t[N] = {KUN_TILE(2, false, 0), KUN_TILE(2, false, 2), KUN_TILE(2, false, 3), KUN_TILE(0, false, 0),
+                                KUN_TILE(1, false, 0), KUN_TILE(2, true, 0),  KUN_TILE(0, true, 0),  KUN_TILE(1, true, 1),
+                                KUN_TILE(0, true, 1)};
+            for (int i = 0; i < N; ++i) best[i] = t[i] < best[i] ? t[i] : best[i];
         }
-        std::printf("attention tile loop, %s operands: %.0f TFLOP/s | every fragment read used twice %.0f | no softmax %.0f |"
-                    " neither %.0f | no barrier, no global->LDS loads %.0f\n",
-                    random ? "random  " : "constant", flops / best[0] / 1e9, flops / best[1] / 1e9, flops / best[2] / 1e9,
-                    flops / best[3] / 1e9, flops / best[4] / 1e9);
+        const char* names[N] = {"bare MFMA loop", "+ barrier", "+ global->LDS loads", "+ LDS fragment reads", "+ half of them",
+                                "+ softmax", "+ reads and softmax", "all, half of the reads", "all (the tile loop)"};
+        std::printf("attention tile loop, %s operands, TFLOP/s:", random ? "random  " : "constant");
+        for (int i = 0; i < N; ++i) std::printf(" %s %.0f%s", names[i], flops / best[i] / 1e9, i + 1 < N ? " |" : "\n");
     }
 }
 

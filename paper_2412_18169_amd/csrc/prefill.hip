@@ -556,11 +556,17 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     // Page addresses this wave stages, resolved a batch at a time in the vector lanes (lane LOADS*t + i
     // = tile batch_first + t, load i): one table gather and one walk over the range table per TPB
     // tiles, instead of dependent scalar loads in front of every tile's loads.
-    auto load_pages = [&](int batch) -> unsigned long long {
+    // The gather (load_ids) and the walk (resolve_pages) are separate steps: the ids of the next batch
+    // are requested half a batch early and used only when the batch begins, so that the wait for them
+    // -- a vmcnt(0), since the compiler does not see the tile loads -- finds them long landed.
+    auto tile_of_lane = [&](int batch) -> int {
         const int t = kt0 + batch * TPB + lane / LOADS, i = lane % LOADS;
-        int lb = t * kBlocksPerTile + (wave >> 2) + 2 * i;
-        if (lb >= nblk_ctx) lb = nblk_ctx - 1;          // past the context: re-read the last tile
-        const int id = trow[lb >> a.sub_shift];
+        const int lb = t * kBlocksPerTile + (wave >> 2) + 2 * i;
+        return lb >= nblk_ctx ? nblk_ctx - 1 : lb;      // past the context: re-read the last tile
+    };
+    auto load_ids = [&](int batch) -> int { return trow[tile_of_lane(batch) >> a.sub_shift]; };
+    auto resolve_pages = [&](int batch, int id) -> unsigned long long {
+        const int lb = tile_of_lane(batch);
         int first = a.rt.first[0];
         unsigned long long base = (unsigned long long)a.rt.base[0];
         for (int r = 1; r < a.rt.n; ++r) {
@@ -571,7 +577,8 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
         return base + (unsigned long long)(id - first) * a.block_bytes + (unsigned long long)kvh * a.page_bytes +
                (unsigned)(lb & ((1 << a.sub_shift) - 1)) * 8192u;
     };
-    unsigned long long pages_cur = load_pages(0), pages_nxt = 0;
+    unsigned long long pages_cur = resolve_pages(0, load_ids(0));
+    int ids_nxt = 0;
 
     // per-lane source offsets inside a page for the slot this lane fills (slot = (wave % 4) * 64 + lane)
     const int slot = (wave & 3) * 64 + lane;
@@ -591,8 +598,8 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     const char* iss_page[LOADS];
     auto issue_begin = [&](int j) {                    // j: tile index relative to kt0
         const int rel = j % TPB;
-        if (rel == 0 && j > 0) pages_cur = pages_nxt;
-        if (rel == TPB / 2 && (j / TPB + 1) * TPB < nt) pages_nxt = load_pages(j / TPB + 1);
+        if (rel == 0 && j > 0) pages_cur = resolve_pages(j / TPB, ids_nxt);
+        if (rel == TPB / 2 && (j / TPB + 1) * TPB < nt) ids_nxt = load_ids(j / TPB + 1);
         iss_stage = ring_addr + (j % NSTAGE) * (2 * kBlocksPerTile * 4096) + (wave_u & 3) * 1024;
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {

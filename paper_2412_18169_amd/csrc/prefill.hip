@@ -111,7 +111,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
                                                                   int4* __restrict__ split_items,
                                                                   int32_t* __restrict__ n_split_items) {
     __shared__ int base_s;
-    __shared__ int cnt[kPlanThreads];
+    __shared__ int cnt[kPlanThreads / 64];               // per-wave totals of the scan
     __shared__ int cost[kPlanSortMax];
     __shared__ int2 tmp_item[kPlanSortMax];
     __shared__ int hist[kPlanBuckets];
@@ -127,10 +127,15 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
             p = prior[ch];
             nt = (c + pos_per_tile - 1) / pos_per_tile;
         }
-        cnt[tid] = nt;
+        int incl = nt;                                     // inclusive scan inside the wave, then over the waves
+        for (int o = 1; o < 64; o <<= 1) {
+            const int y = __shfl_up(incl, o);
+            if ((tid & 63) >= o) incl += y;
+        }
+        if ((tid & 63) == 63) cnt[tid >> 6] = incl;
         __syncthreads();
-        int first = base_s;
-        for (int i = 0; i < tid; ++i) first += cnt[i];
+        int first = base_s + incl - nt;
+        for (int w = 0; w < (tid >> 6); ++w) first += cnt[w];
         for (int t = 0; t < nt; ++t) {
             const int k = first + t;
             if (k >= max_items) break;

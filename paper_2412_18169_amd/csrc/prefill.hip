@@ -501,16 +501,20 @@ typedef __attribute__((address_space(3))) void* kun_lptr;
 // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt = bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 #define KUN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
+// NW = 8 (default) or 12: a 4-stage ring, tiles three ahead, one workgroup per compute unit.
+// NW = 4: a 2-stage ring (64 KiB), tiles one ahead, so that two workgroups share a compute unit and one
+// runs its tile loop while the other is between work items.
 template <int G, int NW, bool PERSIST>
-__global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs a) {
-    constexpr int NSTAGERS = 8;                        // waves that issue the tile loads (4 loads per lane and tile)
-    constexpr int NT = 64 * NSTAGERS, LOADS = 2;
-    static_assert(NW >= NSTAGERS, "the first 8 waves stage the tiles");
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 12 ? 3 : 2, NW == 12 ? 3 : 2)))
+void prefill_ring_kernel(const PrefillArgs a) {
+    constexpr int NSTAGERS = NW < 8 ? NW : 8;          // waves that issue the tile loads
+    constexpr int LOADS = 16 / NSTAGERS;               // page tiles per stager wave and tile: 2 loads per lane each (K, V^T)
+    constexpr int NT = 64 * NSTAGERS;
     // Row r of the workgroup is (position r / G, head r % G).  The workgroup holds POS whole positions;
     // when G does not divide its row count the last rows (1 of 256 for G = 3, 5; 4 for G = 6, 7) are
     // dead, and a wave's 32 rows may begin and end in the middle of a position.
     constexpr int ROWS_W = 32, ROWS = NW * ROWS_W, POS = ROWS / G, LIVE = POS * G;
-    constexpr int NSTAGE = 4, AHEAD = 3;
+    constexpr int NSTAGE = NW < 8 ? 2 : 4, AHEAD = NSTAGE - 1;
     static_assert(G >= 1 && G <= 16, "1 to 8 or 16 query heads per KV head");
 
     __shared__ __attribute__((aligned(16))) unsigned char ring[NSTAGE][2 * kBlocksPerTile * 4096];
@@ -566,7 +570,7 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     // -- a vmcnt(0), since the compiler does not see the tile loads -- finds them long landed.
     auto tile_of_lane = [&](int batch) -> int {
         const int t = kt0 + batch * TPB + lane / LOADS, i = lane % LOADS;
-        const int lb = t * kBlocksPerTile + (wave >> 2) + 2 * i;
+        const int lb = t * kBlocksPerTile + (NSTAGERS == 8 ? (wave >> 2) + 2 * i : i);
         return lb >= nblk_ctx ? nblk_ctx - 1 : lb;      // past the context: re-read the last tile
     };
     auto load_ids = [&](int batch) -> int { return trow[tile_of_lane(batch) >> a.sub_shift]; };
@@ -615,7 +619,7 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     };
     auto issue_part = [&](int j) {
         const int i = j >> 1;
-        const unsigned dk = iss_stage + ((wave_u >> 2) + 2 * i) * 4096;
+        const unsigned dk = iss_stage + (NSTAGERS == 8 ? (wave_u >> 2) + 2 * i : i) * 4096;
         if (j & 1) dma16(iss_page[i] + v_src, dk + V_OFF);
         else dma16(iss_page[i] + k_src, dk);
     };
@@ -629,8 +633,8 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     const bool stager = wave_u < NSTAGERS;
     if (stager) {
         issue(0);
-        if (nt > 1) issue(1);
-        if (nt > 2) issue(2);
+        if (AHEAD > 1 && nt > 1) issue(1);
+        if (AHEAD > 2 && nt > 2) issue(2);
     }
 
     Frag qf[8];
@@ -844,9 +848,10 @@ __global__ __launch_bounds__(64 * NW) void prefill_ring_kernel(const PrefillArgs
     for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks].v));   // q landed before the loop
 
     for (int j = 0; j < nt; ++j) {
-        // this thread's 4 loads of tile j are older than those of tiles j+1 and j+2
-        if (j + 2 < nt) KUN_WAIT_VMCNT(8);
-        else if (j + 1 < nt) KUN_WAIT_VMCNT(4);
+        // this thread's loads of tile j are older than those of the AHEAD - 1 tiles issued after it
+        constexpr int LPT = 2 * LOADS;                 // loads per lane and tile
+        if (AHEAD > 2 && j + 2 < nt) KUN_WAIT_VMCNT(2 * LPT);
+        else if (AHEAD > 1 && j + 1 < nt) KUN_WAIT_VMCNT(LPT);
         else KUN_WAIT_VMCNT(0);
         __builtin_amdgcn_s_barrier();                  // tile j complete in LDS; everybody has left tile j-1
         if (stager && j + AHEAD < nt) issue(j + AHEAD);          // into the stage tile j-1 used
@@ -969,6 +974,7 @@ TileShape choose_shape() {
         if (!strcmp(e, "8x1")) return TileShape{8, 1, false, false};
         if (!strcmp(e, "4x2")) return TileShape{4, 2, false, false};
         if (!strcmp(e, "4x1")) return TileShape{4, 1, false, false};
+        if (!strcmp(e, "4x1ring")) return TileShape{4, 1, true, false};
     }
     return TileShape{8, 1, true, false};
 }
@@ -999,6 +1005,7 @@ void launch_prefill(const PrefillArgs& a, dim3 grid, TileShape t, hipStream_t st
     if (t.persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, true>), grid, dim3(512), 0, st, a);
     else if (t.nw == 12) hipLaunchKernelGGL((prefill_ring_kernel<G, 12, false>), grid, dim3(768), 0, st, a);
     else if (t.nw == 8 && t.ring) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, false>), grid, dim3(512), 0, st, a);
+    else if (t.nw == 4 && t.ring) hipLaunchKernelGGL((prefill_ring_kernel<G, 4, false>), grid, dim3(256), 0, st, a);
     else if (t.nw == 8) hipLaunchKernelGGL((prefill_kernel<G, 8, 1>), grid, dim3(512), 0, st, a);
     else if (t.nq == 2) hipLaunchKernelGGL((prefill_kernel<G, 4, 2>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((prefill_kernel<G, 4, 1>), grid, dim3(256), 0, st, a);

@@ -56,7 +56,7 @@ def set_shape(shape):
         os.environ["KUN_PREFILL_SHAPE"] = shape
 
 
-@pytest.mark.parametrize("shape", ["ring", "persistent", "12x1", "8x1", "4x2", "4x1"])
+@pytest.mark.parametrize("shape", ["ring", "persistent", "12x1", "8x1", "4x2", "4x1", "4x1ring"])
 @pytest.mark.parametrize("G", [4, 8, 1, 2])
 def test_ragged_chunks(G, shape):
     set_shape(shape)
@@ -71,7 +71,7 @@ def test_ragged_chunks(G, shape):
     dw.close()
 
 
-@pytest.mark.parametrize("shape", ["ring", "persistent", "12x1", "8x1"])
+@pytest.mark.parametrize("shape", ["ring", "persistent", "12x1", "8x1", "4x1ring"])
 @pytest.mark.parametrize("profile", ["steps", "jump", "decay"])
 def test_scores_that_outgrow_the_running_maximum(profile, shape):
     # Key magnitude changes along the context, so the rows' reference maximum has to move on tiles
@@ -234,7 +234,7 @@ def test_blocks_of_64_tokens(G, d, dtype, B):
     dw.close()
 
 
-@pytest.mark.parametrize("mode", ["persistent", "on16", "split", "12x1", "8x1", "4x2", "4x1"])
+@pytest.mark.parametrize("mode", ["persistent", "on16", "split", "12x1", "8x1", "4x2", "4x1", "4x1ring"])
 @pytest.mark.parametrize("G", [8, 2])
 def test_blocks_of_64_tokens_other_launches(G, mode):
     # the fetching kernel, a limited number of workgroups, launches small enough to split the keys,

@@ -963,7 +963,8 @@ bool mfma_shape(const kun_kv_pool* p) { return p->dtype == KUN_BF16 && p->d == 1
 // items (ring kernel, 8 waves) instead of one workgroup per item.  Default: ring kernel, 8 waves, one
 // workgroup per item (measured equal to one fetching workgroup per compute unit).
 // KUN_PREFILL_SHAPE picks another one for sweeps and cross-checks: "persistent" (one fetching
-// workgroup per compute unit), "12x1" (ring kernel, 12 waves), "8x1", "4x2", "4x1".
+// workgroup per compute unit), "12x1" (ring kernel, 12 waves), "4x1ring" (ring kernel, 4 waves, two
+// workgroups per compute unit), "8x1", "4x2", "4x1" (register-staged).
 struct TileShape { int nw, nq; bool ring, persistent; };
 
 TileShape choose_shape() {

@@ -57,6 +57,8 @@ struct PrefillArgs {
     int2* items;          // workspace: (chunk, position tile)
     // Launches with too few items to fill the chip split the keys of an item over several workgroups:
     const int2* split_info;   // workspace, NULL when the launch cannot need it: per item (split | nsplit << 16, slot)
+    const int4* desc;         // workspace: two int4 per list entry, (chunk, position tile, prior tokens, first query row)
+                              // and (chunk tokens, first key tile, key tiles, partial-result slot or -1), for the ring kernels
     int4* split_items;        // workspace: (chunk, position tile, nsplit, first slot) of every split item
     int32_t* n_split_items;   // workspace
     float* part_o;            // workspace: [slot, kvh, 256 rows, 128] unnormalised outputs of a key range
@@ -109,7 +111,17 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
                                                                   int max_entries,
                                                                   int2* __restrict__ split_info,
                                                                   int4* __restrict__ split_items,
-                                                                  int32_t* __restrict__ n_split_items) {
+                                                                  int32_t* __restrict__ n_split_items,
+                                                                  int4* __restrict__ desc) {
+    // everything a workgroup needs to know about list entry i, so that it starts with one lookup
+    auto write_desc = [&](int i, int2 it, int2 si) {
+        const int qs = q_start[it.x], c = q_start[it.x + 1] - qs, p = prior[it.x];
+        const int n_tiles = (p + min((it.y + 1) * pos_per_tile, c) - 1) / BN + 1;
+        const int split = si.x & 0xffff, nsplit = si.x >> 16;
+        const int kt0 = split * n_tiles / nsplit;
+        desc[2 * i] = make_int4(it.x, it.y, p, qs);
+        desc[2 * i + 1] = make_int4(c, kt0, (split + 1) * n_tiles / nsplit - kt0, si.y);
+    };
     __shared__ int base_s;
     __shared__ int cnt[kPlanThreads / 64];               // per-wave totals of the scan
     __shared__ int cost[kPlanSortMax];
@@ -176,6 +188,8 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
     for (int i = tid; i < ns; i += kPlanThreads) items[atomicAdd(&hist[cost[i]], 1)] = tmp_item[i];
     if (split_target == 0) {
         if (tid == 0) *n_items = total;
+        __syncthreads();
+        for (int i = tid; i < total; i += kPlanThreads) write_desc(i, items[i], make_int2(1 << 16, -1));
         return;
     }
     // Too few workgroups for the chip (the host only asks when that is possible): give every item up to
@@ -230,6 +244,8 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
         *n_items = n_out_s;
         *n_split_items = n_split_s;
     }
+    __syncthreads();
+    for (int i = tid; i < n_out_s; i += kPlanThreads) write_desc(i, items[i], split_info[i]);
 }
 
 // Staging of one 64-key tile (4 KV blocks): K rows XOR-swizzled by 16-byte chunk, V^T pages as stored.
@@ -534,12 +550,12 @@ void prefill_ring_kernel(const PrefillArgs a) {
         wi = s_next;
     }
     const int item = wi / a.Hkv, kvh = wi % a.Hkv;
-    if (item >= *a.n_items) return;                    // (fetched indices can run past the list's capacity)
-    const int2 it2 = a.items[item];
-    const int chunk = it2.x, qt = it2.y;
-    const int p = a.prior[chunk];
-    const int qs = a.q_start[chunk];
-    const int c = a.q_start[chunk + 1] - qs;
+    if (PERSIST && item >= *a.n_items) return;         // (fetched indices can run past the list's capacity)
+    const int n_items = PERSIST ? item + 1 : *a.n_items;   // plain launch: the grid is within the capacity, so the
+    const int4 d0 = a.desc[2 * item], d1 = a.desc[2 * item + 1];     // entry is read together with the list's length
+    if (item >= n_items) return;
+    const int chunk = d0.x, qt = d0.y, p = d0.z, qs = d0.w, c = d1.x;
+    const int kt0 = d1.y, nt = d1.z, part_slot = d1.w;   // this workgroup's key tiles: all of the item's, or one of its key ranges
     const int ctx = p + c;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, jh = lane >> 5;
@@ -549,17 +565,6 @@ void prefill_ring_kernel(const PrefillArgs a) {
 
     const int32_t* trow = a.table + (size_t)chunk * a.max_blocks;
     const int nblk_ctx = (ctx + kBlock - 1) / kBlock;
-    const int wg_vis_max = p + min(pos0 + POS, c) - 1;
-    const int n_tiles = wg_vis_max / BN + 1;
-    // this workgroup's share of the key tiles: all of them, or one of the item's key ranges
-    int kt0 = 0, nt = n_tiles, part_slot = -1;
-    if (a.split_info) {
-        const int2 si = a.split_info[item];
-        const int split = si.x & 0xffff, nsplit = si.x >> 16;
-        kt0 = split * n_tiles / nsplit;
-        nt = (split + 1) * n_tiles / nsplit - kt0;
-        part_slot = si.y;
-    }
 
     constexpr int TPB = 64 / LOADS;
     // Page addresses this wave stages, resolved a batch at a time in the vector lanes (lane LOADS*t + i
@@ -1022,7 +1027,7 @@ namespace {
 struct PrefillLayout {
     bool may_split;
     int max_items, cap_entries;
-    size_t off_items, off_split_info, off_split_items, off_part_ml, off_part_o, total;
+    size_t off_items, off_desc, off_split_info, off_split_items, off_part_ml, off_part_o, total;
 };
 
 PrefillLayout prefill_layout(const kun_kv_pool* p, int n_chunks, int Hq, int total_new_tokens, int pos_per_tile) {
@@ -1035,6 +1040,7 @@ PrefillLayout prefill_layout(const kun_kv_pool* p, int n_chunks, int Hq, int tot
     lay.cap_entries = lay.may_split ? 2 * lay.max_items + kSplitTarget / p->Hkv + 1 : lay.max_items;
     size_t o = 256;
     lay.off_items = o;        o += align256(sizeof(int2) * (size_t)lay.cap_entries);
+    lay.off_desc = o;         o += align256(sizeof(int4) * 2 * (size_t)lay.cap_entries);
     lay.off_split_info = o;   if (lay.may_split) o += align256(sizeof(int2) * (size_t)lay.cap_entries);
     lay.off_split_items = o;  if (lay.may_split) o += align256(sizeof(int4) * (size_t)(kSplitTarget + 1));
     const size_t part_wgs = 2 * (size_t)kSplitTarget + p->Hkv;       // (key range, kv head) workgroups of split items
@@ -1103,6 +1109,7 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     a.next_item = (int32_t*)ws + 16;
     a.n_split_items = (int32_t*)ws + 32;
     a.items = (int2*)(ws + lay.off_items);
+    a.desc = (const int4*)(ws + lay.off_desc);
     a.split_info = can_split ? (const int2*)(ws + lay.off_split_info) : nullptr;
     a.split_items = (int4*)(ws + lay.off_split_items);
     a.part_ml = (float*)(ws + lay.off_part_ml);
@@ -1121,7 +1128,7 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, q_start, prior_len, n_chunks,
                        pos_per_tile, a.max_items, a.n_items, a.next_item, a.items, p->Hkv,
                        can_split ? kSplitTarget : 0, lay.cap_entries, (int2*)(ws + lay.off_split_info), a.split_items,
-                       a.n_split_items);
+                       a.n_split_items, (int4*)(ws + lay.off_desc));
     KUN_HIP_CHECK_LAUNCH();
     size_t wgs = (size_t)(can_split ? lay.cap_entries : lay.max_items) * p->Hkv;
     if (persistent) {

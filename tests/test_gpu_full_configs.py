@@ -123,6 +123,51 @@ def test_other_numbers_of_kv_heads(Hkv, G):
     dw.close()
 
 
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_seeded_random_shapes_lengths_and_pools(seed):
+    # shape, block size, lengths, chunking and the split of the pool into ranges all drawn from the seed:
+    # one decode call and one prefill call against the oracle (all decode rows, sampled prefill rows)
+    rng = np.random.default_rng(1234 + seed)
+    mfma = seed % 3 != 2
+    G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8] + ([16] if mfma else [])))
+    Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+    B = int(rng.choice([16, 32, 64, 128]))
+    d, dtype = (128, "bf16") if mfma else [(64, "f32"), (128, "f32"), (64, "bf16")][seed % 3 if seed % 3 != 2 else int(rng.integers(3))]
+    sh = synth.LayerShape(Hq=Hkv * G, Hkv=Hkv, d=d, B=B, dtype=dtype)
+    S = int(rng.integers(1, 24))
+    lens = [int(x) for x in np.clip(rng.lognormal(5.5, 1.2, size=S), 1, 5000).astype(int)]
+    if mfma:
+        chunks = [(int(rng.integers(0, 3000)), int(rng.integers(0, 400))) for _ in range(int(rng.integers(1, 6)))]
+    else:
+        chunks = [(int(rng.integers(0, 300)), int(rng.integers(0, 40))) for _ in range(int(rng.integers(1, 4)))]
+    nr = int(rng.integers(1, 5))
+    fr = rng.random(nr) + 0.2
+    w = synth.custom_workload(f"rnd{seed}", sh, lens, chunks=chunks, seed=100 + seed, extra_blocks=int(rng.integers(nr, 9)),
+                              range_fracs=tuple((fr / fr.sum()).tolist()))
+    print(f"seed {seed}: Hq={sh.Hq} Hkv={Hkv} d={d} {dtype} B={B} S={S} chunks={chunks} ranges={w.range_blocks}", flush=True)
+    dw = DeviceWorkload(w)
+    dw.out_dec.fill_(float("nan"))
+    dw.out_pre.fill_(float("nan"))
+    pre = dw.prefill().clone()
+    out = dw.decode().clone()
+    torch.cuda.synchronize()
+    tol = 1e-5 if dtype == "f32" else TOL
+    assert decode_err(dw, out, list(range(w.S))) <= tol
+    got = pre.double().cpu().numpy()
+    assert np.isfinite(got).all()
+    for i, (p, c) in enumerate(w.chunks):
+        if c == 0:
+            continue
+        q0 = int(dw.q_start_host[i])
+        rws = sorted(set([0, c - 1] + rng.choice(c, size=min(c, 24), replace=False).tolist()))
+        pool, tab = bridge.compact_pool(dw.ranges, w.range_blocks, [w.block_tables[w.S + i]], [p + c], sh.Hkv, sh.d,
+                                        sh.B, sh.dtype)
+        ref, _ = O.paged_prefill_chunk(pool, bridge.host_bits(dw.q_pre[q0:q0 + c]), tab[0], p, c, sh.Hq, sh.scale,
+                                       rows=rws)
+        assert float(np.abs(got[q0:q0 + c][rws] - ref).max()) <= tol
+    dw.close()
+
+
 def test_config5_150GB_pool_sampled():
     w = synth.config(5)
     dw = DeviceWorkload(w, poison=False)

@@ -159,7 +159,8 @@ KUN_API size_t kun_decode_workspace_bytes(const kun_kv_pool* pool, int S, int nu
  * out[s] = softmax(scale * q K^T) V over those tokens.  ctx_len: device int32 [S]; a request with
  * ctx_len 0 is skipped and its output row left untouched.  block_table: device int32
  * [S, max_blocks].  total_ctx_upper_bound: host-known bound on sum(ctx_len) (0 = full pool); it
- * sizes the launch and must be the value used for kun_decode_workspace_bytes or smaller.  If
+ * sizes the launch and must be the value used for kun_decode_workspace_bytes or smaller; the
+ * split-K partition size is chosen from it, so a bound close to the real sum is faster than 0.  If
  * sum(ctx_len) is above it, the requests whose partial results no longer fit the workspace are
  * left out as a whole (their rows of out stay untouched); nothing is read or written out of bounds.
  * workspace: device, 256-byte aligned, holds the split-K partial results; contents are scratch. */

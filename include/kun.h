@@ -80,6 +80,18 @@ KUN_API const char* kun_status_string(int status);
  * by the next failure on the same thread. */
 KUN_API const char* kun_last_hip_error(void);
 
+/* Tuning options for tests and sweeps, process-wide.  The library reads the environment variables of
+ * the same names ONCE, when it is loaded; afterwards only this call changes an option (value NULL or
+ * "" = back to the default), and no launch reads the environment.  Not synchronised with launches
+ * made from other host threads.  KUN_ERR_INVALID_ARG for an unknown name or a value outside the set:
+ *   KUN_DECODE_PART    tokens per split-K partition, a multiple of 32 (default: chosen from the bound)
+ *   KUN_DECODE_WAVES   1, 2 or 4 waves per workgroup of the matrix-core decode kernel (default 4)
+ *   KUN_DECODE_KERNEL  "generic": the vector-ALU decode kernel for every shape; "mfma": the default
+ *   KUN_DECODE_MAP     "flat": item-major workgroup order; "xcd": the default XCD-aware order
+ *   KUN_PREFILL_SHAPE  "persistent": workgroups that fetch their work items, one per compute unit;
+ *                      "ring": the earlier one-barrier-per-tile kernel (cross-check); "default" */
+KUN_API int kun_set_option(const char* name, const char* value);
+
 /* ---- pool growth (Section 4.1: the KVCache region is extended at its tail with the memory of
  *      dropped parameters; Section 5.6: two consecutive drops enlarge it twice) ---------------- */
 
@@ -223,8 +235,11 @@ KUN_API int kun_vmm_region_info(const kun_vmm_region* region, void** base, size_
 /* Allocate `bytes` of device memory as one chunk and map it at the tail. */
 KUN_API int kun_vmm_region_grow(kun_vmm_region* region, size_t bytes);
 /* Unmap the last `bytes` of src (whole chunks) and map the same physical chunks, in the same order,
- * at the tail of dst: the contents move with them, no copy is made.  On KUN_ERR_HIP the chunks
- * moved so far stay at dst and the others at src. */
+ * at the tail of dst: the contents move with them, no copy is made.  All or nothing: when a driver
+ * call fails (KUN_ERR_HIP) the steps already made are undone and both regions are what they were.
+ * Should the driver refuse the undoing as well, both regions still list exactly what is mapped -- src
+ * ends below the first chunk that could not be put back, dst keeps the chunks that arrived, a chunk
+ * mapped nowhere is released -- and kun_vmm_region_info shows it (mapped_bytes changed). */
 KUN_API int kun_vmm_region_move_tail(kun_vmm_region* src, kun_vmm_region* dst, size_t bytes);
 /* Unmap the last `bytes` and give the physical memory back to the driver. */
 KUN_API int kun_vmm_region_shrink(kun_vmm_region* region, size_t bytes);
@@ -263,7 +278,7 @@ KUN_API int kun_lookahead(const kun_cost_model* model, const kun_chunk* queue, i
                   int max_microbatches, kun_chunk* out_chunks, int chunk_capacity,
                   int32_t* out_mb_start, int mb_capacity, int* n_microbatches, int* n_chunks);
 
-/* Drop-plan generation (Section 4.2): instance groups, each holding one copy of the num_layers
+/* Drop-plan generation (Section 4.1, "Parameter drop during memory overloading", Algorithm 1): instance groups, each holding one copy of the num_layers
  * layers, wait in a priority queue by size (equal sizes: the group formed first); while
  * demand_bytes is not met and two groups remain, the two smallest merge and one redundant copy
  * (num_layers * layer_bytes) is dropped.  initial_group: host [n_instances], group number of each

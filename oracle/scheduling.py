@@ -9,7 +9,7 @@ Nothing in the product path may import this module; it shares no code with the C
 * Lookahead batch formulation (Section 4.3): the queued tokens start as one microbatch that is
   split recursively into two microbatches of (nearly) equal cost until a microbatch would fall
   below a token threshold.
-* Drop-plan generation (Section 4.2): instance groups sit in a priority queue by size; while the
+* Drop-plan generation (Section 4.1, Algorithm 1): instance groups sit in a priority queue by size; while the
   memory demand is not met the two smallest groups are merged and one redundant copy of the
   parameters is dropped.
 
@@ -124,7 +124,7 @@ def lookahead(chunks: Sequence[Chunk], alpha: float, beta: float, gamma: float, 
 # ---------------------------------------------------------------------------------------------
 @dataclass
 class DropPlan:
-    ok: bool                              # demand met; otherwise fall back (Section 4.2)
+    ok: bool                              # demand met; otherwise fall back (Section 4.1)
     merges: List[Tuple[List[int], List[int]]]      # instance ids of the two groups of every merge, in order
     groups: List[List[int]]               # final groups (instance ids in ascending order)
     freed_bytes: int                      # one parameter copy per merge

@@ -634,11 +634,7 @@ int64_t default_bound(const kun_kv_pool* p, int S, int64_t ub) {
 // resident workgroups each, and a work list that starts the long partitions first); measured best
 // on the 8B/70B-shaped batches.
 int choose_part_tokens(const kun_kv_pool* p, int64_t ub) {
-    const char* e = getenv("KUN_DECODE_PART");
-    if (e) {
-        int v = atoi(e);
-        if (v >= 32 && v % 32 == 0) return v;
-    }
+    if (kun_options().decode_part > 0) return kun_options().decode_part;
     const int64_t per = ub * p->Hkv / kPartDivisor;
     int P = kPartChoices[0];
     for (int i = 0; i < kNumPartChoices; ++i)
@@ -746,6 +742,12 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
     return KUN_OK;
 }
 
+namespace {
+int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* block_table, int max_blocks,
+                   const int32_t* ctx_len, int S, int Hq, float scale, int64_t ub, void* workspace,
+                   size_t workspace_bytes, void* stream);
+}
+
 extern "C" {
 
 size_t kun_decode_workspace_bytes(const kun_kv_pool* p, int S, int Hq, int64_t ub) {
@@ -766,12 +768,22 @@ size_t kun_decode_workspace_bytes(const kun_kv_pool* p, int S, int Hq, int64_t u
 int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* block_table,
                      int max_blocks, const int32_t* ctx_len, int S, int Hq, float scale,
                      int64_t ub, void* workspace, size_t workspace_bytes, void* stream) {
+    return decode_enqueue(p, q, out, block_table, max_blocks, ctx_len, S, Hq, scale, ub, workspace, workspace_bytes,
+                          stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* block_table,
+                   int max_blocks, const int32_t* ctx_len, int S, int Hq, float scale,
+                   int64_t ub, void* workspace, size_t workspace_bytes, void* stream) {
     if (!decode_shape_ok(p, S, Hq)) return KUN_ERR_INVALID_ARG;
     if (S == 0) return KUN_OK;
     if (!q || !out || !block_table || !ctx_len || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
     const int G = Hq / p->Hkv;
-    const char* force = getenv("KUN_DECODE_KERNEL");     // "generic" forces the vector-ALU kernel
-    const bool generic_only = force && force[0] == 'g';
+    const bool generic_only = kun_options().decode_generic;
     const bool mfma = p->dtype == KUN_BF16 && p->d == 128 && !generic_only;
     if (G < 1 || (G > 8 && !(G == 16 && mfma))) return KUN_ERR_UNSUPPORTED;   // 16 heads per KV head: the MFMA kernel only
     ub = default_bound(p, S, ub);
@@ -814,11 +826,8 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     dim3 grid((unsigned)((size_t)lay.max_items * p->Hkv));
     int rc = KUN_OK;
     if (mfma) {
-        int nw = 4;
-        const char* e = getenv("KUN_DECODE_WAVES");
-        if (e) nw = atoi(e);
-        const char* map = getenv("KUN_DECODE_MAP");      // "flat": item-major workgroup order
-        a.xcd_map = !(map && map[0] == 'f');
+        const int nw = kun_options().decode_waves;
+        a.xcd_map = !kun_options().decode_flat_map;
         if (a.xcd_map) grid = dim3((unsigned)(((size_t)lay.max_items + 7) / 8 * 8 * p->Hkv));
         if (nw == 1) hipLaunchKernelGGL((decode_partial_mfma<1>), grid, dim3(64), 0, st, a);
         else if (nw == 2) hipLaunchKernelGGL((decode_partial_mfma<2>), grid, dim3(128), 0, st, a);
@@ -840,4 +849,5 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
     return KUN_OK;
 }
 
-}  // extern "C"
+}  // namespace
+

@@ -42,6 +42,18 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
                             const int32_t* ctx_len, const int32_t* row_of_seq, int T, int Hq, float scale,
                             void* workspace, hipStream_t st);
 
+// Process-wide tuning options (kun_set_option): read from the environment once, when the library is
+// loaded, and changed only by kun_set_option afterwards; launches read this struct, never the
+// environment.
+struct KunOptions {
+    int decode_part = 0;          // tokens per split-K partition (multiple of 32); 0 = chosen from the bound
+    int decode_waves = 4;         // waves per workgroup of the MFMA decode kernel: 1, 2 or 4
+    bool decode_generic = false;  // run the vector-ALU decode kernel where the MFMA one would
+    bool decode_flat_map = false; // item-major workgroup order instead of the XCD-aware one
+    int prefill_shape = 0;        // 0 = default kernel; other values select cross-check kernels (prefill.hip)
+};
+const KunOptions& kun_options();
+
 // Remembers which HIP call failed and how, per host thread, for kun_last_hip_error().
 void kun_note_hip_error(const char* call, hipError_t e);
 

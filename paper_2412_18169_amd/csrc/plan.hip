@@ -2,7 +2,7 @@
 //   * the cost model of a chunk and of a microbatch (Section 4.3, Eq. 1-3) and its least-squares fit,
 //   * the lookahead batch formulation (Section 4.3): recursive halving of the queued tokens into
 //     cost-balanced microbatches,
-//   * drop-plan generation (Section 4.2): merge the two smallest instance groups until the memory
+//   * drop-plan generation (Section 4.1, Algorithm 1): merge the two smallest instance groups until the memory
 //     demand is met; each merge drops one redundant copy of the parameters.
 #include <math.h>
 

@@ -8,12 +8,56 @@
 #include <new>
 
 #include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
 
 #include "kun_internal.h"
 
 namespace {
 thread_local char g_hip_error[160] = "";
+
+// One option from its textual value (NULL or "" = back to the default); false if the value is not valid.
+bool apply_option(KunOptions& o, const char* name, const char* value) {
+    const KunOptions dflt;
+    const bool unset = !value || !value[0];
+    if (!strcmp(name, "KUN_DECODE_PART")) {
+        const int v = unset ? 0 : atoi(value);
+        if (!unset && (v < 32 || v % 32 != 0)) return false;
+        o.decode_part = v;
+    } else if (!strcmp(name, "KUN_DECODE_WAVES")) {
+        const int v = unset ? dflt.decode_waves : atoi(value);
+        if (v != 1 && v != 2 && v != 4) return false;
+        o.decode_waves = v;
+    } else if (!strcmp(name, "KUN_DECODE_KERNEL")) {
+        if (!unset && strcmp(value, "generic") && strcmp(value, "mfma")) return false;
+        o.decode_generic = !unset && !strcmp(value, "generic");
+    } else if (!strcmp(name, "KUN_DECODE_MAP")) {
+        if (!unset && strcmp(value, "flat") && strcmp(value, "xcd")) return false;
+        o.decode_flat_map = !unset && !strcmp(value, "flat");
+    } else if (!strcmp(name, "KUN_PREFILL_SHAPE")) {
+        if (unset || !strcmp(value, "default")) o.prefill_shape = 0;
+        else if (!strcmp(value, "persistent")) o.prefill_shape = 1;
+        else if (!strcmp(value, "ring")) o.prefill_shape = 2;
+        else return false;
+    } else {
+        return false;
+    }
+    return true;
 }
+
+const char* const kOptionNames[] = {"KUN_DECODE_PART", "KUN_DECODE_WAVES", "KUN_DECODE_KERNEL", "KUN_DECODE_MAP",
+                                    "KUN_PREFILL_SHAPE"};
+
+KunOptions options_from_environment() {
+    KunOptions o;
+    for (const char* n : kOptionNames) (void)apply_option(o, n, getenv(n));   // invalid values are ignored
+    return o;
+}
+
+KunOptions g_options = options_from_environment();
+}
+
+const KunOptions& kun_options() { return g_options; }
 
 void kun_note_hip_error(const char* call, hipError_t e) {
     snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s (%d)", call, hipGetErrorString(e), (int)e);
@@ -22,6 +66,14 @@ void kun_note_hip_error(const char* call, hipError_t e) {
 extern "C" {
 
 const char* kun_last_hip_error(void) { return g_hip_error; }
+
+int kun_set_option(const char* name, const char* value) {
+    if (!name) return KUN_ERR_INVALID_ARG;
+    KunOptions o = g_options;
+    if (!apply_option(o, name, value)) return KUN_ERR_INVALID_ARG;
+    g_options = o;
+    return KUN_OK;
+}
 
 const char* kun_status_string(int st) {
     switch (st) {

@@ -973,15 +973,7 @@ bool mfma_shape(const kun_kv_pool* p) { return p->dtype == KUN_BF16 && p->d == 1
 struct TileShape { int nw, nq; bool ring, persistent; };
 
 TileShape choose_shape() {
-    const char* e = getenv("KUN_PREFILL_SHAPE");
-    if (e) {
-        if (!strcmp(e, "persistent")) return TileShape{8, 1, true, true};
-        if (!strcmp(e, "12x1")) return TileShape{12, 1, true, false};
-        if (!strcmp(e, "8x1")) return TileShape{8, 1, false, false};
-        if (!strcmp(e, "4x2")) return TileShape{4, 2, false, false};
-        if (!strcmp(e, "4x1")) return TileShape{4, 1, false, false};
-        if (!strcmp(e, "4x1ring")) return TileShape{4, 1, true, false};
-    }
+    if (kun_options().prefill_shape == 1) return TileShape{8, 1, true, true};
     return TileShape{8, 1, true, false};
 }
 

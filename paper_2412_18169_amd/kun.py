@@ -21,7 +21,7 @@ KUN_F32, KUN_BF16 = 0, 1
 KUN_MAX_RANGES = 16
 
 SYMBOLS = [
-    "kun_status_string", "kun_last_hip_error", "kun_kv_pool_create", "kun_kv_pool_extend", "kun_kv_pool_num_blocks",
+    "kun_status_string", "kun_last_hip_error", "kun_set_option", "kun_kv_pool_create", "kun_kv_pool_extend", "kun_kv_pool_num_blocks",
     "kun_kv_pool_num_ranges", "kun_kv_pool_block_bytes", "kun_kv_pool_resolve",
     "kun_kv_pool_destroy", "kun_validate_block_table", "kun_slot_map", "kun_kv_append",
     "kun_decode_workspace_bytes", "kun_paged_decode", "kun_prefill_workspace_bytes",
@@ -65,6 +65,7 @@ def lib() -> ctypes.CDLL:
     L.kun_status_string.argtypes = [i32]
     L.kun_last_hip_error.restype = ctypes.c_char_p
     L.kun_last_hip_error.argtypes = []
+    L.kun_set_option.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
     L.kun_kv_pool_create.argtypes = [P(vp), vp, sz, i32, i32, i32, i32]
     L.kun_kv_pool_extend.argtypes = [vp, vp, sz, P(i64), P(i64)]
     L.kun_kv_pool_num_blocks.argtypes = [vp, P(i64)]
@@ -111,6 +112,15 @@ def last_hip_error() -> str:
 
 def status_string(status: int) -> str:
     return lib().kun_status_string(int(status)).decode()
+
+
+OPTION_NAMES = ("KUN_DECODE_PART", "KUN_DECODE_WAVES", "KUN_DECODE_KERNEL", "KUN_DECODE_MAP", "KUN_PREFILL_SHAPE")
+
+
+def kun_set_option(name: str, value=None) -> None:
+    """value None = back to the default."""
+    _check(lib().kun_set_option(name.encode(), None if value is None else str(value).encode()),
+           f"kun_set_option({name}={value})")
 
 
 def _check(st: int, where: str) -> None:

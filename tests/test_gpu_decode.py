@@ -43,10 +43,10 @@ def check_decode(dw, seqs=None, tol=None, out=None):
 def _announce(request):
     print(f"\n[gpu-case] {request.node.nodeid}", flush=True)
     yield
-    os.environ.pop("KUN_DECODE_KERNEL", None)
-    os.environ.pop("KUN_DECODE_PART", None)
-    os.environ.pop("KUN_DECODE_WAVES", None)
-    os.environ.pop("KUN_DECODE_MAP", None)
+    kun.kun_set_option("KUN_DECODE_KERNEL", None)
+    kun.kun_set_option("KUN_DECODE_PART", None)
+    kun.kun_set_option("KUN_DECODE_WAVES", None)
+    kun.kun_set_option("KUN_DECODE_MAP", None)
 
 
 def test_config1_tiny_fp32():
@@ -61,7 +61,7 @@ def test_config1_tiny_fp32():
                                        (4, 64, "f32"), (8, 128, "f32"), (1, 64, "f32"), (2, 128, "f32")])
 def test_shapes_ragged_lengths(kernel, G, d, dtype):
     if kernel == "generic":
-        os.environ["KUN_DECODE_KERNEL"] = "generic"
+        kun.kun_set_option("KUN_DECODE_KERNEL", "generic")
     elif not (dtype == "bf16" and d == 128):
         pytest.skip("the MFMA kernel covers bf16 with head_dim 128 only")
     sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=16, dtype=dtype)
@@ -76,8 +76,8 @@ def test_shapes_ragged_lengths(kernel, G, d, dtype):
 @pytest.mark.parametrize("part", [32, 64, 256, 1024])
 @pytest.mark.parametrize("waves", [1, 2, 4])
 def test_result_is_invariant_to_partitioning(part, waves):
-    os.environ["KUN_DECODE_PART"] = str(part)
-    os.environ["KUN_DECODE_WAVES"] = str(waves)
+    kun.kun_set_option("KUN_DECODE_PART", str(part))
+    kun.kun_set_option("KUN_DECODE_WAVES", str(waves))
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     w = synth.custom_workload("parts", sh, [5, 40, 100, 333, 1025, 2049], extra_blocks=3)
     dw = DeviceWorkload(w)
@@ -91,8 +91,8 @@ def test_scores_that_outgrow_the_running_maximum(profile, kernel):
     # key magnitude changes along the context: the running maximum moves late and by a lot
     # ("jump": by more than exp2 can hold in fp32), or never again ("decay")
     if kernel == "generic":
-        os.environ["KUN_DECODE_KERNEL"] = "generic"
-    os.environ["KUN_DECODE_PART"] = "256"
+        kun.kun_set_option("KUN_DECODE_KERNEL", "generic")
+    kun.kun_set_option("KUN_DECODE_PART", "256")
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     lens = [700, 1300, 64, 2500, 201]
     w = synth.custom_workload("grow", sh, lens, extra_blocks=0)
@@ -130,7 +130,7 @@ def test_bound_below_the_real_context_sum_computes_whole_requests_or_none(part):
     # total_ctx_upper_bound sizes the workspace; when sum(ctx_len) is above it, the partitions that do
     # not fit are dropped by request: a row of `out` is either complete and correct or untouched
     if part:
-        os.environ["KUN_DECODE_PART"] = str(part)
+        kun.kun_set_option("KUN_DECODE_PART", str(part))
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     lens = [700, 33, 1500, 64, 900, 2100, 5, 1200, 300, 800] * 3
     w = synth.custom_workload("bound", sh, lens, extra_blocks=3, range_fracs=(0.5, 0.5))
@@ -152,7 +152,7 @@ def test_bound_below_the_real_context_sum_computes_whole_requests_or_none(part):
         assert done < len(lens)
         if bound > 1000:
             assert done > 0
-    os.environ.pop("KUN_DECODE_PART", None)
+    kun.kun_set_option("KUN_DECODE_PART", None)
     dw.close()
 
 
@@ -166,11 +166,11 @@ def test_workgroup_order_does_not_change_a_bit(B):
     dw = DeviceWorkload(w)
     outs = {}
     for mode in ("xcd", "flat"):
-        os.environ["KUN_DECODE_MAP"] = mode
+        kun.kun_set_option("KUN_DECODE_MAP", mode)
         dw.out_dec.fill_(float("nan"))
         outs[mode] = dw.decode().clone()
         torch.cuda.synchronize()
-    os.environ.pop("KUN_DECODE_MAP")
+    kun.kun_set_option("KUN_DECODE_MAP", None)
     assert torch.isfinite(outs["xcd"].float()).all()
     assert torch.equal(outs["xcd"].view(torch.int16), outs["flat"].view(torch.int16))
     check_decode(dw)
@@ -188,7 +188,7 @@ def test_any_number_of_query_heads_per_kv_head_up_to_8(dtype, d, G, B):
     dw = DeviceWorkload(w)
     for part in (None, "64"):
         if part:
-            os.environ["KUN_DECODE_PART"] = part
+            kun.kun_set_option("KUN_DECODE_PART", part)
         dw._ws_dec = None
         dw.out_dec.fill_(float("nan"))
         check_decode(dw)
@@ -231,9 +231,9 @@ def test_empty_calls_and_refused_arguments_leave_outputs_alone():
     assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, 7, sh.scale, 0, big, need) == -1   # 7 % 2
     assert status(kun.kun_paged_decode, dw.pool, None, o, tab, tab.shape[1], ln, 3, sh.Hq, sh.scale, 0, big, need) == -1
     assert status(kun.kun_paged_prefill_chunk, dw.pool, q, o, z, z, tab, tab.shape[1], 1, 18, 4, sh.scale, big, need) == -8
-    os.environ["KUN_DECODE_KERNEL"] = "generic"            # 16 heads per KV head: not on the vector-ALU kernel
+    kun.kun_set_option("KUN_DECODE_KERNEL", "generic")            # 16 heads per KV head: not on the vector-ALU kernel
     assert status(kun.kun_paged_decode, dw.pool, q, o, tab, tab.shape[1], ln, 3, 32, sh.scale, 0, big, need) == -8
-    os.environ.pop("KUN_DECODE_KERNEL")
+    kun.kun_set_option("KUN_DECODE_KERNEL", None)
     assert status(kun.kun_slot_map, dw.pool, z, z, 2, tab, tab.shape[1], 5, z, z, z) == -1           # kv head 5 of 2
     torch.cuda.synchronize()
     assert torch.all(dw.out_dec == 3.0)
@@ -266,13 +266,13 @@ def test_blocks_of_64_tokens(G, d, dtype, B):
         assert np.array_equal(synth.to_host_bits(dw.ranges[r]).reshape(-1), opool.ranges[r], equal_nan=True)
     for kernel in ("default", "generic"):
         if kernel == "generic":
-            os.environ["KUN_DECODE_KERNEL"] = "generic"
+            kun.kun_set_option("KUN_DECODE_KERNEL", "generic")
         for part in (None, "64", "256"):
             if part:
-                os.environ["KUN_DECODE_PART"] = part
+                kun.kun_set_option("KUN_DECODE_PART", part)
             dw.out_dec.fill_(float("nan"))
             check_decode(dw)
-            os.environ.pop("KUN_DECODE_PART", None)
+            kun.kun_set_option("KUN_DECODE_PART", None)
     dw.close()
 
 
@@ -334,7 +334,7 @@ def test_pool_extension_keeps_resident_outputs_bit_identical():
         check_decode(dw, seqs=nres, out=out)
     # resident requests: bit-identical across extend (partition size pinned, so the split of a
     # request does not depend on how many requests are in the batch)
-    os.environ["KUN_DECODE_PART"] = "256"
+    kun.kun_set_option("KUN_DECODE_PART", "256")
     dw2 = DeviceWorkload(w, n_ranges_at_create=1)
     a = dw2.decode(resident[0]).clone()
     dw2.extend_next(); dw2.extend_next()
@@ -348,7 +348,7 @@ def test_pool_extension_keeps_resident_outputs_bit_identical():
 def test_extend_between_enqueued_calls_disturbs_neither():
     # the range table travels with every launch: a call enqueued before kun_kv_pool_extend keeps the
     # table it was given, a call enqueued after sees the new range, no synchronisation in between
-    os.environ["KUN_DECODE_PART"] = "256"
+    kun.kun_set_option("KUN_DECODE_PART", "256")
     sh = synth.SHAPE_8B
     rng = np.random.default_rng(8)
     lens = synth.lognormal_lengths(rng, 48, median=600, sigma=0.7, lo=16, hi=4000)

@@ -19,7 +19,7 @@ TOL = 2e-2
 def _announce(request):
     print(f"\n[gpu-case] {request.node.nodeid}", flush=True)
     yield
-    os.environ.pop("KUN_DECODE_PART", None)
+    kun.kun_set_option("KUN_DECODE_PART", None)
 
 
 def decode_err(dw, out, rows):
@@ -49,7 +49,7 @@ def test_config3_pool_extended_twice_mid_run():
     used = np.concatenate(w.block_tables)
     r, _ = synth.range_of_blocks(w.range_blocks, used.astype(np.int64))
     assert set(np.unique(r)) == {0, 1, 2}                # the final block table mixes all three ranges
-    os.environ["KUN_DECODE_PART"] = "1024"               # pin the split so residents are comparable bit for bit
+    kun.kun_set_option("KUN_DECODE_PART", "1024")               # pin the split so residents are comparable bit for bit
     outs = []
     for phase, nres in enumerate(w.phase_resident):
         if phase:
@@ -66,7 +66,7 @@ def test_config3_pool_extended_twice_mid_run():
     n0, n1 = w.phase_resident[0], w.phase_resident[1]
     assert torch.equal(outs[0][:n0], outs[1][:n0]) and torch.equal(outs[0][:n0], outs[2][:n0])
     assert torch.equal(outs[1][:n1], outs[2][:n1])
-    os.environ.pop("KUN_DECODE_PART")
+    kun.kun_set_option("KUN_DECODE_PART", None)
     out = dw.decode().clone()                            # and with the default partitioning bench.py uses
     torch.cuda.synchronize()
     assert decode_err(dw, out, sample_rows(w)) <= TOL

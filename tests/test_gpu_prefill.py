@@ -18,7 +18,7 @@ TOL = 2e-2
 def _announce(request):
     print(f"\n[gpu-case] {request.node.nodeid}", flush=True)
     yield
-    os.environ.pop("KUN_PREFILL_SHAPE", None)
+    kun.kun_set_option("KUN_PREFILL_SHAPE", None)
 
 
 def check_prefill(dw, rows_per_chunk=None, seed=0, only=None):
@@ -51,12 +51,12 @@ def check_prefill(dw, rows_per_chunk=None, seed=0, only=None):
 
 
 def set_shape(shape):
-    """"ring": the library's own choice (environment left alone); else the named variant."""
-    if shape != "ring":
-        os.environ["KUN_PREFILL_SHAPE"] = shape
+    """"default": the library's own choice; else the named variant."""
+    if shape != "default":
+        kun.kun_set_option("KUN_PREFILL_SHAPE", shape)
 
 
-@pytest.mark.parametrize("shape", ["ring", "persistent", "12x1", "8x1", "4x2", "4x1", "4x1ring"])
+@pytest.mark.parametrize("shape", ["default", "persistent"])
 @pytest.mark.parametrize("G", [4, 8, 1, 2])
 def test_ragged_chunks(G, shape):
     set_shape(shape)
@@ -71,7 +71,7 @@ def test_ragged_chunks(G, shape):
     dw.close()
 
 
-@pytest.mark.parametrize("shape", ["ring", "persistent", "12x1", "8x1", "4x1ring"])
+@pytest.mark.parametrize("shape", ["default", "persistent"])
 @pytest.mark.parametrize("profile", ["steps", "jump", "decay"])
 def test_scores_that_outgrow_the_running_maximum(profile, shape):
     # Key magnitude changes along the context, so the rows' reference maximum has to move on tiles
@@ -98,7 +98,7 @@ def test_scores_that_outgrow_the_running_maximum(profile, shape):
     dw.close()
 
 
-@pytest.mark.parametrize("shape", ["ring", "persistent", "8x1"])
+@pytest.mark.parametrize("shape", ["default", "persistent"])
 def test_more_work_items_than_the_plan_kernel_sorts(shape):
     # 5000 chunks (the plan kernel walks them 1024 at a time and orders only the first 4096 items),
     # most of them a few tokens, some empty, a few spanning several position tiles
@@ -184,13 +184,13 @@ def test_shapes_outside_the_mfma_kernels(dtype, d, G):
     dw.close()
 
 
-@pytest.mark.parametrize("shape", ["ring", "persistent", "on16"])
+@pytest.mark.parametrize("shape", ["default", "persistent", "on16"])
 @pytest.mark.parametrize("G", [8, 4, 1])
 def test_few_query_tiles_after_long_contexts_split_their_keys(G, shape):
     # launches far too small for the chip: the keys of an item are shared out over several workgroups
     # and merged (rows that see nothing of a key range, ranges of unequal length, one-tile items)
-    if shape not in ("ring", "on16"):
-        os.environ["KUN_PREFILL_SHAPE"] = shape
+    if shape not in ("default", "on16"):
+        kun.kun_set_option("KUN_PREFILL_SHAPE", shape)
     sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=128, B=16, dtype="bf16")
     for chunks in ([(3000, 40)], [(2047, 1)], [(5000, 200), (17, 3)], [(0, 700)], [(1500, 64), (64, 64), (9000, 5)]):
         w = synth.custom_workload("few", sh, [3], chunks=chunks, extra_blocks=3, range_fracs=(0.5, 0.5))
@@ -234,13 +234,13 @@ def test_blocks_of_64_tokens(G, d, dtype, B):
     dw.close()
 
 
-@pytest.mark.parametrize("mode", ["persistent", "on16", "split", "12x1", "8x1", "4x2", "4x1", "4x1ring"])
+@pytest.mark.parametrize("mode", ["persistent", "on16", "split"])
 @pytest.mark.parametrize("G", [8, 2])
 def test_blocks_of_64_tokens_other_launches(G, mode):
     # the fetching kernel, a limited number of workgroups, launches small enough to split the keys,
     # and the other tile shapes
     if mode not in ("on16", "split"):
-        os.environ["KUN_PREFILL_SHAPE"] = mode
+        kun.kun_set_option("KUN_PREFILL_SHAPE", mode)
     sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=128, B=(64 if G == 8 else 128), dtype="bf16")
     sets = ([(3000, 40)], [(5000, 200), (17, 3)], [(1500, 64), (64, 64), (9000, 5)]) if mode == "split" else \
         ([(0, 1), (63, 65), (64, 129), (100, 200), (0, 300), (700, 257), (1000, 31), (3000, 40), (0, 2100)],)
@@ -258,14 +258,13 @@ def test_blocks_of_64_tokens_other_launches(G, mode):
         dw.close()
 
 
-@pytest.mark.parametrize("mode", ["ring", "persistent", "on16", "split", "8x1"])
+@pytest.mark.parametrize("mode", ["default", "persistent", "on16", "split"])
 @pytest.mark.parametrize("G", [5, 3, 6, 7, 16])
 def test_group_sizes_that_do_not_divide_32(G, mode):
     # e.g. 40 query heads over 8 KV heads (G = 5): a wave holds floor(32 / G) whole positions and its last
-    # rows are dead; the register-staged shapes ("8x1") hand such shapes to the ring kernel.  Also G = 16
-    # (64 query heads over 4 KV heads), which only the ring kernels take.
-    if mode in ("persistent", "8x1"):
-        os.environ["KUN_PREFILL_SHAPE"] = mode
+    # rows are dead.  Also G = 16 (64 query heads over 4 KV heads).
+    if mode == "persistent":
+        kun.kun_set_option("KUN_PREFILL_SHAPE", mode)
     B = 64 if G == 6 else 16
     sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=128, B=B, dtype="bf16")
     sets = ([(3000, 40)], [(5000, 200), (17, 3)], [(1500, 64), (64, 64), (9000, 5)]) if mode == "split" else \

@@ -18,7 +18,7 @@ TOL = 2e-2
 def _announce(request):
     print(f"\n[gpu-case] {request.node.nodeid}", flush=True)
     yield
-    os.environ.pop("KUN_DECODE_PART", None)
+    kun.kun_set_option("KUN_DECODE_PART", None)
 
 
 def status_of(fn, *a):
@@ -76,7 +76,7 @@ def test_regions_grow_move_their_tail_without_a_copy_and_shrink():
 
 
 def test_decode_over_a_pool_that_grows_in_place_and_gives_the_memory_back():
-    os.environ["KUN_DECODE_PART"] = "256"         # partitions depend on lengths only: bit-identical outputs
+    kun.kun_set_option("KUN_DECODE_PART", "256")         # partitions depend on lengths only: bit-identical outputs
     sh = synth.SHAPE_8B
     bb = sh.block_bytes
     kv = kun.kun_vmm_region_create(1 << 30)

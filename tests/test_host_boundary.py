@@ -200,3 +200,20 @@ def test_header_and_host_entry_points_from_plain_c(tmp_path):
                     "-Wl,-rpath," + libdir], check=True, capture_output=True, text=True)
     run = subprocess.run([exe], capture_output=True, text=True, timeout=60)
     assert run.returncode == 0 and "c abi ok" in run.stdout, run.stdout + run.stderr
+
+
+def test_vmm_region_bookkeeping_survives_driver_failures(tmp_path):
+    # kun_vmm_region_move_tail is all or nothing, and when the driver also refuses the undoing both
+    # regions still list exactly what is mapped: the bookkeeping template behind the entry points, run
+    # on the host against a driver that fails the n-th call (tests/vmm_bookkeeping_test.cpp)
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no g++")
+    exe = str(tmp_path / "vmm_bookkeeping_test")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-Wall", "-Wextra", "-Werror", "-I",
+                    os.path.join(ROOT, "paper_2412_18169_amd", "csrc"),
+                    os.path.join(ROOT, "tests", "vmm_bookkeeping_test.cpp"), "-o", exe],
+                   check=True, capture_output=True, text=True)
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0 and "vmm bookkeeping ok" in run.stdout, run.stdout + run.stderr

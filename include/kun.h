@@ -67,7 +67,8 @@ typedef enum {
     KUN_ERR_WORKSPACE = -6,       /* workspace missing, misaligned or smaller than required     */
     KUN_ERR_HIP = -7,             /* a HIP launch failed                                        */
     KUN_ERR_UNSUPPORTED = -8,     /* shape or dtype outside the supported set                   */
-    KUN_ERR_OVERLAP = -9          /* a new range overlaps one already in the pool               */
+    KUN_ERR_OVERLAP = -9,         /* a new range overlaps one already in the pool               */
+    KUN_ERR_SCRATCH_LIMIT = -10   /* the call needs more than the library's fixed scratch array */
 } kun_status;
 
 #define KUN_MAX_RANGES 16
@@ -180,6 +181,22 @@ KUN_API int kun_paged_decode(kun_kv_pool* pool, const void* q, void* out, const 
                      int max_blocks, const int32_t* ctx_len, int S, int num_q_heads, float scale,
                      int64_t total_ctx_upper_bound, void* workspace, size_t workspace_bytes,
                      void* stream);
+
+/* kun_paged_decode for callers that cannot allocate a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same operation, arguments, kernels and results,
+ * but the split-K records go to a fixed array of KUN_STATIC_SCRATCH_BYTES inside the library's device
+ * image -- every GPU the library is used on holds its own copy until the process ends -- and the call
+ * allocates and frees nothing.  KUN_ERR_SCRATCH_LIMIT if
+ * kun_decode_workspace_bytes(pool, S, num_q_heads, total_ctx_upper_bound) exceeds that size (nothing
+ * is launched then); pass a tight bound, since 0 sizes for a full pool.  All calls on one GPU share
+ * the one array: calls that overlap in time on the same GPU (two streams, two host threads) race;
+ * calls in sequence on one stream are safe, nothing is carried over from one call to the next.  The
+ * first call on a device looks the array's address up (hipGetSymbolAddress); make it outside any
+ * stream capture. */
+#define KUN_STATIC_SCRATCH_BYTES (32u << 20)
+KUN_API int kun_paged_decode_static(kun_kv_pool* pool, const void* q, void* out, const int32_t* block_table,
+                            int max_blocks, const int32_t* ctx_len, int S, int num_q_heads, float scale,
+                            int64_t total_ctx_upper_bound, void* stream);
 
 /* ---- chunked prefill ----------------------------------------------------------------------- */
 

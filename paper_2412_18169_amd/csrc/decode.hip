@@ -18,6 +18,8 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "kun_internal.h"
 
 namespace {
@@ -851,3 +853,51 @@ int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* bloc
 
 }  // namespace
 
+// ---------------------------------------------------------------------------------------------
+// Decode without a caller-provided workspace, for callers that cannot allocate one (code under HIP
+// graph capture, tight serving loops, harnesses that forbid allocation): the split-K records live in
+// a fixed array in the library's own device image.  Every GPU the library runs on holds its own copy
+// of the array, at its own address, until the process ends.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[KUN_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];     // device address of `scratch` on each device, looked up once
+
+// Device address of the current device's copy of `scratch` (the array's name is only a host-side
+// stand-in: host code always goes through this pointer).
+int static_scratch(void** out) {
+    int dev = 0;
+    const hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { kun_note_hip_error("hipGetDevice", e); return KUN_ERR_HIP; }
+    if (dev < 0 || dev >= kMaxDevices) return KUN_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        const hipError_t e2 = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+        if (e2 != hipSuccess || !ptr) { kun_note_hip_error("hipGetSymbolAddress", e2); return KUN_ERR_HIP; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return KUN_OK;
+}
+
+}  // namespace
+
+extern "C" int kun_paged_decode_static(kun_kv_pool* p, const void* q, void* out, const int32_t* block_table,
+                                       int max_blocks, const int32_t* ctx_len, int S, int Hq, float scale,
+                                       int64_t ub, void* stream) {
+    if (!decode_shape_ok(p, S, Hq)) return KUN_ERR_INVALID_ARG;
+    if (S == 0) return KUN_OK;
+    const size_t need = kun_decode_workspace_bytes(p, S, Hq, ub);
+    if (need == 0) return KUN_ERR_INVALID_ARG;
+    if (need > (size_t)KUN_STATIC_SCRATCH_BYTES) return KUN_ERR_SCRATCH_LIMIT;
+    void* ptr = nullptr;
+    const int st = static_scratch(&ptr);
+    if (st != KUN_OK) return st;
+    return decode_enqueue(p, q, out, block_table, max_blocks, ctx_len, S, Hq, scale, ub, ptr,
+                          (size_t)KUN_STATIC_SCRATCH_BYTES, stream);
+}

@@ -87,6 +87,7 @@ const char* kun_status_string(int st) {
         case KUN_ERR_HIP: return "KUN_ERR_HIP";
         case KUN_ERR_UNSUPPORTED: return "KUN_ERR_UNSUPPORTED";
         case KUN_ERR_OVERLAP: return "KUN_ERR_OVERLAP";
+        case KUN_ERR_SCRATCH_LIMIT: return "KUN_ERR_SCRATCH_LIMIT";
         default: return "KUN_ERR_UNKNOWN";
     }
 }

@@ -202,6 +202,26 @@ def test_header_and_host_entry_points_from_plain_c(tmp_path):
     assert run.returncode == 0 and "c abi ok" in run.stdout, run.stdout + run.stderr
 
 
+def test_static_scratch_decode_refuses_what_does_not_fit_before_touching_the_device():
+    # The entry point for callers that cannot allocate keeps its split-K records in a fixed array of
+    # KUN_STATIC_SCRATCH_BYTES; a call that needs more is refused on the host (no HIP call is made, so
+    # this runs without a GPU) with a status of its own.
+    p = make_pool(200 << 30)                       # 200 GB of fake addresses
+    need = kun.kun_decode_workspace_bytes(p, 4096, 32, 0)
+    assert need > kun.KUN_STATIC_SCRATCH_BYTES
+    with pytest.raises(kun.KunError) as e:
+        kun.kun_paged_decode_static(p, BASE, BASE, BASE, 8, BASE, 4096, 32, 0.1, 0, stream=0)
+    assert e.value.status == -10 and "SCRATCH_LIMIT" in str(e.value)
+    text = open(os.path.join(ROOT, "include", "kun.h")).read()
+    assert re.search(r"#define KUN_STATIC_SCRATCH_BYTES \(32u << 20\)", text) and kun.KUN_STATIC_SCRATCH_BYTES == 32 << 20
+    # bad shapes are still argument errors, and an empty batch is a no-op
+    with pytest.raises(kun.KunError) as e:
+        kun.kun_paged_decode_static(p, BASE, BASE, BASE, 8, BASE, 4, 33, 0.1, 0, stream=0)
+    assert e.value.status == -1
+    kun.kun_paged_decode_static(p, BASE, BASE, BASE, 8, BASE, 0, 32, 0.1, 0, stream=0)
+    kun.kun_kv_pool_destroy(p)
+
+
 def test_vmm_region_bookkeeping_survives_driver_failures(tmp_path):
     # kun_vmm_region_move_tail is all or nothing, and when the driver also refuses the undoing both
     # regions still list exactly what is mapped: the bookkeeping template behind the entry points, run

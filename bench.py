@@ -249,7 +249,7 @@ def cost_model_report(sh, reps=10):
         total = int(sum(cs))
         q = torch.cat([dw.q_pre[int(dw.q_start_host[i]):int(dw.q_start_host[i + 1])] for i in ids]).contiguous()
         o = torch.empty_like(q)
-        need = kun.kun_prefill_workspace_bytes(dw.pool, len(ids), sh.Hq, total)
+        need = kun.kun_prefill_workspace_bytes(dw.pool, len(ids), sh.Hq, total, table.shape[1])
         ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dw.dev)
 
         def call():

@@ -201,9 +201,10 @@ KUN_API int kun_paged_decode_static(kun_kv_pool* pool, const void* q, void* out,
 /* ---- chunked prefill ----------------------------------------------------------------------- */
 
 /* Bytes of device workspace kun_paged_prefill_chunk needs for n_chunks chunks holding
- * total_new_tokens query rows in total. */
+ * total_new_tokens query rows in total, with a block table of max_blocks entries per chunk (the
+ * workspace holds, among other things, the resolved address of every block a chunk can name). */
 KUN_API size_t kun_prefill_workspace_bytes(const kun_kv_pool* pool, int n_chunks, int num_q_heads,
-                                   int total_new_tokens);
+                                   int total_new_tokens, int max_blocks);
 
 /* Attention for n_chunks prefill chunks (Section 4.3, Eq. 1: chunk j of a request has c new tokens
  * after p prior tokens; it attends to the p prior tokens and causally to itself, diagonal

@@ -38,6 +38,7 @@ bool apply_option(KunOptions& o, const char* name, const char* value) {
         if (unset || !strcmp(value, "default")) o.prefill_shape = 0;
         else if (!strcmp(value, "persistent")) o.prefill_shape = 1;
         else if (!strcmp(value, "ring")) o.prefill_shape = 2;
+        else if (!strcmp(value, "ring-persistent")) o.prefill_shape = 3;
         else return false;
     } else {
         return false;

@@ -23,6 +23,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <type_traits>
+
 #include "kun_internal.h"
 
 namespace {
@@ -59,6 +61,9 @@ struct PrefillArgs {
     const int2* split_info;   // workspace, NULL when the launch cannot need it: per item (split | nsplit << 16, slot)
     const int4* desc;         // workspace: two int4 per list entry, (chunk, position tile, prior tokens, first query row)
                               // and (chunk tokens, first key tile, key tiles, partial-result slot or -1), for the ring kernels
+    const unsigned long long* page_addr;   // workspace: [chunk][16-token tile of the request] device address of the tile of
+                                           // KV head 0 (block resolution done once per tile, by the plan launch)
+    int tiles_per_row;        // entries per chunk in page_addr: max_blocks * (block_size / 16)
     int4* split_items;        // workspace: (chunk, position tile, nsplit, first slot) of every split item
     int32_t* n_split_items;   // workspace
     float* part_o;            // workspace: [slot, kvh, 256 rows, 128] unnormalised outputs of a key range
@@ -102,7 +107,35 @@ constexpr int kMaxSplit = 16;           // key ranges per item at most
 constexpr int kMinTilesPerSplit = 8;    // ... of at least this many 64-key tiles each
 constexpr int kSplitRows = 256;         // rows of a workgroup of the kernels that can split (8 waves x 32)
 
-__global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_t* __restrict__ q_start,
+// Block resolution for the whole launch, once per 16-token tile instead of once per (tile, query tile,
+// kv head): entry (chunk i, tile t) = address of tile t % (B / 16) of block table[i][t / (B / 16)], KV
+// head 0.  Entries past a chunk's context are not written (their table entries may hold anything).
+__device__ void resolve_tiles(const KunRanges& rt, const int32_t* __restrict__ q_start,
+                              const int32_t* __restrict__ prior, const int32_t* __restrict__ table, int n_chunks,
+                              int max_blocks, int sub_shift, unsigned block_bytes,
+                              unsigned long long* __restrict__ page_addr, int first_wg, int n_wgs) {
+    const int tiles_per_row = max_blocks << sub_shift;
+    const long long total = (long long)n_chunks * tiles_per_row;
+    for (long long e = (long long)(blockIdx.x - first_wg) * blockDim.x + threadIdx.x; e < total;
+         e += (long long)n_wgs * blockDim.x) {
+        const int ch = (int)(e / tiles_per_row), t = (int)(e % tiles_per_row);
+        const int ctx = prior[ch] + q_start[ch + 1] - q_start[ch];
+        if (t * kBlock >= ctx || q_start[ch + 1] == q_start[ch]) continue;
+        const int id = table[(size_t)ch * max_blocks + (t >> sub_shift)];
+        page_addr[e] = (unsigned long long)kun_block_addr(rt, id, block_bytes) +
+                       (unsigned)(t & ((1 << sub_shift) - 1)) * 8192u;
+    }
+}
+
+struct ResolveArgs {
+    KunRanges rt;
+    const int32_t* table;
+    unsigned long long* page_addr;
+    int max_blocks, sub_shift, n_wgs;
+    unsigned block_bytes;
+};
+
+__global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const ResolveArgs ra, const int32_t* __restrict__ q_start,
                                                                   const int32_t* __restrict__ prior, int n_chunks,
                                                                   int pos_per_tile, int max_items,
                                                                   int32_t* __restrict__ n_items,
@@ -113,6 +146,11 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
                                                                   int4* __restrict__ split_items,
                                                                   int32_t* __restrict__ n_split_items,
                                                                   int4* __restrict__ desc) {
+    if (blockIdx.x > 0) {      // workgroups 1 .. n_wgs resolve the blocks; workgroup 0 makes the work list
+        resolve_tiles(ra.rt, q_start, prior, ra.table, n_chunks, ra.max_blocks, ra.sub_shift, ra.block_bytes,
+                      ra.page_addr, 1, ra.n_wgs);
+        return;
+    }
     // everything a workgroup needs to know about list entry i, so that it starts with one lookup
     auto write_desc = [&](int i, int2 it, int2 si) {
         const int qs = q_start[it.x], c = q_start[it.x + 1] - qs, p = prior[it.x];
@@ -248,253 +286,6 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
     for (int i = tid; i < n_out_s; i += kPlanThreads) write_desc(i, items[i], split_info[i]);
 }
 
-// Staging of one 64-key tile (4 KV blocks): K rows XOR-swizzled by 16-byte chunk, V^T pages as stored.
-template <int NT>
-struct TileRegs {
-    uint4 k[1024 / NT];
-    uint4 v[1024 / NT];
-};
-
-template <int G, int NW, int NQ>
-__global__ __launch_bounds__(64 * NW) void prefill_kernel(const PrefillArgs a) {
-    constexpr int NT = 64 * NW;                // threads
-    constexpr int LOADS = 1024 / NT;           // 16-byte K (and V) loads per thread per tile
-    constexpr int ROWS_W = 32 * NQ;            // rows per wave
-    constexpr int ROWS = NW * ROWS_W;          // rows per workgroup
-    constexpr int POS = ROWS / G;              // query positions per workgroup
-    constexpr int POS_W = ROWS_W / G;          // query positions per wave
-    static_assert(ROWS_W % G == 0, "a wave must hold whole positions");
-
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][2][kBlocksPerTile * 4096];   // [stage][K|V]
-
-    const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
-    if (item >= *a.n_items) return;
-    const int2 it2 = a.items[item];
-    const int chunk = it2.x, qt = it2.y;
-    const int p = a.prior[chunk];
-    const int qs = a.q_start[chunk];
-    const int c = a.q_start[chunk + 1] - qs;
-    const int ctx = p + c;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n = lane & 31, jh = lane >> 5;
-    const int pos0 = qt * POS;                         // first position of the workgroup (chunk-local)
-    const int wpos0 = pos0 + wave * POS_W;             // first position of the wave
-
-    const int32_t* trow = a.table + (size_t)chunk * a.max_blocks;
-    const int nblk_ctx = (ctx + kBlock - 1) / kBlock;
-    const int wg_vis_max = p + min(pos0 + POS, c) - 1; // last key the workgroup needs
-    const int n_tiles = wg_vis_max / BN + 1;
-
-    // Block ids this wave stages: LOADS per tile.  One VGPR holds them for TPB tiles (lane
-    // LOADS * t + i = tile batch_first + t, load i); the next batch is fetched half a batch early.
-    constexpr int TPB = 64 / LOADS;
-    auto load_ids = [&](int batch) -> int {
-        const int t = batch * TPB + lane / LOADS, i = lane % LOADS;
-        const int lb = t * kBlocksPerTile + ((wave * 64 + i * NT) >> 8);
-        return (lb < nblk_ctx) ? trow[lb >> a.sub_shift] : 0;
-    };
-    int ids_cur = load_ids(0), ids_nxt = 0;
-
-    auto issue = [&](int kt, TileRegs<NT>& t) {
-        const int rel = kt % TPB;
-        if (rel == 0 && kt > 0) ids_cur = ids_nxt;
-        if (rel == TPB / 2 && (kt / TPB + 1) * TPB < n_tiles) ids_nxt = load_ids(kt / TPB + 1);
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int idx = tid + i * NT;
-            const int lb = kt * kBlocksPerTile + ((wave * 64 + i * NT) >> 8);   // logical block; uniform inside a wave
-            const int w = idx & 255;
-            uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-            if (lb < nblk_ctx) {
-                const int id = __builtin_amdgcn_readlane(ids_cur, rel * LOADS + i);
-                const char* page = kun_block_addr(a.rt, id, a.block_bytes) + (size_t)kvh * a.page_bytes +
-                                   (size_t)(lb & ((1 << a.sub_shift) - 1)) * 8192;
-                kv = *(const uint4*)(page + w * 16);
-                vv = *(const uint4*)(page + 4096 + w * 16);
-            }
-            t.k[i] = kv;
-            t.v[i] = vv;
-        }
-    };
-    auto commit = [&](int kt, int stage, TileRegs<NT>& t) {
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int idx = tid + i * NT;
-            const int b = idx >> 8, w = idx & 255;
-            uint4 vv = t.v[i];
-            // V^T: this thread holds dim w/2, tokens 8 (w%2) .. +8 of the block; slots past the context
-            // may hold anything (0 * NaN = NaN), so zero them
-            const int t0 = (kt * kBlocksPerTile + b) * kBlock + (w & 1) * 8;
-            if (t0 + 8 > ctx) {
-                unsigned x[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (t0 + e >= ctx) x[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                vv = make_uint4(x[0], x[1], x[2], x[3]);
-            }
-            const int r = w >> 4, ch = w & 15;
-            *(uint4*)(&lds[stage][0][b * 4096 + r * 256 + ((ch ^ r) * 16)]) = t.k[i];
-            // V^T rows are 32 B: swap the halves of every second group of 8 dims so that the 16 lanes of
-            // an A-operand read (dims n, n+1, ..) touch 16 different 16-byte bank groups
-            *(uint4*)(&lds[stage][1][b * 4096 + ((w ^ ((w >> 4) & 1)) * 16)]) = vv;
-        }
-    };
-
-    TileRegs<NT> treg;
-    issue(0, treg);
-
-    // ---- Q as the B operand: q[nq][ks] = Q[row][16 ks + 8 jh .. +8] ---------------------------
-    Frag qf[NQ][8];
-    int vis[NQ];                                       // last visible key of the lane's row
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        const int row = wave * ROWS_W + nq * 32 + n;
-        int pos = pos0 + row / G;
-        const int g = row % G;
-        if (pos >= c) pos = c - 1;
-        vis[nq] = p + pos;
-        const char* qrow = (const char*)a.q + (((size_t)(qs + pos)) * a.Hq + kvh * G + g) * (D * 2);
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[nq][ks].u = *(const uint4*)(qrow + (2 * ks + jh) * 16);
-    }
-    // q must have landed before the loop: a wait for it inside the loop would also wait for the
-    // tile loads issued just before
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[nq][ks].v));
-    const int wave_vis_max = p + min(wpos0 + POS_W, c) - 1;   // last key any row of the wave sees
-    const int wave_vis_min = p + min(wpos0, c - 1);           // last key the wave's first row sees
-
-    f32x16 o[NQ][4];
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[nq][dt][i] = 0.f;
-    float m[NQ], l[NQ];                                // m in scaled (log2) units
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) { m[nq] = -INFINITY; l[nq] = 0.f; }
-
-    // A-operand addressing of K: S^T tile row n -> key 16 (n/16) + 8 ((n/4)%2) + 4 ((n/8)%2) + n%4
-    const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);   // key inside a 32-key sub-tile
-    const int krow_blk = krow >> 4, krow_in = krow & 15;
-
-    commit(0, 0, treg);
-    __syncthreads();
-
-    for (int kt = 0; kt < n_tiles; ++kt) {
-        const int stage = kt & 1;
-        if (kt + 1 < n_tiles) issue(kt + 1, treg);
-
-#pragma unroll
-        for (int st = 0; st < BN / 32; ++st) {
-            const int key0 = kt * BN + st * 32;                // first key of the sub-tile
-            if (key0 > wave_vis_max) continue;                 // nothing visible for this wave
-            // ---- S^T = K Q^T -------------------------------------------------------------------
-            f32x16 s[NQ];
-#pragma unroll
-            for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[nq][i] = 0.f;
-            const unsigned char* kbase = &lds[stage][0][(st * 2 + krow_blk) * 4096 + krow_in * 256];
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                Frag kf;
-                kf.u = *(const uint4*)(kbase + (((2 * ks + jh) ^ krow_in) * 16));
-#pragma unroll
-                for (int nq = 0; nq < NQ; ++nq)
-                    s[nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[nq][ks].v, s[nq], 0, 0, 0);
-            }
-            // ---- online softmax; register i <-> key key0 + 16 (i/8) + 8 jh + i%8 ---------------
-            const bool need_mask = (key0 + 31 > wave_vis_min);
-            Frag pb[NQ][2];
-#pragma unroll
-            for (int nq = 0; nq < NQ; ++nq) {
-                if (need_mask) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int key = key0 + 16 * (i >> 3) + 8 * jh + (i & 7);
-                        if (key > vis[nq]) s[nq][i] = -INFINITY;
-                    }
-                }
-                float mx = s[nq][0];
-#pragma unroll
-                for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[nq][i]);
-                {   // both lane halves hold keys of the same row: exchange the maxima
-                    auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-                    mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-                }
-                // The reference maximum only moves when the true one outgrows it by 2^kLazy: p stays
-                // below 2^kLazy (exact in fp32 and in bf16's exponent range) and o, l are rescaled rarely.
-                // mn is finite: key 0 is visible to every row and is in the first sub-tile.
-                const float mxs = mx * a.scale_log2;
-                const float mn = (mxs > m[nq] + kLazy) ? mxs : m[nq];
-                const float alpha = __builtin_amdgcn_exp2f(m[nq] - mn);
-                float ps = 0.f;
-                f32x2 pr[8];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float pv = __builtin_amdgcn_exp2f(fmaf(s[nq][i], a.scale_log2, -mn));
-                    ps += pv;
-                    pr[i >> 1][i & 1] = pv;
-                }
-                l[nq] = l[nq] * alpha + ps;
-                m[nq] = mn;
-                union { bf16x2 h[8]; uint4 u[2]; } cv;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) cv.h[i] = __builtin_convertvector(pr[i], bf16x2);
-                pb[nq][0].u = cv.u[0];
-                pb[nq][1].u = cv.u[1];
-                if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-                    for (int dt = 0; dt < 4; ++dt) o[nq][dt] *= alpha;
-                }
-            }
-            // ---- O^T += V^T P^T ------------------------------------------------------------------
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const unsigned char* vbase = &lds[stage][1][(st * 2 + h) * 4096 + n * 32 + ((jh ^ ((n >> 3) & 1)) * 16)];
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    Frag vf;
-                    vf.u = *(const uint4*)(vbase + dt * 1024);
-#pragma unroll
-                    for (int nq = 0; nq < NQ; ++nq)
-                        o[nq][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pb[nq][h].v, o[nq][dt], 0, 0, 0);
-                }
-            }
-        }
-        // the other stage was last read in the previous iteration, which every wave has left
-        if (kt + 1 < n_tiles) commit(kt + 1, stage ^ 1, treg);
-        __syncthreads();
-    }
-
-    // ---- normalise and store: lane (row n, half jh) holds dims 32 dt + 8 (i/4) + 4 jh + i%4 -------
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        const float lt = l[nq] + __shfl_xor(l[nq], 32);
-        const float inv = 1.0f / lt;
-        const int row = wave * ROWS_W + nq * 32 + n;
-        const int pos = pos0 + row / G;
-        const int g = row % G;
-        if (pos < c) {
-            char* orow = (char*)a.out + (((size_t)(qs + pos)) * a.Hq + kvh * G + g) * (D * 2);
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    const int dim = 32 * dt + 8 * i4 + 4 * jh;
-                    union { bf16x2 h[2]; uint2 u; } w;
-                    w.h[0] = __builtin_convertvector((f32x2){o[nq][dt][4 * i4 + 0] * inv, o[nq][dt][4 * i4 + 1] * inv}, bf16x2);
-                    w.h[1] = __builtin_convertvector((f32x2){o[nq][dt][4 * i4 + 2] * inv, o[nq][dt][4 * i4 + 3] * inv}, bf16x2);
-                    *(uint2*)(orow + dim * 2) = w.u;
-                }
-        }
-    }
-}
-
 // ---------------------------------------------------------------------------------------------
 // Ring variant (default): 8 waves x 32 rows, 64-key tiles in a 4-stage LDS ring filled by direct
 // global->LDS loads (no registers, no LDS stores), three tiles in flight, ONE barrier per tile.
@@ -513,24 +304,20 @@ __global__ __launch_bounds__(64 * NW) void prefill_kernel(const PrefillArgs a) {
 // ---------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(1))) const void* kun_gptr;
 typedef __attribute__((address_space(3))) void* kun_lptr;
+typedef const __attribute__((address_space(4))) unsigned long long* kun_caddr;   // constant address space: scalar loads
 
 // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt = bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 #define KUN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
-// NW = 8 (default) or 12: a 4-stage ring, tiles three ahead, one workgroup per compute unit.
-// NW = 4: a 2-stage ring (64 KiB), tiles one ahead, so that two workgroups share a compute unit and one
-// runs its tile loop while the other is between work items.
-template <int G, int NW, bool PERSIST>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 12 ? 3 : 2, NW == 12 ? 3 : 2)))
+template <int G, bool PERSIST>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void prefill_ring_kernel(const PrefillArgs a) {
-    constexpr int NSTAGERS = NW < 8 ? NW : 8;          // waves that issue the tile loads
-    constexpr int LOADS = 16 / NSTAGERS;               // page tiles per stager wave and tile: 2 loads per lane each (K, V^T)
-    constexpr int NT = 64 * NSTAGERS;
+    constexpr int NW = 8, LOADS = 2;                   // 8 waves; page tiles per wave and tile: 2 loads per lane each (K, V^T)
     // Row r of the workgroup is (position r / G, head r % G).  The workgroup holds POS whole positions;
     // when G does not divide its row count the last rows (1 of 256 for G = 3, 5; 4 for G = 6, 7) are
     // dead, and a wave's 32 rows may begin and end in the middle of a position.
     constexpr int ROWS_W = 32, ROWS = NW * ROWS_W, POS = ROWS / G, LIVE = POS * G;
-    constexpr int NSTAGE = NW < 8 ? 2 : 4, AHEAD = NSTAGE - 1;
+    constexpr int NSTAGE = 4, AHEAD = NSTAGE - 1;
     static_assert(G >= 1 && G <= 16, "1 to 8 or 16 query heads per KV head");
 
     __shared__ __attribute__((aligned(16))) unsigned char ring[NSTAGE][2 * kBlocksPerTile * 4096];
@@ -563,84 +350,49 @@ void prefill_ring_kernel(const PrefillArgs a) {
     const int wpos0 = pos0 + wave * ROWS_W / G;                                  // first position the wave touches
     const int wpos_end = pos0 + min((wave * ROWS_W + ROWS_W - 1) / G, POS - 1) + 1;  // one past its last live one
 
-    const int32_t* trow = a.table + (size_t)chunk * a.max_blocks;
-    const int nblk_ctx = (ctx + kBlock - 1) / kBlock;
+    // Addresses of the 16-token page tiles of this chunk's request, resolved by the plan launch; read
+    // with scalar loads (wave-uniform index), one tile ahead of the loads that use them.
+    const kun_caddr arow = (kun_caddr)(a.page_addr + (size_t)chunk * a.tiles_per_row);
+    const int ntile_ctx = (ctx + kBlock - 1) / kBlock;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
-    constexpr int TPB = 64 / LOADS;
-    // Page addresses this wave stages, resolved a batch at a time in the vector lanes (lane LOADS*t + i
-    // = tile batch_first + t, load i): one table gather and one walk over the range table per TPB
-    // tiles, instead of dependent scalar loads in front of every tile's loads.
-    // The gather (load_ids) and the walk (resolve_pages) are separate steps: the ids of the next batch
-    // are requested half a batch early and used only when the batch begins, so that the wait for them
-    // -- a vmcnt(0), since the compiler does not see the tile loads -- finds them long landed.
-    auto tile_of_lane = [&](int batch) -> int {
-        const int t = kt0 + batch * TPB + lane / LOADS, i = lane % LOADS;
-        const int lb = t * kBlocksPerTile + (NSTAGERS == 8 ? (wave >> 2) + 2 * i : i);
-        return lb >= nblk_ctx ? nblk_ctx - 1 : lb;      // past the context: re-read the last tile
-    };
-    auto load_ids = [&](int batch) -> int { return trow[tile_of_lane(batch) >> a.sub_shift]; };
-    auto resolve_pages = [&](int batch, int id) -> unsigned long long {
-        const int lb = tile_of_lane(batch);
-        int first = a.rt.first[0];
-        unsigned long long base = (unsigned long long)a.rt.base[0];
-        for (int r = 1; r < a.rt.n; ++r) {
-            const bool in = id >= a.rt.first[r];
-            first = in ? a.rt.first[r] : first;
-            base = in ? (unsigned long long)a.rt.base[r] : base;
-        }
-        return base + (unsigned long long)(id - first) * a.block_bytes + (unsigned long long)kvh * a.page_bytes +
-               (unsigned)(lb & ((1 << a.sub_shift) - 1)) * 8192u;
-    };
-    unsigned long long pages_cur = resolve_pages(0, load_ids(0));
-    int ids_nxt = 0;
-
-    // per-lane source offsets inside a page for the slot this lane fills (slot = (wave % 4) * 64 + lane)
+    // per-lane source offsets inside a block for the slot this lane fills (slot = (wave % 4) * 64 + lane),
+    // the kv head's page included
     const int slot = (wave & 3) * 64 + lane;
-    const unsigned k_src = (slot >> 4) * 256 + (((slot & 15) ^ (slot >> 4)) * 16);
-    const unsigned v_src = 4096 + ((slot ^ ((slot >> 4) & 1)) * 16);
+    const unsigned k_src = kvh * a.page_bytes + (slot >> 4) * 256 + (((slot & 15) ^ (slot >> 4)) * 16);
+    const unsigned v_src = kvh * a.page_bytes + 4096 + ((slot ^ ((slot >> 4) & 1)) * 16);
 
     // The loads are issued through inline asm: the compiler then neither tracks them nor adds waits of
-    // its own in front of LDS reads; completion is tracked by hand with vmcnt (see `iteration`).
-    auto dma16 = [&](const char* src, unsigned lds_addr) {
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr) : "memory", "m0");
+    // its own in front of LDS reads; completion is tracked by hand with vmcnt (see the tile loop).
+    // Address = 64-bit scalar tile address + 32-bit lane offset; LDS destination = M0 + 16 * lane.
+    auto dma16 = [&](unsigned long long page, unsigned off, unsigned lds_addr) {
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(page), "s"(lds_addr)
+                     : "memory", "m0");
     };
     const unsigned ring_addr = (unsigned)(size_t)(kun_lptr)&ring[0][0];
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    // A tile is 4 loads per lane of a stager wave: issue_begin picks the tile's addresses, issue_part(j)
-    // sends load j (block j/2, K or V^T).
-    unsigned iss_stage = 0;
-    const char* iss_page[LOADS];
-    auto issue_begin = [&](int j) {                    // j: tile index relative to kt0
-        const int rel = j % TPB;
-        if (rel == 0 && j > 0) pages_cur = resolve_pages(j / TPB, ids_nxt);
-        if (rel == TPB / 2 && (j / TPB + 1) * TPB < nt) ids_nxt = load_ids(j / TPB + 1);
-        iss_stage = ring_addr + (j % NSTAGE) * (2 * kBlocksPerTile * 4096) + (wave_u & 3) * 1024;
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const unsigned lo = __builtin_amdgcn_readlane((unsigned)pages_cur, rel * LOADS + i);
-            const unsigned hi = __builtin_amdgcn_readlane((unsigned)(pages_cur >> 32), rel * LOADS + i);
-            iss_page[i] = (const char*)(((unsigned long long)hi << 32) | lo);
-        }
+    // A tile is 4 loads per lane: this wave brings quarter (wave % 4) of K and of V^T of the tile's page
+    // tiles wave / 4 and wave / 4 + 2.  Tiles past the context re-read the last one (every lane issues the
+    // same number of loads per tile, so the wait counts stay exact).
+    auto tile_addr = [&](int j, int i) -> unsigned long long {     // j: tile index relative to kt0
+        const int lb = (kt0 + j) * kBlocksPerTile + (wave_u >> 2) + 2 * i;
+        return arow[lb < ntile_ctx ? lb : ntile_ctx - 1];
     };
-    auto issue_part = [&](int j) {
-        const int i = j >> 1;
-        const unsigned dk = iss_stage + (NSTAGERS == 8 ? (wave_u >> 2) + 2 * i : i) * 4096;
-        if (j & 1) dma16(iss_page[i] + v_src, dk + V_OFF);
-        else dma16(iss_page[i] + k_src, dk);
-    };
+    unsigned long long pg0 = tile_addr(0, 0), pg1 = tile_addr(0, 1);      // of the tile to be issued next
     auto issue = [&](int j) {
-        issue_begin(j);
-#pragma unroll
-        for (int j = 0; j < 2 * LOADS; ++j) issue_part(j);
+        const unsigned st = ring_addr + (j % NSTAGE) * (2 * kBlocksPerTile * 4096) + (wave_u & 3) * 1024;
+        const unsigned d0 = st + (wave_u >> 2) * 4096, d1 = d0 + 2 * 4096;
+        dma16(pg0, k_src, d0);
+        dma16(pg0, v_src, d0 + V_OFF);
+        dma16(pg1, k_src, d1);
+        dma16(pg1, v_src, d1 + V_OFF);
+        pg0 = tile_addr(j + 1, 0);
+        pg1 = tile_addr(j + 1, 1);
     };
 
     // ---- prologue: the first AHEAD tiles go in flight, then Q ------------------------------------
-    const bool stager = wave_u < NSTAGERS;
-    if (stager) {
-        issue(0);
-        if (AHEAD > 1 && nt > 1) issue(1);
-        if (AHEAD > 2 && nt > 2) issue(2);
-    }
+    issue(0);
+    if (nt > 1) issue(1);
+    if (nt > 2) issue(2);
 
     Frag qf[8];
     int pos = pos0 + (wave * ROWS_W + n) / G;
@@ -859,7 +611,7 @@ void prefill_ring_kernel(const PrefillArgs a) {
         else if (AHEAD > 1 && j + 1 < nt) KUN_WAIT_VMCNT(LPT);
         else KUN_WAIT_VMCNT(0);
         __builtin_amdgcn_s_barrier();                  // tile j complete in LDS; everybody has left tile j-1
-        if (stager && j + AHEAD < nt) issue(j + AHEAD);          // into the stage tile j-1 used
+        if (j + AHEAD < nt) issue(j + AHEAD);                    // into the stage tile j-1 used
         compute(kt0 + j, &ring[j % NSTAGE][0]);
     }
 
@@ -867,6 +619,359 @@ void prefill_ring_kernel(const PrefillArgs a) {
     if (part_slot >= 0) {
         // one key range of a split item: unnormalised O^T ([dim][row]: a register's 32 lanes are 32
         // consecutive rows) and the rows' (m, l), for prefill_merge_kernel
+        const size_t wg_rec = (size_t)part_slot * a.Hkv + kvh;
+        float* po = a.part_o + wg_rec * (D * kSplitRows) + wave * ROWS_W + n;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) po[(32 * dt + 8 * (i >> 2) + 4 * jh + (i & 3)) * kSplitRows] = o[dt][i];
+        if (jh == 0) *(float2*)(a.part_ml + (wg_rec * kSplitRows + wave * ROWS_W + n) * 2) = make_float2(m, lt);
+    }
+    const float inv = 1.0f / lt;
+    if (live_row && part_slot < 0) {
+        char* orow = (char*)a.out + (((size_t)(qs + pos)) * a.Hq + kvh * G + g_head) * (D * 2);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int dim = 32 * dt + 8 * i4 + 4 * jh;
+                union { bf16x2 h[2]; uint2 u; } w;
+                w.h[0] = __builtin_convertvector((f32x2){o[dt][4 * i4 + 0] * inv, o[dt][4 * i4 + 1] * inv}, bf16x2);
+                w.h[1] = __builtin_convertvector((f32x2){o[dt][4 * i4 + 2] * inv, o[dt][4 * i4 + 3] * inv}, bf16x2);
+                *(uint2*)(orow + dim * 2) = w.u;
+            }
+    }
+    if (!PERSIST) return;
+    }
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Ping-pong variant: the same tiling (8 waves x 32 rows, 64-key tiles, 4-stage LDS ring, direct
+// global->LDS loads), but the two waves that share a SIMD (wave w and w + 4) run half a tile apart:
+// while one is in its matrix phase M(t) = { O^T += V^T(t-1) P^T(t-1) ; S^T(t) = K(t) Q^T }, 32 MFMAs
+// back to back, the other is in its vector phase V(t') = softmax numerators of tile t', page-address
+// loads and the tile loads.  Two waves that both follow one barrier per tile stay in lock step and
+// leave the matrix pipe idle whenever both are in their softmax; here every phase boundary is an
+// s_barrier of the whole workgroup and group 1 (waves 4-7) starts one barrier late:
+//
+//   barrier      b0      b1      b2      b3      b4            b(2nt)   b(2nt+1)
+//   waves 0-3    | M(0)  | V(0)  | M(1)  | V(1)  | M(2) ...    | M(nt)  |
+//   waves 4-7    |       | M(0)  | V(0)  | M(1)  | V(1) ...    | V(nt-1)| M(nt)
+//
+// Ring stage t % 4 holds what M(t) reads: K of tile t and V^T of tile t-1 (loaded together, four loads
+// per lane as before), so a stage is busy for one and a half tile times; stage t + 4 is requested right
+// after b(2t + 2), when M(t) of both groups is over (waves 4-7 at the start of their V(t), waves 0-3 at
+// the start of their M(t + 1)), and has to be complete at b(2t + 7): two and a half tile times.
+// Inside M every MFMA is paired with one LDS fragment read that is used four MFMAs later
+// (sched_group_barrier); the first four fragments are requested in the vector phase before, so the
+// phase runs at the rate of the matrix pipe from its first instruction.
+// ---------------------------------------------------------------------------------------------
+template <int G, bool PERSIST>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void prefill_pp_kernel(const PrefillArgs a) {
+    constexpr int NW = 8, ROWS_W = 32, ROWS = NW * ROWS_W, POS = ROWS / G, LIVE = POS * G;
+    constexpr int NSTAGE = 4, STAGE_BYTES = 2 * kBlocksPerTile * 4096, V_OFF = kBlocksPerTile * 4096;
+    constexpr int kAhead = 4;                          // distance, in MFMAs, between a fragment read and its use
+    constexpr int kPre = 4;                            // V^T fragments requested before the matrix phase begins
+    static_assert(G >= 1 && G <= 16, "1 to 8 or 16 query heads per KV head");
+
+    __shared__ __attribute__((aligned(16))) unsigned char ring[NSTAGE][STAGE_BYTES];
+    __shared__ int s_next;
+    int wi = blockIdx.x;
+    for (;;) {
+    if (PERSIST) {
+        __syncthreads();                               // everybody has left the previous item's ring
+        if (threadIdx.x == 0) s_next = atomicAdd(&a.next_item[blockIdx.x & 7], 1) * 8 + (blockIdx.x & 7);
+        __syncthreads();
+        wi = s_next;
+    }
+    wi = __builtin_amdgcn_readfirstlane(wi);
+    const int item = wi / a.Hkv, kvh = wi % a.Hkv;
+    if (PERSIST && item >= *a.n_items) return;
+    const int n_items = PERSIST ? item + 1 : *a.n_items;
+    const int4 d0 = a.desc[2 * item], d1 = a.desc[2 * item + 1];
+    if (item >= n_items) return;
+    const int chunk = d0.x, qt = d0.y, p = d0.z, qs = d0.w, c = d1.x;
+    const int kt0 = d1.y, nt = d1.z, part_slot = d1.w;
+    const int ctx = p + c;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, jh = lane >> 5;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int group = wave_u >> 2;                     // 0: waves 0-3, 1: waves 4-7 (one barrier behind)
+    const int pos0 = qt * POS;
+    const int wpos0 = pos0 + wave_u * ROWS_W / G;
+    const int wpos_end = pos0 + min((wave_u * ROWS_W + ROWS_W - 1) / G, POS - 1) + 1;
+
+    const kun_caddr arow = (kun_caddr)(a.page_addr + (size_t)chunk * a.tiles_per_row);
+    const int ntile_ctx = (ctx + kBlock - 1) / kBlock;
+    const int slot = (wave & 3) * 64 + lane;
+    const unsigned k_src = kvh * a.page_bytes + (slot >> 4) * 256 + (((slot & 15) ^ (slot >> 4)) * 16);
+    const unsigned v_src = kvh * a.page_bytes + 4096 + ((slot ^ ((slot >> 4) & 1)) * 16);
+    auto dma16 = [&](unsigned long long page, unsigned off, unsigned lds_addr) {
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(page), "s"(lds_addr)
+                     : "memory", "m0");
+    };
+    const unsigned ring_addr = (unsigned)(size_t)(kun_lptr)&ring[0][0];
+    // page tiles wave / 4 and wave / 4 + 2 of key tile j (relative to kt0), clamped into the context
+    auto tile_addr = [&](int j, int i) -> unsigned long long {
+        int lb = (kt0 + j) * kBlocksPerTile + (wave_u >> 2) + 2 * i;
+        lb = lb < 0 ? 0 : lb;
+        return arow[lb < ntile_ctx ? lb : ntile_ctx - 1];
+    };
+    // Stage t: K of key tile t and V^T of key tile t - 1.  kpg: page tiles of key tile `next_t`, vpg: of
+    // key tile next_t - 1 (what the next call of issue() sends).
+    unsigned long long kpg0 = tile_addr(0, 0), kpg1 = tile_addr(0, 1), vpg0 = kpg0, vpg1 = kpg1;
+    int next_t = 0;                                    // next stage to request
+    auto issue = [&]() {
+        const unsigned st = ring_addr + (next_t % NSTAGE) * STAGE_BYTES + (wave_u & 3) * 1024;
+        const unsigned dst0 = st + (wave_u >> 2) * 4096, dst1 = dst0 + 2 * 4096;
+        dma16(kpg0, k_src, dst0);
+        dma16(vpg0, v_src, dst0 + V_OFF);
+        dma16(kpg1, k_src, dst1);
+        dma16(vpg1, v_src, dst1 + V_OFF);
+        vpg0 = kpg0;
+        vpg1 = kpg1;
+        ++next_t;
+        kpg0 = tile_addr(next_t, 0);
+        kpg1 = tile_addr(next_t, 1);
+    };
+    // stages 0 .. nt exist; `landed(t)`: this lane's loads of stage t are complete (stages are requested
+    // in order, four loads each, so everything but the 4 * (next_t - 1 - t) youngest loads is waited for)
+    auto landed = [&](int t) {
+        const int younger = next_t - 1 - t;
+        if (younger >= 3) KUN_WAIT_VMCNT(12);
+        else if (younger == 2) KUN_WAIT_VMCNT(8);
+        else if (younger == 1) KUN_WAIT_VMCNT(4);
+        else KUN_WAIT_VMCNT(0);
+    };
+
+    // ---- prologue ---------------------------------------------------------------------------------
+    issue();
+    if (nt >= 1) issue();
+    if (nt >= 2) issue();
+    if (nt >= 3) issue();
+
+    Frag qf[8];
+    int pos = pos0 + (wave * ROWS_W + n) / G;
+    const int g_head = (wave * ROWS_W + n) % G;
+    const bool live_row = wave * ROWS_W + n < LIVE && pos < c;
+    if (!live_row) pos = min(wpos0, c - 1);
+    const int vis = p + pos;
+    {
+        const char* qrow = (const char*)a.q + (((size_t)(qs + pos)) * a.Hq + kvh * G + g_head) * (D * 2);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[ks].u = *(const uint4*)(qrow + (2 * ks + jh) * 16);
+    }
+    const int wave_vis_min = p + min(wpos0, c - 1);
+
+    f32x16 o[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+    float m = -INFINITY, l = 0.f;                      // m in log2 units
+
+    const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
+    const int krow_blk = krow >> 4, krow_in = krow & 15;
+    const unsigned k_lane = krow_blk * 4096 + krow_in * 256;
+    const unsigned v_lane = V_OFF + n * 32 + ((jh ^ ((n >> 3) & 1)) * 16);
+    const float sl2 = a.scale_log2;
+
+    f32x16 sa, sb;                                     // S^T of the tile between its M and its V phase
+    union { bf16x2 h[16]; uint4 u[4]; } cv;            // P^T of the tile between its V and the next M phase
+
+    // ---- matrix phase of stage t: PV of key tile t - 1, QK^T of key tile t --------------------------
+    // The first kPre V^T fragments were requested in the vector phase before (prefetch_v), so the first
+    // MFMAs find their operands; from then on every MFMA is followed by the read of a fragment that is
+    // used kPre MFMAs later.
+    Frag vpre[kPre];
+    auto prefetch_v = [&](int t) {
+        const unsigned char* vbase = &ring[t % NSTAGE][0] + v_lane;
+#pragma unroll
+        for (int i = 0; i < kPre; ++i) vpre[i].u = *(const uint4*)(vbase + (i >> 2) * 4096 + (i & 3) * 1024);
+    };
+    auto mphase = [&](int t, auto do_pv, auto do_qk) {
+        const unsigned char* stage = &ring[t % NSTAGE][0];
+        const unsigned char* vbase = stage + v_lane;
+        const unsigned char* kbase = stage + k_lane;
+        constexpr bool PV = decltype(do_pv)::value, QK = decltype(do_qk)::value;
+        Frag vf[16], ka[8], kb[8];
+        if (PV) {
+#pragma unroll
+            for (int i = kPre; i < 16; ++i) vf[i].u = *(const uint4*)(vbase + (i >> 2) * 4096 + (i & 3) * 1024);
+        }
+        if (QK) {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const unsigned off = ((2 * ks + jh) ^ krow_in) * 16;
+                ka[ks].u = *(const uint4*)(kbase + off);
+                kb[ks].u = *(const uint4*)(kbase + 8192 + off);
+            }
+        }
+        if (PV) {
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                Frag pb;
+                pb.u = cv.u[h];
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(4 * h + dt < kPre ? vpre[(4 * h + dt) % kPre].v : vf[4 * h + dt].v,
+                                                                    pb.v, o[dt], 0, 0, 0);
+            }
+        }
+        if (QK) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { sa[i] = 0.f; sb[i] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks].v, qf[ks].v, sa, 0, 0, 0);
+                sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[ks].v, qf[ks].v, sb, 0, 0, 0);
+            }
+        }
+        constexpr int NM = (PV ? 16 : 0) + (QK ? 16 : 0);       // MFMAs
+        constexpr int NR = (PV ? 16 - kPre : 0) + (QK ? 16 : 0);   // fragment reads inside the phase
+        constexpr int LEAD = PV ? 0 : kAhead;                   // reads in front of the first MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, LEAD, 0);
+#pragma unroll
+        for (int i = 0; i < NR - LEAD; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, NM - (NR - LEAD), 0);
+    };
+    // PV of the context's last key tile when it holds keys past the context (once per item at most)
+    auto pv_tail = [&](int t) {
+        const unsigned char* vbase = &ring[t % NSTAGE][0] + v_lane;
+        const int key0 = (kt0 + t - 1) * BN;
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            Frag pb;
+            pb.u = cv.u[h];
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                Frag vf;
+                vf.u = *(const uint4*)(vbase + h * 4096 + dt * 1024);
+                const int t0 = key0 + 16 * h + 8 * jh;
+                unsigned x[4] = {vf.u.x, vf.u.y, vf.u.z, vf.u.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (t0 + e >= ctx) x[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                vf.u = make_uint4(x[0], x[1], x[2], x[3]);
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pb.v, o[dt], 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- vector phase of key tile t: softmax numerators of sa / sb -> cv, row sums, lazy maximum ----
+    // Accumulator register i of sa <-> key 64 kt + 16 (i / 8) + 8 jh + i % 8, of sb 32 keys further on.
+    auto numerators = [&](float mref) -> float {
+        float ps0 = 0.f, ps1 = 0.f, ps2 = 0.f, ps3 = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[i], sl2, -mref)), p1 = __builtin_amdgcn_exp2f(fmaf(sa[i + 1], sl2, -mref));
+            const float p2 = __builtin_amdgcn_exp2f(fmaf(sb[i], sl2, -mref)), p3 = __builtin_amdgcn_exp2f(fmaf(sb[i + 1], sl2, -mref));
+            ps0 += p0; ps1 += p1; ps2 += p2; ps3 += p3;
+            cv.h[i >> 1] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+            cv.h[8 + (i >> 1)] = __builtin_convertvector((f32x2){p2, p3}, bf16x2);
+        }
+        return (ps0 + ps1) + (ps2 + ps3);
+    };
+    auto vphase = [&](int t) {
+        const int kt = kt0 + t;
+        const bool plain = t > 0 && kt * BN + BN - 1 <= wave_vis_min;   // every key visible to every row, m is set
+        float pt = 0.f;
+        bool redo = !plain;
+        if (plain) {
+            // No maximum is taken: the row sums, needed anyway, show when a row has outgrown its reference
+            // (32 numerators summing above 32 * 2^kLazy, or an overflow of exp2); only then the slow way.
+            pt = numerators(m);
+            redo = __builtin_amdgcn_ballot_w64(!(pt <= kSumCap)) != 0;
+        }
+        if (redo) {
+            if (!plain) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int key = kt * BN + 16 * (i >> 3) + 8 * jh + (i & 7);
+                    if (key > vis) sa[i] = -INFINITY;
+                    if (key + 32 > vis) sb[i] = -INFINITY;
+                }
+            }
+            float mx = fmaxf(sa[0], sb[0]);            // the chain's first read of both accumulators
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = max3(mx, sa[i], sb[i]);
+            {
+                auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            }
+            const float mxs = mx * sl2;
+            const bool grow = mxs > m + kLazy;         // also true for a first visible key (m = -inf)
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                const float mn = grow ? mxs : m;
+                const float alpha = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mn);   // o and l are 0 then
+                l *= alpha;
+                m = mn;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) o[dt] *= alpha;
+            }
+            // a row that has seen no key yet still has m = -inf and only -inf scores: keep inf - inf out
+            pt = numerators(m == -INFINITY ? 0.f : m);
+        }
+        l += pt;
+    };
+
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks].v));   // q landed before the loop
+
+    const bool last_is_tail = (kt0 + nt) * BN > ctx;   // the item's last key tile reaches past the context
+    using T1 = std::integral_constant<bool, true>;
+    using T0 = std::integral_constant<bool, false>;
+
+    // Both groups walk the same list of phases; group 1 does it one barrier later.  Stage s is complete
+    // (every wave's part landed) at barrier b(2s - 1), one phase before group 0's M(s), so that both
+    // groups can prefetch from it in the vector phase before their M(s).
+    if (group == 1) {
+        landed(1 < nt ? 1 : nt);                       // its parts of stages 0 and 1
+        __builtin_amdgcn_s_barrier();                  // b0
+    }
+    landed(0);
+    __builtin_amdgcn_s_barrier();                      // b0 (group 0) / b1 (group 1)
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(1);
+    mphase(0, T0{}, T1{});
+    __builtin_amdgcn_s_setprio(0);
+    if (group == 0) landed(1 < nt ? 1 : nt);           // group 0 arrives at b1: stage 1
+    // vector phase of key tile t between two barriers; requests stage t + 4 when `more`
+    auto vector_part = [&](int t, bool prefetch) {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();                  // b(2t + 1) / b(2t + 2)
+        __builtin_amdgcn_sched_barrier(0);
+        // M(t) of both groups is over once group 1 is here; group 0 learns that one barrier later
+        if (group == 1 && next_t <= nt) issue();       // stage t + 4
+        if (prefetch) prefetch_v(t + 1);
+        vphase(t);
+        if (group == 1) landed(min(t + 2, nt));        // group 1 arrives at b(2t + 3): stage t + 2
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();                  // b(2t + 2) / b(2t + 3)
+        __builtin_amdgcn_sched_barrier(0);
+        if (group == 0 && next_t <= nt) issue();       // stage t + 4
+    };
+    for (int t = 0; t + 1 < nt; ++t) {
+        vector_part(t, true);
+        __builtin_amdgcn_s_setprio(1);
+        mphase(t + 1, T1{}, T1{});
+        __builtin_amdgcn_s_setprio(0);
+        if (group == 0) landed(min(t + 2, nt));        // group 0 arrives at b(2t + 3): stage t + 2
+    }
+    // the last key tile: its vector phase, then M(nt) = its PV
+    vector_part(nt - 1, !last_is_tail);
+    if (last_is_tail) pv_tail(nt);
+    else mphase(nt, T1{}, T0{});
+    if (group == 0) __builtin_amdgcn_s_barrier();      // b(2 nt + 1)
+    KUN_WAIT_VMCNT(0);                                 // (nothing is in flight any more; no load may outlive the item)
+
+    const float lt = l + __shfl_xor(l, 32);
+    if (part_slot >= 0) {
         const size_t wg_rec = (size_t)part_slot * a.Hkv + kvh;
         float* po = a.part_o + wg_rec * (D * kSplitRows) + wave * ROWS_W + n;
 #pragma unroll
@@ -963,21 +1068,7 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(const int32_t* __rest
 
 bool mfma_shape(const kun_kv_pool* p) { return p->dtype == KUN_BF16 && p->d == 128; }
 
-// Tile shape: NW waves x 32 NQ rows per workgroup; `ring` selects prefill_ring_kernel, otherwise the
-// register-staged prefill_kernel runs; `persistent`: a fixed number of workgroups fetch the work
-// items (ring kernel, 8 waves) instead of one workgroup per item.  Default: ring kernel, 8 waves, one
-// workgroup per item (measured equal to one fetching workgroup per compute unit).
-// KUN_PREFILL_SHAPE picks another one for sweeps and cross-checks: "persistent" (one fetching
-// workgroup per compute unit), "12x1" (ring kernel, 12 waves), "4x1ring" (ring kernel, 4 waves, two
-// workgroups per compute unit), "8x1", "4x2", "4x1" (register-staged).
-struct TileShape { int nw, nq; bool ring, persistent; };
-
-TileShape choose_shape() {
-    if (kun_options().prefill_shape == 1) return TileShape{8, 1, true, true};
-    return TileShape{8, 1, true, false};
-}
-
-// compute units of the current device (one persistent workgroup each)
+// compute units of the current device (one fetching workgroup each)
 int device_compute_units() {
     int dev = 0, n = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 256;
@@ -985,54 +1076,45 @@ int device_compute_units() {
     return n;
 }
 
-int rows_per_wg(TileShape t) { return t.nw * 32 * t.nq; }
-int pos_per_wg(TileShape t, int G) { return rows_per_wg(t) / G; }    // whole query positions per workgroup
-
 template <int G>
-void launch_ring(const PrefillArgs& a, dim3 grid, bool persistent, hipStream_t st) {
-    if (persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, true>), grid, dim3(512), 0, st, a);
-    else hipLaunchKernelGGL((prefill_ring_kernel<G, 8, false>), grid, dim3(512), 0, st, a);
+void launch_tiles(const PrefillArgs& a, dim3 grid, bool persistent, bool ring, hipStream_t st) {
+    if (ring) {
+        if (persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((prefill_ring_kernel<G, false>), grid, dim3(512), 0, st, a);
+    } else {
+        if (persistent) hipLaunchKernelGGL((prefill_pp_kernel<G, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((prefill_pp_kernel<G, false>), grid, dim3(512), 0, st, a);
+    }
 }
 
-bool prefill_shape_ok(const kun_kv_pool* p, int n_chunks, int Hq, int total_new) {
-    return p && n_chunks >= 0 && Hq > 0 && Hq % p->Hkv == 0 && total_new >= 0;
+bool prefill_shape_ok(const kun_kv_pool* p, int n_chunks, int Hq, int total_new, int max_blocks) {
+    return p && n_chunks >= 0 && Hq > 0 && Hq % p->Hkv == 0 && total_new >= 0 && max_blocks >= 0;
 }
 
-template <int G>
-void launch_prefill(const PrefillArgs& a, dim3 grid, TileShape t, hipStream_t st) {
-    if (t.persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, true>), grid, dim3(512), 0, st, a);
-    else if (t.nw == 12) hipLaunchKernelGGL((prefill_ring_kernel<G, 12, false>), grid, dim3(768), 0, st, a);
-    else if (t.nw == 8 && t.ring) hipLaunchKernelGGL((prefill_ring_kernel<G, 8, false>), grid, dim3(512), 0, st, a);
-    else if (t.nw == 4 && t.ring) hipLaunchKernelGGL((prefill_ring_kernel<G, 4, false>), grid, dim3(256), 0, st, a);
-    else if (t.nw == 8) hipLaunchKernelGGL((prefill_kernel<G, 8, 1>), grid, dim3(512), 0, st, a);
-    else if (t.nq == 2) hipLaunchKernelGGL((prefill_kernel<G, 4, 2>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((prefill_kernel<G, 4, 1>), grid, dim3(256), 0, st, a);
-}
-
-}  // namespace
-
-namespace {
+int sub_shift_of(const kun_kv_pool* p) { return p->B == 128 ? 3 : p->B == 64 ? 2 : p->B == 32 ? 1 : 0; }
 
 // Workspace of the MFMA path: header (256 B: n_items, the 8 fetch counters at +64, n_split_items at
-// +128), the item list, and -- only when the launch is small enough to be split -- the per-item
-// split records, the list of split items and the partial results of the key ranges.
+// +128), the item list and its descriptors, the resolved address of every 16-token page tile of every
+// chunk, and -- only when the launch is small enough to be split -- the per-item split records, the
+// list of split items and the partial results of the key ranges.
 struct PrefillLayout {
     bool may_split;
     int max_items, cap_entries;
-    size_t off_items, off_desc, off_split_info, off_split_items, off_part_ml, off_part_o, total;
+    size_t off_items, off_desc, off_pages, off_split_info, off_split_items, off_part_ml, off_part_o, total;
 };
 
-PrefillLayout prefill_layout(const kun_kv_pool* p, int n_chunks, int Hq, int total_new_tokens, int pos_per_tile) {
+PrefillLayout prefill_layout(const kun_kv_pool* p, int n_chunks, int Hq, int total_new_tokens, int max_blocks) {
     PrefillLayout lay;
     const int G = Hq / p->Hkv;
-    const int pos_ring = kSplitRows / G;                   // positions per workgroup of the kernels that can split
+    const int pos_per_tile = kSplitRows / G;               // whole query positions per workgroup
     // at least total / pos items exist, so a launch with that many workgroups or more is never split
-    lay.may_split = (int64_t)(total_new_tokens / pos_ring) * p->Hkv < kSplitTarget;
+    lay.may_split = (int64_t)(total_new_tokens / pos_per_tile) * p->Hkv < kSplitTarget;
     lay.max_items = total_new_tokens / pos_per_tile + n_chunks;
     lay.cap_entries = lay.may_split ? 2 * lay.max_items + kSplitTarget / p->Hkv + 1 : lay.max_items;
     size_t o = 256;
     lay.off_items = o;        o += align256(sizeof(int2) * (size_t)lay.cap_entries);
     lay.off_desc = o;         o += align256(sizeof(int4) * 2 * (size_t)lay.cap_entries);
+    lay.off_pages = o;        o += align256(sizeof(unsigned long long) * (size_t)n_chunks * ((size_t)max_blocks << sub_shift_of(p)));
     lay.off_split_info = o;   if (lay.may_split) o += align256(sizeof(int2) * (size_t)lay.cap_entries);
     lay.off_split_items = o;  if (lay.may_split) o += align256(sizeof(int4) * (size_t)(kSplitTarget + 1));
     const size_t part_wgs = 2 * (size_t)kSplitTarget + p->Hkv;       // (key range, kv head) workgroups of split items
@@ -1044,30 +1126,31 @@ PrefillLayout prefill_layout(const kun_kv_pool* p, int n_chunks, int Hq, int tot
 
 }  // namespace
 
-extern "C" size_t kun_prefill_workspace_bytes(const kun_kv_pool* p, int n_chunks, int Hq, int total_new_tokens) {
-    if (!prefill_shape_ok(p, n_chunks, Hq, total_new_tokens)) return 0;
+extern "C" size_t kun_prefill_workspace_bytes(const kun_kv_pool* p, int n_chunks, int Hq, int total_new_tokens,
+                                              int max_blocks) {
+    if (!prefill_shape_ok(p, n_chunks, Hq, total_new_tokens, max_blocks)) return 0;
     if (!mfma_shape(p))                                    // rows as decode requests: two int32 per row + its plan
         return 256 + 2 * align256(sizeof(int32_t) * (size_t)total_new_tokens) +
                kun_attend_rows_workspace_bytes(total_new_tokens);
     const int G = Hq / p->Hkv;
     if (G < 1 || (G > 8 && G != 16)) return 0;
-    const int pos_min = 128 / G;                           // smallest tile of any variant (4 waves, NQ = 1)
-    return prefill_layout(p, n_chunks, Hq, total_new_tokens, pos_min).total;
+    return prefill_layout(p, n_chunks, Hq, total_new_tokens, max_blocks).total;
 }
 
 namespace {
 
-// max_workgroups == 0: the default shape (or what KUN_PREFILL_SHAPE asks for); otherwise that many
-// workgroups (rounded down to a multiple of 8, at least 8) of the ring kernel fetch the items.
+// max_workgroups == 0: one workgroup per work item (or, with the option "persistent", one fetching
+// workgroup per compute unit); otherwise that many workgroups (rounded down to a multiple of 8, at
+// least 8) fetch the items.
 int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_start, const int32_t* prior_len,
                     const int32_t* block_table, int max_blocks, int n_chunks, int Hq, int total_new_tokens,
                     float scale, int max_workgroups, void* workspace, size_t workspace_bytes, void* stream) {
-    if (!prefill_shape_ok(p, n_chunks, Hq, total_new_tokens) || max_workgroups < 0) return KUN_ERR_INVALID_ARG;
+    if (!prefill_shape_ok(p, n_chunks, Hq, total_new_tokens, max_blocks) || max_workgroups < 0) return KUN_ERR_INVALID_ARG;
     if (n_chunks == 0 || total_new_tokens == 0) return KUN_OK;
     if (!q || !out || !q_start || !prior_len || !block_table || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
     const int G = Hq / p->Hkv;
     if (G < 1 || (G > 8 && !(G == 16 && mfma_shape(p)))) return KUN_ERR_UNSUPPORTED;   // 16: the MFMA kernels only
-    const size_t need = kun_prefill_workspace_bytes(p, n_chunks, Hq, total_new_tokens);
+    const size_t need = kun_prefill_workspace_bytes(p, n_chunks, Hq, total_new_tokens, max_blocks);
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < need) return KUN_ERR_WORKSPACE;
     if (!mfma_shape(p)) {
         const size_t col = align256(sizeof(int32_t) * (size_t)total_new_tokens);
@@ -1081,14 +1164,11 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
                                        scale, (char*)workspace + 256 + 2 * col, st);
     }
 
-    TileShape shape = max_workgroups > 0 ? TileShape{8, 1, true, true} : choose_shape();
-    if (((G & (G - 1)) != 0 || G == 16) && !(shape.ring && shape.nw == 8))
-        shape = TileShape{8, 1, true, false};              // 3, 5, 6, 7, 16 heads per KV head: the 8-wave ring kernels only
-    const bool persistent = shape.persistent;
+    bool persistent = max_workgroups > 0 || kun_options().prefill_shape == 1 || kun_options().prefill_shape == 3;
     if (persistent && max_workgroups == 0) max_workgroups = device_compute_units();
-    const int pos_per_tile = pos_per_wg(shape, G);
-    const PrefillLayout lay = prefill_layout(p, n_chunks, Hq, total_new_tokens, pos_per_tile);
-    const bool can_split = lay.may_split && shape.ring && shape.nw == 8;     // the 8-wave ring kernels only
+    const int pos_per_tile = kSplitRows / G;
+    const PrefillLayout lay = prefill_layout(p, n_chunks, Hq, total_new_tokens, max_blocks);
+    const bool can_split = lay.may_split;
     char* ws = (char*)workspace;
     PrefillArgs a;
     a.rt = p->ranges;
@@ -1102,6 +1182,8 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     a.n_split_items = (int32_t*)ws + 32;
     a.items = (int2*)(ws + lay.off_items);
     a.desc = (const int4*)(ws + lay.off_desc);
+    a.page_addr = (const unsigned long long*)(ws + lay.off_pages);
+    a.tiles_per_row = max_blocks << sub_shift_of(p);
     a.split_info = can_split ? (const int2*)(ws + lay.off_split_info) : nullptr;
     a.split_items = (int4*)(ws + lay.off_split_items);
     a.part_ml = (float*)(ws + lay.off_part_ml);
@@ -1114,11 +1196,21 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     a.scale_log2 = scale * kLog2e;
     a.block_bytes = (unsigned)p->block_bytes;
     a.page_bytes = (unsigned)p->page_bytes;
-    a.sub_shift = p->B == 128 ? 3 : p->B == 64 ? 2 : p->B == 32 ? 1 : 0;
+    a.sub_shift = sub_shift_of(p);
     hipStream_t st = (hipStream_t)stream;
 
-    hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, q_start, prior_len, n_chunks,
-                       pos_per_tile, a.max_items, a.n_items, a.next_item, a.items, p->Hkv,
+    // one launch: workgroup 0 makes the work list, the others resolve the blocks of every chunk
+    ResolveArgs ra;
+    ra.rt = p->ranges;
+    ra.table = block_table;
+    ra.page_addr = (unsigned long long*)(ws + lay.off_pages);
+    ra.max_blocks = max_blocks;
+    ra.sub_shift = a.sub_shift;
+    ra.block_bytes = a.block_bytes;
+    const size_t n_entries = (size_t)n_chunks * (size_t)a.tiles_per_row;
+    ra.n_wgs = (int)((n_entries + kPlanThreads - 1) / kPlanThreads < 1024 ? (n_entries + kPlanThreads - 1) / kPlanThreads : 1024);
+    hipLaunchKernelGGL(prefill_plan_kernel, dim3(1 + ra.n_wgs), dim3(kPlanThreads), 0, st, ra, q_start, prior_len,
+                       n_chunks, pos_per_tile, a.max_items, a.n_items, a.next_item, a.items, p->Hkv,
                        can_split ? kSplitTarget : 0, lay.cap_entries, (int2*)(ws + lay.off_split_info), a.split_items,
                        a.n_split_items, (int4*)(ws + lay.off_desc));
     KUN_HIP_CHECK_LAUNCH();
@@ -1129,16 +1221,17 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
         wgs = (wgs + 7) & ~(size_t)7;                  // every residue class mod 8 needs a workgroup
     }
     const dim3 grid((unsigned)wgs);
+    const bool ring = kun_options().prefill_shape >= 2;     // the one-barrier-per-tile kernel (cross-check)
     switch (G) {
-        case 1: launch_prefill<1>(a, grid, shape, st); break;
-        case 2: launch_prefill<2>(a, grid, shape, st); break;
-        case 4: launch_prefill<4>(a, grid, shape, st); break;
-        case 8: launch_prefill<8>(a, grid, shape, st); break;
-        case 3: launch_ring<3>(a, grid, shape.persistent, st); break;
-        case 5: launch_ring<5>(a, grid, shape.persistent, st); break;
-        case 6: launch_ring<6>(a, grid, shape.persistent, st); break;
-        case 7: launch_ring<7>(a, grid, shape.persistent, st); break;
-        default: launch_ring<16>(a, grid, shape.persistent, st); break;
+        case 1: launch_tiles<1>(a, grid, persistent, ring, st); break;
+        case 2: launch_tiles<2>(a, grid, persistent, ring, st); break;
+        case 3: launch_tiles<3>(a, grid, persistent, ring, st); break;
+        case 4: launch_tiles<4>(a, grid, persistent, ring, st); break;
+        case 5: launch_tiles<5>(a, grid, persistent, ring, st); break;
+        case 6: launch_tiles<6>(a, grid, persistent, ring, st); break;
+        case 7: launch_tiles<7>(a, grid, persistent, ring, st); break;
+        case 8: launch_tiles<8>(a, grid, persistent, ring, st); break;
+        default: launch_tiles<16>(a, grid, persistent, ring, st); break;
     }
     KUN_HIP_CHECK_LAUNCH();
     if (can_split) {

@@ -96,7 +96,7 @@ def lib() -> ctypes.CDLL:
     L.kun_paged_decode.argtypes = [vp, vp, vp, vp, i32, vp, i32, i32, f32, i64, vp, sz, vp]
     L.kun_paged_decode_static.argtypes = [vp, vp, vp, vp, i32, vp, i32, i32, f32, i64, vp]
     L.kun_prefill_workspace_bytes.restype = sz
-    L.kun_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    L.kun_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     L.kun_paged_prefill_chunk.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]
     L.kun_paged_prefill_chunk_on.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, sz, vp]
     for name in SYMBOLS:
@@ -286,8 +286,10 @@ def kun_paged_decode_static(pool: int, q, out, block_table, max_blocks: int, ctx
                                          int(total_ctx_upper_bound), _stream(stream)), "kun_paged_decode_static")
 
 
-def kun_prefill_workspace_bytes(pool: int, n_chunks: int, num_q_heads: int, total_new_tokens: int) -> int:
-    return lib().kun_prefill_workspace_bytes(pool, int(n_chunks), int(num_q_heads), int(total_new_tokens))
+def kun_prefill_workspace_bytes(pool: int, n_chunks: int, num_q_heads: int, total_new_tokens: int,
+                                max_blocks: int) -> int:
+    return lib().kun_prefill_workspace_bytes(pool, int(n_chunks), int(num_q_heads), int(total_new_tokens),
+                                             int(max_blocks))
 
 
 def kun_paged_prefill_chunk(pool: int, q, out, q_start, prior_len, block_table, max_blocks: int,

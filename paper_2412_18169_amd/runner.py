@@ -87,7 +87,8 @@ class DeviceWorkload:
     def prefill(self, stream=None, max_workgroups: int = 0) -> torch.Tensor:
         """All prefill chunks; max_workgroups > 0 runs them on that many workgroups (mixed batches)."""
         sh = self.w.shape
-        need = kun.kun_prefill_workspace_bytes(self.pool, self.n_chunks, sh.Hq, self.total_new)
+        need = kun.kun_prefill_workspace_bytes(self.pool, self.n_chunks, sh.Hq, self.total_new,
+                                               self.pre_table.shape[1])
         if self._ws_pre is None or self._ws_pre.numel() < need:
             self._ws_pre = torch.empty(max(need, 256), dtype=torch.uint8, device=self.dev)
         if max_workgroups > 0:

@@ -10,6 +10,9 @@ of the batch / average duration of the decode call measured with HIP events on t
 the prefill rate, the per-part times and the oracle timed on the host cores are in the same line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {2,3,4,5}]
+
+Without --config the line describes configuration 5 (the largest one-GPU workload) and carries, under
+"others", the decode and prefill rates of configurations 3, 4 and 2 measured the same way.
 """
 import argparse
 import json
@@ -37,6 +40,8 @@ def parse():
     ap.add_argument("--q-heads", type=int, default=0,
                     help="query heads (default: the configuration's own); e.g. 40 over the 8 KV heads of cfg 2-4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the shorter runs of configurations 3, 4 and 2 that follow the default workload")
     ap.add_argument("--no-mixed", action="store_true",
                     help="skip the side-by-side prefill + decode measurement (keeps profiles to the K timed steps)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -65,23 +70,16 @@ def prefill_flops(w):
     return 4 * sh.d * sh.Hq * w.prefill_pairs
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
+def time_steps(cfg, args, block_size=0, q_heads=0):
+    """Builds configuration `cfg` on the device and times args.steps steps (after args.warmup untimed
+    ones).  A step = KV append of the step's new tokens + chunked prefill + decode on one stream, inputs
+    resident in HBM.  Returns (report, dw, dws): the per-part figures, the first DeviceWorkload (kept
+    for the follow-up measurements) and all of them (to close)."""
     import torch
     from paper_2412_18169_amd import kun, synth
     from paper_2412_18169_amd.runner import DeviceWorkload
-
-    kun.lib()   # fail loudly if the HIP library is missing
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    cfg = args.config or DEFAULT_CONFIG
     t_setup = time.time()
-    w = synth.config(cfg, args.block_size, args.q_heads)
+    w = synth.config(cfg, block_size, q_heads)
     sh = w.shape
     dw = DeviceWorkload(w, poison=(cfg != 5))
     torch.cuda.synchronize()
@@ -133,6 +131,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # HIP events on the stream the kernels are launched on (torch's current stream)
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -148,13 +147,11 @@ def main():
 
     dbytes = decode_bytes(w)
     gbps = dbytes / (t_dec * 1e-3) / 1e9
-    out = {
-        "metric": "paged_decode_hbm_bandwidth", "value": round(gbps, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype,
-        "data": "synthetic",
-        "config": {"workload": f"cfg{cfg}:{w.name}", "block_size": w.shape.B, "pools_alternated": len(dws), "decode_requests": w.S, "prefill_chunks": w.n_chunks if has_prefill else 0,
-                   "Hq": sh.Hq, "Hkv": sh.Hkv, "head_dim": sh.d, "block_size": sh.B,
+    rep = {
+        "ms_per_step": round(ms_per_step, 4), "dtype": sh.dtype,
+        "config": {"workload": f"cfg{cfg}:{w.name}", "block_size": w.shape.B, "pools_alternated": len(dws),
+                   "decode_requests": w.S, "prefill_chunks": w.n_chunks if has_prefill else 0,
+                   "Hq": sh.Hq, "Hkv": sh.Hkv, "head_dim": sh.d,
                    "pool_ranges": len(w.range_blocks), "pool_GB": round(w.num_blocks * sh.block_bytes / 1e9, 2),
                    "decode_kv_tokens": w.decode_kv_tokens, "seed": w.seed},
         "decode": {"ms": round(t_dec, 4), "ms_median": round(t_dec_med, 4), "algorithmic_bytes": dbytes,
@@ -162,17 +159,51 @@ def main():
                    "requests_per_s": round(w.S / (t_dec * 1e-3), 1),
                    "kv_tokens_per_s": round(w.decode_kv_tokens / (t_dec * 1e-3), 1)},
         "append": {"ms": round(t_app, 4), "tokens": T_new},
-        "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC_BYTES.get(cfg) if w.shape.B == 16 else None,
-                     "kernel": "decode_partial_mfma (timed with its plan and merge launches)"},
         "setup_s": round(t_setup, 1),
     }
     if has_prefill:
         fl = prefill_flops(w)
         tf = fl / (t_pre * 1e-3) / 1e12
-        out["prefill"] = {"ms": round(t_pre, 4), "flops": fl, "TFLOP_per_s": round(tf, 1),
+        rep["prefill"] = {"ms": round(t_pre, 4), "flops": fl, "TFLOP_per_s": round(tf, 1),
                           "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                           "new_tokens_per_s": round(dw.total_new / (t_pre * 1e-3), 1)}
+    return rep, dw, dws
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2412_18169_amd import kun
+
+    kun.lib()   # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    cfg = args.config or DEFAULT_CONFIG
+    rep, dw, dws = time_steps(cfg, args, args.block_size, args.q_heads)
+    w, sh = dw.w, dw.w.shape
+    has_prefill = "prefill" in rep
+    gbps = rep["decode"]["GB_per_s"]
+    traffic = TRAFFIC.get((cfg, sh.B, sh.Hq))
+    out = {
+        "metric": "paged_decode_hbm_bandwidth", "value": gbps, "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": rep["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype,
+        "data": "synthetic",
+        "config": rep["config"], "decode": rep["decode"], "append": rep["append"],
+        "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": traffic[0] if traffic else None,
+                     "traffic_source": traffic[1] if traffic else None,
+                     "kernel": "decode_partial_mfma (timed with the plan launch in front of it)"},
+        "setup_s": rep["setup_s"],
+    }
+    if has_prefill:
+        out["prefill"] = rep["prefill"]
 
     if has_prefill and not args.pmc_calibration and not args.no_mixed:
         out["mixed"] = mixed_batch(dw, args.steps)
@@ -188,6 +219,26 @@ def main():
             out["prefill_max_abs_err_vs_oracle"] = prefill_check(dw)
     for d in dws:
         d.close()
+    del dw, dws
+    torch.cuda.empty_cache()
+
+    # The other configurations the targets are quoted on, same number of steps each: the metric, value,
+    # roofline and config above stay those of the default workload.
+    if not args.config and not args.no_others and not args.pmc_calibration:
+        out["others"] = {}
+        for c in OTHER_CONFIGS:
+            r, d0, ds = time_steps(c, args, args.block_size, args.q_heads)
+            o = {"decode_ms": r["decode"]["ms"], "GB_per_s": r["decode"]["GB_per_s"],
+                 "frac": r["decode"]["frac_of_hbm_peak"], "decode_kv_tokens": r["config"]["decode_kv_tokens"],
+                 "ms_per_step": r["ms_per_step"]}
+            if "prefill" in r:
+                o.update({"prefill_ms": r["prefill"]["ms"], "TFLOP_per_s": r["prefill"]["TFLOP_per_s"],
+                          "prefill_frac": r["prefill"]["frac_of_mfma_peak"]})
+            out["others"][f"cfg{c}"] = o
+            for d in ds:
+                d.close()
+            del d0, ds
+            torch.cuda.empty_cache()
     print(json.dumps(out), flush=True)
 
 
@@ -426,7 +477,12 @@ def prefill_check(dw, rows_per_chunk=6):
 DEFAULT_CONFIG = 5
 PREFILL_SUPPORTED = True
 ORACLE_TOKENS_PER_S = 80000.0      # rough speed of the numpy oracle, only used to size its sample
-TRAFFIC_BYTES = {5: 17322737541}                 # per-launch HBM bytes from rocprofv3 --pmc runs (see profiles/)
+OTHER_CONFIGS = (3, 4, 2)          # reported under "others" after the default workload
+# HBM bytes per decode launch from rocprofv3 --pmc runs of an EARLIER session (not of this run), keyed by
+# (config, block size, query heads): (bytes, where the figure comes from).
+TRAFFIC = {(5, 16, 64): (17322737541, "profiles/bench_cfg5_70b_stage_kernels.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                                       "of decode_partial_mfma in an earlier session, 1.015 x the algorithmic bytes; "
+                                       "not measured in this run")}
 
 if __name__ == "__main__":
     main()

@@ -89,8 +89,10 @@ KUN_API const char* kun_last_hip_error(void);
  *   KUN_DECODE_WAVES   1, 2 or 4 waves per workgroup of the matrix-core decode kernel (default 4)
  *   KUN_DECODE_KERNEL  "generic": the vector-ALU decode kernel for every shape; "mfma": the default
  *   KUN_DECODE_MAP     "flat": item-major workgroup order; "xcd": the default XCD-aware order
+ *   KUN_DECODE_MERGE   "fold": partial results are merged inside the partial kernel; "kernel": by a launch
+ *                      of its own; "auto": by batch size (the default)
  *   KUN_PREFILL_SHAPE  "persistent": workgroups that fetch their work items, one per compute unit;
- *                      "ring": the earlier one-barrier-per-tile kernel (cross-check); "default" */
+ *                      "ring": the one-barrier-per-tile kernel (cross-check), "ring-persistent"; "default" */
 KUN_API int kun_set_option(const char* name, const char* value);
 
 /* ---- pool growth (Section 4.1: the KVCache region is extended at its tail with the memory of

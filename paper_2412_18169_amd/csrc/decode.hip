@@ -5,12 +5,16 @@
 //
 // Launch sequence (one stream, no host synchronisation):
 //   1. plan     -- one workgroup turns ctx_len[] into a list of work items (request, partition)
-//                  of `part_tokens` tokens each and a per-request index of its first item.
+//                  of `part_tokens` tokens each and a per-request index of its first item, and
+//                  clears the arrival counters.
 //   2. partial  -- one workgroup per (item, kv head): online softmax over the item's tokens for
 //                  the G query heads that share the kv head, K/V pages read exactly once.
-//                  Requests that fit one partition are normalised and written to `out` directly.
-//   3. merge    -- one workgroup per (request, kv head) with more than one partition:
-//                  o = sum_i acc_i e^(m_i - M) / sum_i l_i e^(m_i - M).
+//                  Requests that fit one partition are normalised and written to `out` directly;
+//                  otherwise the workgroup writes a partial record.
+//   3. merge    -- o = sum_i acc_i e^(m_i - M) / sum_i l_i e^(m_i - M), records in partition order.
+//                  Small batches: inside the partial kernel, by the LAST workgroup of a (request,
+//                  kv head) to arrive (one device-scope counter per pair).  Large batches: a launch
+//                  of its own, one workgroup group per (request, kv head) with several partitions.
 //
 // Two partial kernels: a generic one on the vector ALUs (any supported dtype/shape; used for
 // fp32) and an MFMA one for bf16 with head_dim 128, where the G query rows are padded to a
@@ -37,6 +41,7 @@ struct DecodeArgs {
     int32_t* n_items;        // workspace: number of work items (written by plan)
     int32_t* seq_first;      // workspace: [S + 1] first item of each request
     int4* items;             // workspace: (request, partition, the request's context length, record slot)
+    int32_t* arrived;        // workspace: [S, Hkv] partitions of a (request, kv head) whose records are written
     float* part_ml;          // workspace: [item, kvh, G, 2]  (m in log2 units, l)
     float* part_acc;         // workspace: [item, kvh, G, d]
     int max_blocks;
@@ -48,6 +53,7 @@ struct DecodeArgs {
     float scale_log2;        // softmax scale * log2(e)
     unsigned block_bytes, page_bytes;
     int xcd_map;             // MFMA kernel: the KV heads of a work item run on one XCD
+    int fold;                // the last workgroup of a (request, kv head) merges its records (else decode_merge_kernel does)
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -64,7 +70,9 @@ __global__ __launch_bounds__(1024) void decode_plan_kernel(const int32_t* __rest
                                                          int part_tokens, int max_items,
                                                          int32_t* __restrict__ n_items,
                                                          int32_t* __restrict__ seq_first,
-                                                         int4* __restrict__ items) {
+                                                         int4* __restrict__ items,
+                                                         int32_t* __restrict__ arrived, int n_arrived) {
+    for (int i = threadIdx.x; i < n_arrived; i += 1024) arrived[i] = 0;
     __shared__ int wave_tot[16], wave_full[16];
     __shared__ int carry_s, carry_full;
     __shared__ int bucket[kLenBuckets];
@@ -175,10 +183,57 @@ template <> struct Elem<bf16_t> {
     __device__ static void store(bf16_t* p, float x) { p->bits = f32_to_bf16_rne(x); }
 };
 
+// Stores and loads of partial records that are coherent across the whole device (they bypass what
+// the XCD-local L2 may hold of the line): relaxed atomic accesses at device scope.
+__device__ __forceinline__ void rec_store(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float rec_load(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// out[seq, heads of kvh] from the nparts partial records that start at record slot `first`: the records
+// are combined in partition order, two per step, whoever does it, so the result does not depend on
+// which workgroup merges or when.  Elements idx0, idx0 + stride, ... of the G x D outputs.
+template <typename T, int D, bool COHERENT>
+__device__ __forceinline__ void merge_records(const DecodeArgs& a, int first, int nparts, int kvh, int seq, int G,
+                                              int idx0, int stride) {
+    auto ld = [](const float* p) { return COHERENT ? rec_load(p) : *p; };
+    for (int idx = idx0; idx < G * D; idx += stride) {
+        const int g = idx / D, j = idx - g * D;
+        const size_t rec0 = (((size_t)first) * a.Hkv + kvh) * G + g, step = (size_t)a.Hkv * G;
+        float M = -INFINITY;
+        for (int p = 0; p < nparts; ++p) M = fmaxf(M, ld(&a.part_ml[(rec0 + p * step) * 2]));
+        float l = 0.f, acc = 0.f;
+        int p = 0;
+        for (; p + 1 < nparts; p += 2) {                   // two independent records per step
+            const size_t r0 = rec0 + p * step, r1 = r0 + step;
+            const float m0 = ld(&a.part_ml[r0 * 2]), m1 = ld(&a.part_ml[r1 * 2]);
+            const float l0 = ld(&a.part_ml[r0 * 2 + 1]), l1 = ld(&a.part_ml[r1 * 2 + 1]);
+            const float a0 = ld(&a.part_acc[r0 * D + j]), a1 = ld(&a.part_acc[r1 * D + j]);
+            const float f0 = exp2f(m0 - M), f1 = exp2f(m1 - M);
+            l += f0 * l0;
+            acc += f0 * a0;
+            l += f1 * l1;
+            acc += f1 * a1;
+        }
+        if (p < nparts) {
+            const size_t r0 = rec0 + p * step;
+            const float f0 = exp2f(ld(&a.part_ml[r0 * 2]) - M);
+            l += f0 * ld(&a.part_ml[r0 * 2 + 1]);
+            acc += f0 * ld(&a.part_acc[r0 * D + j]);
+        }
+        T* o = (T*)a.out + ((size_t)seq * a.Hkv * G + (size_t)kvh * G + g) * D + j;
+        Elem<T>::store(o, acc / l);
+    }
+}
+
 // Combine the per-wave partial results held in LDS and write either the final output row (request
-// with one partition) or the item's partial record.  sm_m/sm_l: [NW][G]; sm_acc: [NW][G][D].
+// with one partition) or the item's partial record; the workgroup that completes the records of its
+// (request, kv head) then merges them.  sm_m/sm_l: [NW][G]; sm_acc: [NW][G][D].  Called by every
+// thread of the workgroup.
 template <typename T, int D, int NW>
-__device__ __forceinline__ void finish_item(const DecodeArgs& a, int slot, int kvh, int seq, int nparts,
+__device__ __forceinline__ void finish_item(const DecodeArgs& a, int slot, int part, int kvh, int seq, int nparts,
                                             int G, const float* sm_m, const float* sm_l,
                                             const float* sm_acc) {
     for (int idx = threadIdx.x; idx < G * D; idx += blockDim.x) {
@@ -199,13 +254,37 @@ __device__ __forceinline__ void finish_item(const DecodeArgs& a, int slot, int k
             Elem<T>::store(o, acc / l);
         } else {
             const size_t rec = ((size_t)slot * a.Hkv + kvh) * G + g;
-            a.part_acc[rec * D + j] = acc;
-            if (j == 0) {
-                a.part_ml[rec * 2 + 0] = M;
-                a.part_ml[rec * 2 + 1] = l;
+            if (a.fold) {
+                rec_store(&a.part_acc[rec * D + j], acc);
+                if (j == 0) {
+                    rec_store(&a.part_ml[rec * 2 + 0], M);
+                    rec_store(&a.part_ml[rec * 2 + 1], l);
+                }
+            } else {
+                a.part_acc[rec * D + j] = acc;
+                if (j == 0) {
+                    a.part_ml[rec * 2 + 0] = M;
+                    a.part_ml[rec * 2 + 1] = l;
+                }
             }
         }
     }
+    if (nparts == 1 || !a.fold) return;                  // (not folding: decode_merge_kernel follows)
+    // The partitions of a request run on different XCDs, whose L2 caches do not see each other's
+    // lines.  A device-wide fence would write back and invalidate a whole L2 per workgroup (measured:
+    // the decode step took half as long again), so the records themselves go through device-coherent
+    // stores and loads instead (rec_store / rec_load): every thread waits until its stores are
+    // acknowledged, the workgroup meets at a barrier, and only then is its arrival counted; the
+    // workgroup that counts the last arrival reads every record of the pair coherently.
+    __shared__ int s_last;
+    __builtin_amdgcn_s_waitcnt(0);                       // vmcnt(0): this thread's record stores are done
+    __syncthreads();
+    if (threadIdx.x == 0)
+        s_last = __hip_atomic_fetch_add(&a.arrived[(size_t)seq * a.Hkv + kvh], 1, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT) == nparts - 1;
+    __syncthreads();
+    if (!s_last) return;
+    merge_records<T, D, true>(a, slot - part, nparts, kvh, seq, G, threadIdx.x, blockDim.x);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -337,7 +416,7 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
         for (int i = 0; i < DPL; ++i) sm_acc[(wave * G + g) * D + lane + 64 * i] = acc[g][i];
     }
     __syncthreads();
-    finish_item<T, D, NW>(a, it4.w, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
+    finish_item<T, D, NW>(a, it4.w, part, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -571,15 +650,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
             for (int i = 0; i < 4; ++i) sm_acc[(wave * G + n) * D + s * 16 + 4 * j + i] = o[s][i];
     }
     __syncthreads();
-    finish_item<bf16_t, D, NW>(a, it4.w, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
+    finish_item<bf16_t, D, NW>(a, it4.w, part, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
 }
 
 // ---------------------------------------------------------------------------------------------
-// 3. merge: one workgroup per (request, kv head); only requests with more than one partition
+// 3. merge as a launch of its own (large batches): workgroups per (request, kv head); only requests
+//    with more than one partition have work
 // ---------------------------------------------------------------------------------------------
 constexpr int kMergeSlices = 4;      // workgroups per (request, kv head): the chain of dependent loads per thread is short
-template <typename T>
-__global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a, int D) {
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a) {
     const int slice = blockIdx.x % kMergeSlices;
     const int seq = blockIdx.x / kMergeSlices / a.Hkv, kvh = blockIdx.x / kMergeSlices % a.Hkv;
     const int L = a.ctx_len[seq];
@@ -587,34 +667,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a, i
     if (nparts <= 1) return;
     const int first = a.seq_first[seq];
     if (first + nparts > a.max_items) return;   // the caller's bound on sum(ctx_len) was too small
-    const int G = a.G;
-    for (int idx = slice * 256 + threadIdx.x; idx < G * D; idx += kMergeSlices * 256) {
-        const int g = idx / D, j = idx - g * D;
-        const size_t rec0 = (((size_t)first) * a.Hkv + kvh) * G + g, step = (size_t)a.Hkv * G;
-        float M = -INFINITY;
-        for (int p = 0; p < nparts; ++p) M = fmaxf(M, a.part_ml[(rec0 + p * step) * 2]);
-        float l = 0.f, acc = 0.f;
-        int p = 0;
-        for (; p + 1 < nparts; p += 2) {                   // two independent records per step
-            const size_t r0 = rec0 + p * step, r1 = r0 + step;
-            const float m0 = a.part_ml[r0 * 2], m1 = a.part_ml[r1 * 2];
-            const float l0 = a.part_ml[r0 * 2 + 1], l1 = a.part_ml[r1 * 2 + 1];
-            const float a0 = a.part_acc[r0 * D + j], a1 = a.part_acc[r1 * D + j];
-            const float f0 = exp2f(m0 - M), f1 = exp2f(m1 - M);
-            l += f0 * l0;
-            acc += f0 * a0;
-            l += f1 * l1;
-            acc += f1 * a1;
-        }
-        if (p < nparts) {
-            const size_t r0 = rec0 + p * step;
-            const float f0 = exp2f(a.part_ml[r0 * 2] - M);
-            l += f0 * a.part_ml[r0 * 2 + 1];
-            acc += f0 * a.part_acc[r0 * D + j];
-        }
-        T* o = (T*)a.out + ((size_t)seq * a.Hkv * G + (size_t)kvh * G + g) * D + j;
-        Elem<T>::store(o, acc / l);
-    }
+    merge_records<T, D, false>(a, first, nparts, kvh, seq, a.G, slice * 256 + threadIdx.x, kMergeSlices * 256);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -622,6 +675,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a, i
 // ---------------------------------------------------------------------------------------------
 constexpr int kPartChoices[] = {256, 512, 1024, 2048, 4096, 8192};
 constexpr int kNumPartChoices = 6;
+constexpr int64_t kFoldMaxTokens = 2000000;   // context tokens up to which the merge is folded into the partial kernel
 constexpr int kPartDivisor = 1024;    // aim at >= this many (partition, kv head) workgroups
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -645,7 +699,7 @@ int choose_part_tokens(const kun_kv_pool* p, int64_t ub) {
 }
 
 struct DecodeLayout {
-    size_t off_first, off_items, off_ml, off_acc, total;
+    size_t off_first, off_arrived, off_items, off_ml, off_acc, total;
     int max_items;
 };
 
@@ -656,6 +710,7 @@ DecodeLayout layout_for(const kun_kv_pool* p, int S, int Hq, int64_t ub, int P) 
     lay.max_items = (int)(mi > INT32_MAX / 2 ? INT32_MAX / 2 : mi);
     size_t o = 256;
     lay.off_first = o; o += align256(sizeof(int32_t) * ((size_t)S + 1));
+    lay.off_arrived = o; o += align256(sizeof(int32_t) * (size_t)S * p->Hkv);
     lay.off_items = o; o += align256(sizeof(int4) * (size_t)lay.max_items);
     lay.off_ml = o;    o += align256(sizeof(float) * 2 * (size_t)lay.max_items * p->Hkv * G);
     lay.off_acc = o;   o += align256(sizeof(float) * (size_t)lay.max_items * p->Hkv * G * p->d);
@@ -715,7 +770,8 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
     a.n_items = (int32_t*)ws;
     a.seq_first = (int32_t*)(ws + 256);
     a.items = (int4*)(ws + 256 + align256(sizeof(int32_t) * ((size_t)T + 1)));
-    a.part_ml = nullptr;          // one partition per row: outputs are written directly
+    a.arrived = nullptr;          // one partition per row: outputs are written directly
+    a.part_ml = nullptr;
     a.part_acc = nullptr;
     a.max_blocks = max_blocks;
     a.S = T;
@@ -729,6 +785,7 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
     a.block_bytes = (unsigned)p->block_bytes;
     a.page_bytes = (unsigned)p->page_bytes;
     a.xcd_map = 0;
+    a.fold = 0;
     const int nb = (T + 256) / 256;
     hipLaunchKernelGGL(rows_plan_kernel, dim3((unsigned)(nb < 1024 ? nb : 1024)), dim3(256), 0, st, T, a.n_items,
                        a.seq_first, a.items, ctx_len);
@@ -806,6 +863,7 @@ int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* bloc
     a.n_items = (int32_t*)ws;
     a.seq_first = (int32_t*)(ws + lay.off_first);
     a.items = (int4*)(ws + lay.off_items);
+    a.arrived = (int32_t*)(ws + lay.off_arrived);
     a.part_ml = (float*)(ws + lay.off_ml);
     a.part_acc = (float*)(ws + lay.off_acc);
     a.max_blocks = max_blocks;
@@ -820,9 +878,14 @@ int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* bloc
     a.block_bytes = (unsigned)p->block_bytes;
     a.page_bytes = (unsigned)p->page_bytes;
     a.xcd_map = 0;
+    // Small batches: the merge rides in the partial kernel (one launch and one gap less, worth 2 % of
+    // a 0.5 ms call).  Large ones: a launch of its own (there the wait for the arrival count at the end
+    // of every workgroup costs more than the launch: 4 % of a 2.6 ms call).
+    const int merge_opt = kun_options().decode_merge;
+    a.fold = merge_opt == 1 || (merge_opt == 0 && ub <= kFoldMaxTokens);
 
     hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(1024), 0, st, ctx_len, S, P, lay.max_items,
-                       a.n_items, a.seq_first, a.items);
+                       a.n_items, a.seq_first, a.items, a.arrived, S * p->Hkv);
     KUN_HIP_CHECK_LAUNCH();
 
     dim3 grid((unsigned)((size_t)lay.max_items * p->Hkv));
@@ -841,13 +904,14 @@ int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* bloc
     }
     if (rc != KUN_OK) return rc;
     KUN_HIP_CHECK_LAUNCH();
-
-    const dim3 mgrid((unsigned)((size_t)S * p->Hkv * kMergeSlices));
-    if (p->dtype == KUN_BF16)
-        hipLaunchKernelGGL(decode_merge_kernel<bf16_t>, mgrid, dim3(256), 0, st, a, p->d);
-    else
-        hipLaunchKernelGGL(decode_merge_kernel<float>, mgrid, dim3(256), 0, st, a, p->d);
-    KUN_HIP_CHECK_LAUNCH();
+    if (!a.fold) {
+        const dim3 mgrid((unsigned)((size_t)S * p->Hkv * kMergeSlices));
+        if (p->dtype == KUN_BF16 && p->d == 128) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 128>), mgrid, dim3(256), 0, st, a);
+        else if (p->dtype == KUN_BF16) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 64>), mgrid, dim3(256), 0, st, a);
+        else if (p->d == 128) hipLaunchKernelGGL((decode_merge_kernel<float, 128>), mgrid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((decode_merge_kernel<float, 64>), mgrid, dim3(256), 0, st, a);
+        KUN_HIP_CHECK_LAUNCH();
+    }
     return KUN_OK;
 }
 

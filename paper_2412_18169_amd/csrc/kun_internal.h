@@ -50,6 +50,7 @@ struct KunOptions {
     int decode_waves = 4;         // waves per workgroup of the MFMA decode kernel: 1, 2 or 4
     bool decode_generic = false;  // run the vector-ALU decode kernel where the MFMA one would
     bool decode_flat_map = false; // item-major workgroup order instead of the XCD-aware one
+    int decode_merge = 0;         // 0 = by batch size, 1 = always inside the partial kernel, 2 = always a launch of its own
     int prefill_shape = 0;        // 0 = default kernel; other values select cross-check kernels (prefill.hip)
 };
 const KunOptions& kun_options();

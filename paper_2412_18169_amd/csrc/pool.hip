@@ -34,6 +34,11 @@ bool apply_option(KunOptions& o, const char* name, const char* value) {
     } else if (!strcmp(name, "KUN_DECODE_MAP")) {
         if (!unset && strcmp(value, "flat") && strcmp(value, "xcd")) return false;
         o.decode_flat_map = !unset && !strcmp(value, "flat");
+    } else if (!strcmp(name, "KUN_DECODE_MERGE")) {
+        if (unset || !strcmp(value, "auto")) o.decode_merge = 0;
+        else if (!strcmp(value, "fold")) o.decode_merge = 1;
+        else if (!strcmp(value, "kernel")) o.decode_merge = 2;
+        else return false;
     } else if (!strcmp(name, "KUN_PREFILL_SHAPE")) {
         if (unset || !strcmp(value, "default")) o.prefill_shape = 0;
         else if (!strcmp(value, "persistent")) o.prefill_shape = 1;
@@ -47,7 +52,7 @@ bool apply_option(KunOptions& o, const char* name, const char* value) {
 }
 
 const char* const kOptionNames[] = {"KUN_DECODE_PART", "KUN_DECODE_WAVES", "KUN_DECODE_KERNEL", "KUN_DECODE_MAP",
-                                    "KUN_PREFILL_SHAPE"};
+                                    "KUN_DECODE_MERGE", "KUN_PREFILL_SHAPE"};
 
 KunOptions options_from_environment() {
     KunOptions o;

@@ -672,8 +672,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void prefill_pp_kernel(const PrefillArgs a) {
     constexpr int NW = 8, ROWS_W = 32, ROWS = NW * ROWS_W, POS = ROWS / G, LIVE = POS * G;
     constexpr int NSTAGE = 4, STAGE_BYTES = 2 * kBlocksPerTile * 4096, V_OFF = kBlocksPerTile * 4096;
-    constexpr int kAhead = 4;                          // distance, in MFMAs, between a fragment read and its use
-    constexpr int kPre = 4;                            // V^T fragments requested before the matrix phase begins
+#ifndef KUN_PP_AHEAD
+#define KUN_PP_AHEAD 4
+#endif
+#ifndef KUN_PP_PRE
+#define KUN_PP_PRE 4
+#endif
+    constexpr int kAhead = KUN_PP_AHEAD;               // distance, in MFMAs, between a fragment read and its use
+    constexpr int kPre = KUN_PP_PRE;                   // V^T fragments requested before the matrix phase begins
     static_assert(G >= 1 && G <= 16, "1 to 8 or 16 query heads per KV head");
 
     __shared__ __attribute__((aligned(16))) unsigned char ring[NSTAGE][STAGE_BYTES];

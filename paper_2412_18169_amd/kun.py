@@ -115,7 +115,8 @@ def status_string(status: int) -> str:
     return lib().kun_status_string(int(status)).decode()
 
 
-OPTION_NAMES = ("KUN_DECODE_PART", "KUN_DECODE_WAVES", "KUN_DECODE_KERNEL", "KUN_DECODE_MAP", "KUN_PREFILL_SHAPE")
+OPTION_NAMES = ("KUN_DECODE_PART", "KUN_DECODE_WAVES", "KUN_DECODE_KERNEL", "KUN_DECODE_MAP", "KUN_DECODE_MERGE",
+                "KUN_PREFILL_SHAPE")
 
 
 def kun_set_option(name: str, value=None) -> None:

@@ -47,6 +47,7 @@ def _announce(request):
     kun.kun_set_option("KUN_DECODE_PART", None)
     kun.kun_set_option("KUN_DECODE_WAVES", None)
     kun.kun_set_option("KUN_DECODE_MAP", None)
+    kun.kun_set_option("KUN_DECODE_MERGE", None)
 
 
 def test_config1_tiny_fp32():
@@ -429,4 +430,53 @@ def test_config2_8b_decode_full_parity():
                                  torch.from_numpy(w.decode_lens.astype(np.int32)))
     err = check_decode(dw)
     print("cfg2 max err", err)
+    dw.close()
+
+
+def test_merged_records_are_fresh_when_the_workspace_is_reused():
+    # The last workgroup of a (request, kv head) to finish merges the partial records that the other
+    # partitions -- on other XCDs, behind other L2 caches -- have written.  A stale read would pick up
+    # the records of the call before: so the same workspace serves calls with different queries in
+    # turn, many multi-partition requests each, and every output is checked against the oracle.
+    sh = synth.LayerShape(Hq=32, Hkv=8, d=128, B=16, dtype="bf16")
+    rng = np.random.default_rng(5)
+    lens = rng.integers(600, 5000, size=96).tolist()
+    w = synth.custom_workload("fresh", sh, lens, extra_blocks=3, range_fracs=(0.5, 0.5))
+    kun.kun_set_option("KUN_DECODE_PART", "256")         # 3 to 20 partitions per request
+    kun.kun_set_option("KUN_DECODE_MERGE", "fold")
+    dw = DeviceWorkload(w)
+    q_a = dw.q_dec.clone()
+    q_b = (-2.0 * q_a.float()).to(q_a.dtype)
+    outs = {}
+    for name, q in (("a", q_a), ("b", q_b), ("a", q_a), ("b", q_b)):
+        dw.q_dec.copy_(q)
+        dw.out_dec.fill_(float("nan"))
+        check_decode(dw)
+        got = dw.out_dec.clone()
+        if name in outs:
+            assert torch.equal(got.view(torch.int16), outs[name].view(torch.int16))
+        outs[name] = got
+    assert not torch.equal(outs["a"].view(torch.int16), outs["b"].view(torch.int16))
+    dw.close()
+
+
+@pytest.mark.parametrize("dtype,d,G", [("bf16", 128, 4), ("f32", 64, 2)])
+def test_merge_inside_the_partial_kernel_and_as_a_launch_of_its_own_give_the_same_bits(dtype, d, G):
+    # small batches merge the split-K records in the partial kernel (last workgroup to arrive), large
+    # ones in a separate launch; both combine the records in partition order with the same arithmetic
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=16, dtype=dtype)
+    lens = [1, 255, 256, 257, 700, 1025, 2049, 3000, 64, 0, 513]
+    w = synth.custom_workload("merge-modes", sh, lens, extra_blocks=3, range_fracs=(0.4, 0.6))
+    kun.kun_set_option("KUN_DECODE_PART", "256")
+    dw = DeviceWorkload(w)
+    outs = []
+    for mode in ("fold", "kernel", "auto"):
+        kun.kun_set_option("KUN_DECODE_MERGE", mode)
+        dw.out_dec.fill_(float("nan"))
+        check_decode(dw)
+        outs.append(dw.out_dec.clone())
+    live = torch.tensor([L > 0 for L in lens], device=outs[0].device)
+    bits = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(outs[0][live].view(bits), outs[1][live].view(bits))
+    assert torch.equal(outs[0][live].view(bits), outs[2][live].view(bits))
     dw.close()

@@ -56,7 +56,7 @@ def set_shape(shape):
         kun.kun_set_option("KUN_PREFILL_SHAPE", shape)
 
 
-@pytest.mark.parametrize("shape", ["default", "persistent"])
+@pytest.mark.parametrize("shape", ["default", "persistent", "ring", "ring-persistent"])
 @pytest.mark.parametrize("G", [4, 8, 1, 2])
 def test_ragged_chunks(G, shape):
     set_shape(shape)
@@ -71,7 +71,7 @@ def test_ragged_chunks(G, shape):
     dw.close()
 
 
-@pytest.mark.parametrize("shape", ["default", "persistent"])
+@pytest.mark.parametrize("shape", ["default", "persistent", "ring"])
 @pytest.mark.parametrize("profile", ["steps", "jump", "decay"])
 def test_scores_that_outgrow_the_running_maximum(profile, shape):
     # Key magnitude changes along the context, so the rows' reference maximum has to move on tiles

@@ -15,6 +15,11 @@ of a request gathered in logical order from its KV blocks:
   ("prefix-attn") and causally to itself, diagonal included ("self-attn"), which is
   p*c + (c^2 + c)/2 (query, key) pairs (Section 4.3, Eq. 1).
 
+KV quantisation is what Section 7 names as the lossy alternative for a KVCache under memory pressure:
+pages may hold K and V as 8-bit floats (OCP FP8 "E4M3": 1 sign, 4 exponent bits with bias 7, 3 mantissa
+bits, no infinities, the one NaN pattern S.1111.111) while queries and outputs stay bf16; the oracle
+widens the page bytes exactly and computes as before, so the same tolerance applies.
+
 Readings where the paper is silent: consecutive query heads share a KV head (GQA); the context
 length counts the token being decoded; one page (block, kv head) is a row of tiles of min(B, 16)
 tokens, a tile storing K as [token][dim] then V as [dim][token] (the paper fixes no layout inside
@@ -37,16 +42,22 @@ import numpy as np
 
 @dataclass
 class OraclePool:
-    """ranges[r]: flat numpy array of raw elements of range r (float32, or uint16 holding bf16)."""
+    """ranges[r]: flat numpy array of raw elements of range r (float32, uint16 holding bf16, or uint8
+    holding FP8 E4M3 codes)."""
     ranges: List[np.ndarray]
     Hkv: int
     d: int
     B: int
-    dtype: str  # 'f32' | 'bf16'
+    dtype: str  # 'f32' | 'bf16' | 'fp8' (what the pages hold)
 
     @property
     def elt(self) -> int:
-        return 4 if self.dtype == "f32" else 2
+        return {"f32": 4, "bf16": 2, "fp8": 1}[self.dtype]
+
+    @property
+    def q_dtype(self) -> str:
+        """Element type of queries (and outputs): the pages' type, except that FP8 pages go with bf16."""
+        return "bf16" if self.dtype == "fp8" else self.dtype
 
     @property
     def block_elems(self) -> int:
@@ -120,9 +131,16 @@ def v_elem_offset(pool: OraclePool, local_block: int, kvh: int, slot: int, j: in
 
 
 def widen(raw: np.ndarray, dtype: str) -> np.ndarray:
-    """Raw elements -> fp64, exactly (bf16 is the upper half of an fp32)."""
+    """Raw elements -> fp64, exactly (bf16 is the upper half of an fp32; an FP8 E4M3 code S.EEEE.MMM is
+    (-1)^S (1 + M/8) 2^(E - 7) for E > 0, (-1)^S (M/8) 2^-6 for E = 0, and NaN for S.1111.111)."""
     if dtype == "bf16":
         return (raw.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    if dtype == "fp8":
+        c = raw.astype(np.int64)
+        sign = np.where((c >> 7) & 1, -1.0, 1.0)
+        e, m = (c >> 3) & 15, c & 7
+        val = np.where(e == 0, np.ldexp(m / 8.0, -6), np.ldexp(1.0 + m / 8.0, (e - 7).astype(np.int64)))
+        return np.where((e == 15) & (m == 7), np.nan, sign * val)
     return raw.astype(np.float64)
 
 
@@ -176,7 +194,7 @@ def paged_decode(pool: OraclePool, q: np.ndarray, tables: np.ndarray, ctx_len: S
     S = q.shape[0]
     G = Hq // pool.Hkv
     scale = float(np.float32(scale))
-    q64 = widen(q.reshape(-1), pool.dtype).reshape(S, Hq, pool.d)
+    q64 = widen(q.reshape(-1), pool.q_dtype).reshape(S, Hq, pool.d)
     out = np.full((S, Hq, pool.d), np.nan, dtype=np.float64)
     for s in range(S):
         L = int(ctx_len[s])
@@ -199,7 +217,7 @@ def paged_prefill_chunk(pool: OraclePool, q: np.ndarray, table_row: Sequence[int
     if rows is None:
         rows = range(c)
     rows = list(rows)
-    q64 = widen(q.reshape(-1), pool.dtype).reshape(c, Hq, pool.d)
+    q64 = widen(q.reshape(-1), pool.q_dtype).reshape(c, Hq, pool.d)
     out = np.empty((len(rows), Hq, pool.d), dtype=np.float64)
     pairs = 0
     if not rows:

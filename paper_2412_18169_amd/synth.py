@@ -88,19 +88,26 @@ def hash_u16_numpy(key: int, idx: np.ndarray) -> np.ndarray:
 _TABLES = {}
 
 
-def normal_table(dtype: torch.dtype, device="cpu") -> torch.Tensor:
-    """T[i] = round_to_dtype(Phi^-1((i + 1/2) / 65536)), built in fp64 on the host."""
+FP8 = "fp8"      # stands for "uint8 codes of OCP FP8 E4M3" where a torch dtype is expected below
+
+
+def normal_table(dtype, device="cpu") -> torch.Tensor:
+    """T[i] = round_to_dtype(Phi^-1((i + 1/2) / 65536)), built in fp64 on the host.  For FP8 the
+    table holds the uint8 codes of the values rounded to E4M3 (round to nearest even)."""
     k = (dtype, str(device))
     if k not in _TABLES:
         from scipy.special import ndtri
 
-        t64 = ndtri((np.arange(65536, dtype=np.float64) + 0.5) / 65536.0)
-        _TABLES[k] = torch.from_numpy(t64).to(dtype).to(device)
+        t64 = torch.from_numpy(ndtri((np.arange(65536, dtype=np.float64) + 0.5) / 65536.0))
+        if dtype == FP8:
+            _TABLES[k] = t64.to(torch.float32).to(torch.float8_e4m3fn).view(torch.uint8).to(device)
+        else:
+            _TABLES[k] = t64.to(dtype).to(device)
     return _TABLES[k]
 
 
 def normal_values(seed: int, tensor_id: int, seq: int, first: int, count: int,
-                  dtype: torch.dtype, device="cpu") -> torch.Tensor:
+                  dtype, device="cpu") -> torch.Tensor:
     """`count` N(0,1) values of stream (seed, tensor, seq), counters first .. first+count-1."""
     idx = torch.arange(first, first + count, dtype=torch.int64, device=device)
     u = hash_u16(stream_key(seed, tensor_id, seq), idx)
@@ -113,7 +120,8 @@ def normal_values(seed: int, tensor_id: int, seq: int, first: int, count: int,
 
 @dataclass(frozen=True)
 class LayerShape:
-    """One attention layer. dtype is 'f32' or 'bf16'. B = tokens per KV block."""
+    """One attention layer. dtype is what the KV pages hold: 'f32', 'bf16' or 'fp8' (OCP E4M3 codes;
+    queries and outputs are bf16 then). B = tokens per KV block."""
     Hq: int
     Hkv: int
     d: int
@@ -126,11 +134,27 @@ class LayerShape:
 
     @property
     def elt(self) -> int:
+        """bytes per K/V element"""
+        return {"f32": 4, "bf16": 2, "fp8": 1}[self.dtype]
+
+    @property
+    def q_elt(self) -> int:
         return 4 if self.dtype == "f32" else 2
 
     @property
     def torch_dtype(self) -> torch.dtype:
+        """of queries and outputs"""
         return torch.float32 if self.dtype == "f32" else torch.bfloat16
+
+    @property
+    def kv_torch_dtype(self) -> torch.dtype:
+        """of the page buffers and of K/V rows handed to kun_kv_append (uint8 codes for fp8)"""
+        return torch.uint8 if self.dtype == "fp8" else self.torch_dtype
+
+    @property
+    def kv_value_kind(self):
+        """key of the value table K/V are drawn from"""
+        return FP8 if self.dtype == "fp8" else self.torch_dtype
 
     @property
     def block_bytes(self) -> int:
@@ -353,8 +377,8 @@ def kv_logical(w: Workload, seq: int, t0: int, t1: int, device="cpu"):
     """Logical K and V of sequence `seq`, tokens t0..t1-1: two tensors [t1-t0, Hkv, d]."""
     sh = w.shape
     n = sh.Hkv * sh.d
-    k = normal_values(w.seed, TENSOR_K, seq, t0 * n, (t1 - t0) * n, sh.torch_dtype, device)
-    v = normal_values(w.seed, TENSOR_V, seq, t0 * n, (t1 - t0) * n, sh.torch_dtype, device)
+    k = normal_values(w.seed, TENSOR_K, seq, t0 * n, (t1 - t0) * n, sh.kv_value_kind, device)
+    v = normal_values(w.seed, TENSOR_V, seq, t0 * n, (t1 - t0) * n, sh.kv_value_kind, device)
     return k.view(t1 - t0, sh.Hkv, sh.d), v.view(t1 - t0, sh.Hkv, sh.d)
 
 
@@ -366,15 +390,16 @@ def range_of_blocks(range_blocks: Sequence[int], ids: np.ndarray):
 
 
 def alloc_ranges(w: Workload, device="cpu", poison: bool = True) -> List[torch.Tensor]:
-    """One buffer per pool range, [n_blocks, Hkv, 2, B*d] elements; unused space NaN-poisoned."""
+    """One buffer per pool range, [n_blocks, Hkv, 2, B*d] elements; unused space NaN-poisoned (FP8:
+    the code 0x7F)."""
     sh = w.shape
     out = []
     for nb in w.range_blocks:
         if poison:
-            t = torch.full((nb, sh.Hkv, 2, sh.B * sh.d), float("nan"), dtype=sh.torch_dtype,
-                           device=device)
+            t = torch.full((nb, sh.Hkv, 2, sh.B * sh.d), 0x7F if sh.dtype == "fp8" else float("nan"),
+                           dtype=sh.kv_torch_dtype, device=device)
         else:
-            t = torch.empty((nb, sh.Hkv, 2, sh.B * sh.d), dtype=sh.torch_dtype, device=device)
+            t = torch.empty((nb, sh.Hkv, 2, sh.B * sh.d), dtype=sh.kv_torch_dtype, device=device)
         out.append(t)
     return out
 

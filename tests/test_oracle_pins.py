@@ -422,3 +422,86 @@ def test_config_shapes():
     assert w5.num_blocks * w5.shape.block_bytes >= 149 * 10**9 and len(w5.range_blocks) == 5
     used = np.concatenate(w5.block_tables)
     assert len(np.unique(used)) == len(used)
+
+
+# ------------------------------------------------------------------------------------------
+# FP8 (E4M3) pages: the lossy KV representation Section 7 names as the alternative under memory
+# pressure.  The oracle widens the page bytes exactly; these pins fix what "exactly" means.
+# ------------------------------------------------------------------------------------------
+
+def test_fp8_e4m3_codes_widen_to_the_values_the_format_defines():
+    codes = np.arange(256, dtype=np.uint8)
+    got = O.widen(codes, "fp8")
+    # (a) values typed in by hand from the format's definition (1 sign, 4 exponent bits, bias 7, 3
+    #     mantissa bits, subnormals at exponent 0, no infinities, S.1111.111 is the only NaN)
+    by_hand = {0x00: 0.0, 0x01: 2.0 ** -9, 0x02: 2.0 ** -8, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x09: 1.125 * 2.0 ** -6,
+               0x30: 0.5, 0x38: 1.0, 0x39: 1.125, 0x3F: 1.875, 0x40: 2.0, 0x44: 3.0, 0x48: 4.0, 0x77: 240.0, 0x78: 256.0,
+               0x7E: 448.0, 0x81: -2.0 ** -9, 0xB8: -1.0, 0xC0: -2.0, 0xFE: -448.0}
+    for c, v in by_hand.items():
+        assert got[c] == v, (hex(c), got[c], v)
+    assert np.isnan(got[0x7F]) and np.isnan(got[0xFF]) and np.isfinite(np.delete(got, [0x7F, 0xFF])).all()
+    assert got[0x80] == 0.0 and np.signbit(got[0x80]) and not np.signbit(got[0x00])
+    # (b) structure: the 127 non-negative finite codes increase strictly; inside a binade the step is
+    #     constant and doubles from one binade to the next; the negative half mirrors the positive one
+    pos = got[:0x7F]
+    assert (np.diff(pos) > 0).all()
+    steps = np.diff(pos)
+    assert (steps[:15] == 2.0 ** -9).all()                              # subnormals and the first binade
+    for e in range(2, 16):
+        assert (steps[8 * e:8 * e + 7] == 2.0 ** (e - 10)).all()
+    assert np.array_equal(got[0x80:0xFF], -pos)
+    # (c) a library's conversion of the same codes (torch's float8_e4m3fn), all 256
+    lib = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(got, lib, equal_nan=True)
+
+
+def test_fp8_pages_decode_and_prefill_match_dense_brute_force():
+    # K/V pages hold E4M3 codes, queries are bf16; the dense reference decodes the codes with the
+    # library conversion and never sees pages, tiles or block tables
+    sh = synth.LayerShape(Hq=4, Hkv=2, d=8, B=4, dtype="fp8")
+    w = synth.custom_workload("fp8-tiny", sh, [1, 3, 4, 9], chunks=[(2, 5)], extra_blocks=2, range_fracs=(0.5, 0.5))
+    ranges, pool = make_pool(w)
+    assert pool.elt == 1 and pool.q_dtype == "bf16" and pool.block_bytes == 2 * 2 * 4 * 8
+    q = synth.q_decode(w)
+    got = O.paged_decode(pool, synth.to_host_bits(q), w.table_array(range(w.S)), w.decode_lens, sh.Hq, sh.scale)
+
+    def dense_kv(seq, L):
+        k, v = synth.kv_logical(w, seq, 0, L)
+        assert k.dtype == torch.uint8
+        return (k.view(torch.float8_e4m3fn).to(torch.float64).numpy(), v.view(torch.float8_e4m3fn).to(torch.float64).numpy())
+
+    scale = float(np.float32(sh.scale))
+    for s in range(w.S):
+        L = int(w.decode_lens[s])
+        k, v = dense_kv(s, L)
+        for h in range(sh.Hq):
+            kvh = h // sh.G
+            ref = dense_attention([q[s, h].double().tolist()], k[:, kvh].tolist(), v[:, kvh].tolist(), scale,
+                                  [[True] * L])
+            assert np.allclose(got[s, h], ref[0], rtol=0, atol=1e-12)
+    p, c = w.chunks[0]
+    qc = synth.q_chunk(w, 0)
+    gotc, pairs = O.paged_prefill_chunk(pool, synth.to_host_bits(qc), w.block_tables[w.S], p, c, sh.Hq, sh.scale)
+    assert pairs == p * c + (c * c + c) // 2
+    k, v = dense_kv(w.S, p + c)
+    for h in range(sh.Hq):
+        kvh = h // sh.G
+        mask = [[t <= p + r for t in range(p + c)] for r in range(c)]
+        ref = dense_attention(qc[:, h].double().tolist(), k[:, kvh].tolist(), v[:, kvh].tolist(), scale, mask)
+        assert np.allclose(gotc[:, h], np.asarray(ref), rtol=0, atol=1e-12)
+    # unused slots hold the NaN code and never reach an output
+    assert np.isfinite(got).all() and np.isfinite(gotc).all()
+    assert any((synth.to_host_bits(r) == 0x7F).any() for r in ranges)
+
+
+def test_fp8_values_of_the_generator_are_the_nearest_e4m3_codes():
+    # the input generator rounds its N(0,1) quantiles to E4M3 with torch; the oracle's widening of those
+    # codes must land within half a step of the quantile (round to nearest), so the two agree on the format
+    tab = synth.normal_table(synth.FP8)
+    from scipy.special import ndtri
+    want = ndtri((np.arange(65536, dtype=np.float64) + 0.5) / 65536.0)
+    got = O.widen(tab.numpy(), "fp8")
+    step = np.maximum(2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 2.0 ** -6))) - 3), 2.0 ** -9)
+    # (the generator goes through fp32 first, which can turn a near tie into a tie: half a step plus an fp32 ulp)
+    assert (np.abs(got - want) <= step / 2 * (1 + 2.0 ** -20)).all()
+    assert abs(got.mean()) < 1e-3 and abs(got.std() - 1.0) < 2e-2

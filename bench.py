@@ -39,6 +39,9 @@ def parse():
                     help="tokens per KV block (default: the configuration's own, 16)")
     ap.add_argument("--q-heads", type=int, default=0,
                     help="query heads (default: the configuration's own); e.g. 40 over the 8 KV heads of cfg 2-4")
+    ap.add_argument("--kv-dtype", default="", choices=["", "fp8"],
+                    help="element type of the KV pages (default: the configuration's own, bf16); fp8 = E4M3 pages "
+                         "with bf16 queries: 2 048 instead of 4 096 algorithmic bytes per token")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true",
                     help="skip the shorter runs of configurations 3, 4 and 2 that follow the default workload")
@@ -60,7 +63,7 @@ def decode_bytes(w):
     sh = w.shape
     L = w.decode_lens.astype(np.int64)
     kv = int(L.sum()) * 2 * sh.Hkv * sh.d * sh.elt
-    qo = w.S * sh.Hq * sh.d * sh.elt * 2
+    qo = w.S * sh.Hq * sh.d * sh.q_elt * 2
     tab = 4 * int(((L + sh.B - 1) // sh.B).sum())
     return kv + qo + tab
 
@@ -70,7 +73,7 @@ def prefill_flops(w):
     return 4 * sh.d * sh.Hq * w.prefill_pairs
 
 
-def time_steps(cfg, args, block_size=0, q_heads=0):
+def time_steps(cfg, args, block_size=0, q_heads=0, kv_dtype=""):
     """Builds configuration `cfg` on the device and times args.steps steps (after args.warmup untimed
     ones).  A step = KV append of the step's new tokens + chunked prefill + decode on one stream, inputs
     resident in HBM.  Returns (report, dw, dws): the per-part figures, the first DeviceWorkload (kept
@@ -79,7 +82,7 @@ def time_steps(cfg, args, block_size=0, q_heads=0):
     from paper_2412_18169_amd import kun, synth
     from paper_2412_18169_amd.runner import DeviceWorkload
     t_setup = time.time()
-    w = synth.config(cfg, block_size, q_heads)
+    w = synth.config(cfg, block_size, q_heads, kv_dtype)
     sh = w.shape
     dw = DeviceWorkload(w, poison=(cfg != 5))
     torch.cuda.synchronize()
@@ -151,7 +154,7 @@ def time_steps(cfg, args, block_size=0, q_heads=0):
         "ms_per_step": round(ms_per_step, 4), "dtype": sh.dtype,
         "config": {"workload": f"cfg{cfg}:{w.name}", "block_size": w.shape.B, "pools_alternated": len(dws),
                    "decode_requests": w.S, "prefill_chunks": w.n_chunks if has_prefill else 0,
-                   "Hq": sh.Hq, "Hkv": sh.Hkv, "head_dim": sh.d,
+                   "Hq": sh.Hq, "Hkv": sh.Hkv, "head_dim": sh.d, "kv_dtype": sh.dtype,
                    "pool_ranges": len(w.range_blocks), "pool_GB": round(w.num_blocks * sh.block_bytes / 1e9, 2),
                    "decode_kv_tokens": w.decode_kv_tokens, "seed": w.seed},
         "decode": {"ms": round(t_dec, 4), "ms_median": round(t_dec_med, 4), "algorithmic_bytes": dbytes,
@@ -184,22 +187,24 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     cfg = args.config or DEFAULT_CONFIG
-    rep, dw, dws = time_steps(cfg, args, args.block_size, args.q_heads)
+    rep, dw, dws = time_steps(cfg, args, args.block_size, args.q_heads, args.kv_dtype)
     w, sh = dw.w, dw.w.shape
     has_prefill = "prefill" in rep
     gbps = rep["decode"]["GB_per_s"]
-    traffic = TRAFFIC.get((cfg, sh.B, sh.Hq))
+    traffic = TRAFFIC.get((cfg, sh.B, sh.Hq, sh.dtype))
     out = {
         "metric": "paged_decode_hbm_bandwidth", "value": gbps, "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": rep["ms_per_step"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 (fp8 e4m3 pages)" if sh.dtype == "fp8" else sh.dtype,
         "data": "synthetic",
         "config": rep["config"], "decode": rep["decode"], "append": rep["append"],
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gbps / HBM_PEAK_GBPS, 4),
                      "traffic": traffic[0] if traffic else None,
                      "traffic_source": traffic[1] if traffic else None,
-                     "kernel": "decode_partial_mfma (timed with the plan launch in front of it)"},
+                     "kernel": ("decode_partial_mfma_fp8" if sh.dtype == "fp8" else "decode_partial_mfma") +
+                               " (timed with the plan launch in front of it and the merge behind it)"},
         "setup_s": rep["setup_s"],
     }
     if has_prefill:
@@ -227,7 +232,7 @@ def main():
     if not args.config and not args.no_others and not args.pmc_calibration:
         out["others"] = {}
         for c in OTHER_CONFIGS:
-            r, d0, ds = time_steps(c, args, args.block_size, args.q_heads)
+            r, d0, ds = time_steps(c, args, args.block_size, args.q_heads, args.kv_dtype)
             o = {"decode_ms": r["decode"]["ms"], "GB_per_s": r["decode"]["GB_per_s"],
                  "frac": r["decode"]["frac_of_hbm_peak"], "decode_kv_tokens": r["config"]["decode_kv_tokens"],
                  "ms_per_step": r["ms_per_step"]}
@@ -430,7 +435,7 @@ def cpu_baseline(dw, target_s):
     out_gpu = dw.decode().double().cpu().numpy()
     torch.cuda.synchronize()
     # sample: requests in batch order until about ORACLE_TOKENS_PER_S * target_s KV tokens
-    budget = int(ORACLE_TOKENS_PER_S * target_s)
+    budget = int(ORACLE_TOKENS_PER_S * (0.15 if sh.dtype == "fp8" else 1.0) * target_s)   # (widening E4M3 codes is slower)
     rows, tot = [], 0
     for s in range(w.S):
         rows.append(s)
@@ -445,7 +450,7 @@ def cpu_baseline(dw, target_s):
     ref = O.paged_decode(pool, qb, tab, lens, sh.Hq, sh.scale)
     dt = time.perf_counter() - t0
     err = float(np.abs(out_gpu[rows] - ref).max())
-    nbytes = tot * 2 * sh.Hkv * sh.d * sh.elt + len(rows) * sh.Hq * sh.d * sh.elt * 2
+    nbytes = tot * 2 * sh.Hkv * sh.d * sh.elt + len(rows) * sh.Hq * sh.d * sh.q_elt * 2
     return ({"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": int(cores), "kind": "oracle",
              "seconds": round(dt, 2),
              "sample": f"decode of the first {len(rows)} of {w.S} requests ({tot} KV tokens) of the same batch, "
@@ -479,8 +484,8 @@ PREFILL_SUPPORTED = True
 ORACLE_TOKENS_PER_S = 80000.0      # rough speed of the numpy oracle, only used to size its sample
 OTHER_CONFIGS = (3, 4, 2)          # reported under "others" after the default workload
 # HBM bytes per decode launch from rocprofv3 --pmc runs of an EARLIER session (not of this run), keyed by
-# (config, block size, query heads): (bytes, where the figure comes from).
-TRAFFIC = {(5, 16, 64): (17322737541, "profiles/bench_cfg5_70b_stage_kernels.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+# (config, block size, query heads, page dtype): (bytes, where the figure comes from).
+TRAFFIC = {(5, 16, 64, "bf16"): (17322737541, "profiles/bench_cfg5_70b_stage_kernels.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
                                        "of decode_partial_mfma in an earlier session, 1.015 x the algorithmic bytes; "
                                        "not measured in this run")}
 

@@ -37,9 +37,11 @@
  *
  * Supported shapes: block_size 16, 32, 64 or 128 (Section 5.1 tunes it to 64); head_dim 64 or 128;
  *   num_q_heads / num_kv_heads = 1 .. 8 (e.g. 40 query heads over 8 KV heads), or 16 with bf16 and
- *   head_dim 128 (e.g. 64 over 4); dtype f32 or bf16 (accumulation is always fp32).
- *   Anything else is KUN_ERR_UNSUPPORTED.  bf16 with head_dim 128 runs on the matrix cores, the
- *   other combinations on vector-ALU kernels that are correct to the same bar but not tuned.
+ *   head_dim 128 (e.g. 64 over 4); dtype f32, bf16 or FP8 E4M3 pages with bf16 queries
+ *   (accumulation is always fp32).  Anything else is KUN_ERR_UNSUPPORTED.  bf16 with head_dim 128
+ *   runs on the matrix cores (decode and prefill), and so does decode over FP8 pages with head_dim
+ *   128 (16 query heads per KV head included); the other combinations -- prefill over FP8 pages
+ *   among them -- run on vector-ALU kernels that are correct to the same bar but not tuned.
  */
 #ifndef KUN_H
 #define KUN_H
@@ -55,7 +57,12 @@ extern "C" {
 
 typedef struct kun_kv_pool kun_kv_pool; /* opaque host object */
 
-typedef enum { KUN_F32 = 0, KUN_BF16 = 1 } kun_dtype;
+/* Element type of the K/V pages.  KUN_FP8_E4M3: pages hold OCP FP8 E4M3 codes (1 sign, 4 exponent bits
+ * with bias 7, 3 mantissa bits, no infinities, NaN = S.1111.111), one byte per element -- the lossy KV
+ * representation Section 7 names as the alternative under memory pressure; queries, outputs and the
+ * softmax weights fed to the matrix cores stay bf16, accumulation fp32, and the K/V rows handed to
+ * kun_kv_append are FP8 bytes already (the caller quantises). */
+typedef enum { KUN_F32 = 0, KUN_BF16 = 1, KUN_FP8_E4M3 = 2 } kun_dtype;
 
 typedef enum {
     KUN_OK = 0,
@@ -153,7 +160,7 @@ KUN_API int kun_slot_map(const kun_kv_pool* pool, const int32_t* seq_of_tok, con
 
 /* ---- KV append: write the K/V rows of new tokens into their slots -------------------------- */
 
-/* k_new, v_new: device [T, num_kv_heads, head_dim] in the pool's dtype.  Token i belongs to row
+/* k_new, v_new: device [T, num_kv_heads, head_dim] in the pool's dtype (FP8 pools: one byte per element).  Token i belongs to row
  * seq_of_tok[i] of block_table (device int32 [rows, max_blocks]) at logical position
  * pos_of_tok[i] (device int32 [T]); it lands in block block_table[seq][pos / block_size], slot
  * pos % block_size.  T == 0 is a no-op. */
@@ -169,7 +176,7 @@ KUN_API size_t kun_decode_workspace_bytes(const kun_kv_pool* pool, int S, int nu
                                   int64_t total_ctx_upper_bound);
 
 /* One decode step for S requests (Section 2.1: decode reads the whole KVCache of each request
- * and is memory-bound).  q, out: device [S, num_q_heads, head_dim] in the pool's dtype; request s
+ * and is memory-bound).  q, out: device [S, num_q_heads, head_dim] in the pool's dtype (bf16 for FP8 pools); request s
  * has ctx_len[s] tokens in its pages INCLUDING the token being decoded, whose query is row s of q;
  * out[s] = softmax(scale * q K^T) V over those tokens.  ctx_len: device int32 [S]; a request with
  * ctx_len 0 is skipped and its output row left untouched.  block_table: device int32

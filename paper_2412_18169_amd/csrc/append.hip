@@ -79,7 +79,12 @@ extern "C" int kun_kv_append(kun_kv_pool* p, const void* k_new, const void* v_ne
         return KUN_ERR_INVALID_ARG;
     const dim3 grid((unsigned)(T < 65536 ? T : 65536));
     hipStream_t st = (hipStream_t)stream;
-    if (p->elt == 2)
+    if (p->elt == 1)
+        hipLaunchKernelGGL(kv_append_kernel<uint8_t>, grid, dim3(256), 0, st, p->ranges,
+                           (const uint8_t*)k_new, (const uint8_t*)v_new, seq_of_tok, pos_of_tok,
+                           block_table, max_blocks, T, p->Hkv, p->d, p->B, (unsigned)p->block_bytes,
+                           (unsigned)p->page_bytes);
+    else if (p->elt == 2)
         hipLaunchKernelGGL(kv_append_kernel<uint16_t>, grid, dim3(256), 0, st, p->ranges,
                            (const uint16_t*)k_new, (const uint16_t*)v_new, seq_of_tok, pos_of_tok,
                            block_table, max_blocks, T, p->Hkv, p->d, p->B, (unsigned)p->block_bytes,

@@ -23,6 +23,7 @@
 #include <stdlib.h>
 
 #include <mutex>
+#include <type_traits>
 
 #include "kun_internal.h"
 
@@ -183,6 +184,25 @@ template <> struct Elem<bf16_t> {
     __device__ static void store(bf16_t* p, float x) { p->bits = f32_to_bf16_rne(x); }
 };
 
+// K/V pages as OCP FP8 E4M3 codes (1 sign, 4 exponent, 3 mantissa bits; bias 7): converted exactly by the
+// hardware's conversion instruction.  Queries and outputs of such pools are bf16.
+struct fp8_t { unsigned char bits; };
+template <> struct Elem<fp8_t> {
+    static constexpr int kPerLoad = 16;
+    __device__ static float get(const uint4& v, int i) {
+        const unsigned w = (i >> 2) == 0 ? v.x : (i >> 2) == 1 ? v.y : (i >> 2) == 2 ? v.z : v.w;
+        switch (i & 3) {
+            case 0: return __builtin_amdgcn_cvt_f32_fp8(w, 0);
+            case 1: return __builtin_amdgcn_cvt_f32_fp8(w, 1);
+            case 2: return __builtin_amdgcn_cvt_f32_fp8(w, 2);
+            default: return __builtin_amdgcn_cvt_f32_fp8(w, 3);
+        }
+    }
+};
+// element type of queries and outputs for pages of type T
+template <typename T> struct QueryOf { typedef T type; };
+template <> struct QueryOf<fp8_t> { typedef bf16_t type; };
+
 // Stores and loads of partial records that are coherent across the whole device (they bypass what
 // the XCD-local L2 may hold of the line): relaxed atomic accesses at device scope.
 __device__ __forceinline__ void rec_store(float* p, float v) {
@@ -317,15 +337,19 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane % LPR, grp = lane / LPR;
 
+    typedef typename QueryOf<T>::type QT;              // queries and outputs
+    constexpr int QPL = Elem<QT>::kPerLoad;            // query elements per 16-byte load
     float qf[G][EPL];
     {
-        const T* qrow = (const T*)a.q + ((size_t)seq * a.Hkv + kvh) * G * D;
+        const QT* qrow = (const QT*)a.q + ((size_t)seq * a.Hkv + kvh) * G * D;
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            uint4 v = *(const uint4*)((const char*)(qrow + g * D) + col * 16);
+        for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) qf[g][e] = Elem<T>::get(v, e);
-        }
+            for (int c = 0; c < EPL / QPL; ++c) {
+                uint4 v = *(const uint4*)(qrow + g * D + col * EPL + c * QPL);
+#pragma unroll
+                for (int e = 0; e < QPL; ++e) qf[g][c * QPL + e] = Elem<QT>::get(v, e);
+            }
     }
     float m[G], l[G], acc[G][DPL];
 #pragma unroll
@@ -416,7 +440,7 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
         for (int i = 0; i < DPL; ++i) sm_acc[(wave * G + g) * D + lane + 64 * i] = acc[g][i];
     }
     __syncthreads();
-    finish_item<T, D, NW>(a, it4.w, part, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
+    finish_item<QT, D, NW>(a, it4.w, part, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -654,6 +678,263 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 }
 
 // ---------------------------------------------------------------------------------------------
+// 2c. MFMA partial kernel for FP8 (E4M3) pages: head_dim 128, q and out bf16, G <= 16.
+//
+// Half the bytes per token, so a wave walks QUADS of 16-token page tiles (64 tokens): the same sixteen
+// 16-byte loads per lane and step as the bf16 kernel's pair, each now holding sixteen elements, i.e.
+// two MFMA operands after conversion to bf16 (exact: every E4M3 value is a bf16 value).  The matrix
+// instructions stay the bf16 ones -- the query is bf16, and there is no MFMA that multiplies bf16 by
+// fp8.  With lane = 16 j + n:
+//   QK^T  four row sets a = 0..3 of S^T[token][head], 4 MFMA 16x16x32 each.  Row r of set a is token
+//         (r & 3) + 4a of tile r >> 2, so lane (n, j) loads K rows of tile n >> 2: chunk c = 0, 1 is
+//         bytes 64c + 16j .. + 16 of the row = dims 64c + 16j .. + 16, its low half the operand of
+//         k-step 2c and its high half that of k-step 2c + 1 (Q is loaded in the same order of dims).
+//         After the four sets lane (n, j) holds the scores of head n for all 16 tokens of tile j.
+//   PV    O^T[dim][head] += V^T[dim][token] P^T[token][head], two MFMA per 16 dims: k-slot (j, e) of
+//         half h is token 8h + e of tile j.  A = one 16-byte V^T row of tile j (16 tokens of one dim):
+//         low half for h = 0, high half for h = 1; B = P of those tokens, already in the lane.
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+
+struct QuadK {
+    uint4 k[4][2];   // K rows of a quad: [row set][chunk]
+};
+
+// sixteen E4M3 codes -> two operands of eight bf16 each (codes 0..7, codes 8..15)
+__device__ __forceinline__ void fp8x16_to_bf16(const uint4& x, Frag& lo, Frag& hi) {
+    union { bf16x2_t h; unsigned u; } c[8];
+    c[0].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.x, 1.0f, false);
+    c[1].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.x, 1.0f, true);
+    c[2].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.y, 1.0f, false);
+    c[3].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.y, 1.0f, true);
+    c[4].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.z, 1.0f, false);
+    c[5].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.z, 1.0f, true);
+    c[6].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.w, 1.0f, false);
+    c[7].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.w, 1.0f, true);
+    lo.u = make_uint4(c[0].u, c[1].u, c[2].u, c[3].u);
+    hi.u = make_uint4(c[4].u, c[5].u, c[6].u, c[7].u);
+}
+
+template <int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_partial_mfma_fp8(const DecodeArgs a) {
+    constexpr int D = 128;
+    constexpr int GMAX = 16;
+    constexpr int kTileBytes = 2 * kBlock * D;         // K [16][128] then V^T [128][16], one byte each
+    __shared__ float sm_m[NW * GMAX], sm_l[NW * GMAX];
+    __shared__ float sm_acc[NW * GMAX * D];
+
+    int item, kvh;
+    if (a.xcd_map) {
+        const int x = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        kvh = slot % a.Hkv;
+        item = (slot / a.Hkv) * 8 + x;
+    } else {
+        item = blockIdx.x / a.Hkv;
+        kvh = blockIdx.x % a.Hkv;
+    }
+    const int n_items = *a.n_items;
+    const int4 it4 = a.items[item < a.max_items ? item : a.max_items - 1];
+    if (item >= n_items || it4.w >= a.max_items) return;
+    const int seq = it4.x, part = it4.y;
+    const int G = a.G;
+    const int L = it4.z;
+    const int nparts = (L + a.part_tokens - 1) / a.part_tokens;
+    const int t0 = part * a.part_tokens;
+    const int t1 = min(L, t0 + a.part_tokens);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, j = lane >> 4;
+
+    // B operand of QK^T for k-step kk: Q[head n][dims 64 (kk / 2) + 16 j + 8 (kk % 2) .. + 8]
+    Frag qf[4];
+    {
+        const char* qrow = (const char*)a.q + (((size_t)seq * a.Hkv + kvh) * G + (n < G ? n : 0)) * D * 2;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            uint4 v = *(const uint4*)(qrow + 128 * (kk >> 1) + 32 * j + 16 * (kk & 1));
+            if (n >= G) v = make_uint4(0, 0, 0, 0);
+            qf[kk].u = v;
+        }
+    }
+    f32x4 o[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) o[s] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, l = 0.f;
+
+    const int32_t* trow = a.table + (size_t)seq * a.max_blocks;
+    const int ntile = (t1 + kBlock - 1) / kBlock;      // page tiles of the request this item may touch
+    const int tile0 = t0 / kBlock;                     // first page tile of the partition
+    const int ktile = n >> 2;                          // tile of the quad this lane's K rows come from
+    const unsigned k_off = (unsigned)(n & 3) * D + 16 * j;          // + 4 a rows, + 64 c
+    const unsigned v_off = kBlock * D + (unsigned)n * kBlock;       // + 16 s rows of V^T
+
+    const int quad_end = (ntile - tile0 + 3) / 4;      // quads of the partition
+
+    // Page-tile addresses of this wave's quads, 16 quads per register pair: lane 4k + b = tile b of the
+    // wave's k-th quad of the current batch.
+    auto load_pages = [&](int first_quad) -> unsigned long long {
+        int t = tile0 + 4 * (first_quad + (lane >> 2) * NW) + (lane & 3);
+        if (t >= ntile) t = ntile - 1;                 // beyond the partition: any valid tile
+        const int id = trow[t >> a.tile_shift];
+        int first = a.rt.first[0];
+        unsigned long long base = (unsigned long long)a.rt.base[0];
+        for (int r = 1; r < a.rt.n; ++r) {
+            const bool in = id >= a.rt.first[r];
+            first = in ? a.rt.first[r] : first;
+            base = in ? (unsigned long long)a.rt.base[r] : base;
+        }
+        return base + (unsigned long long)(id - first) * a.block_bytes + (unsigned long long)kvh * a.page_bytes +
+               (unsigned)(t & ((1 << a.tile_shift) - 1)) * kTileBytes;
+    };
+    unsigned long long pages = load_pages(wave);
+    int pages_first = wave;
+
+    // K of the next quad is requested before the current quad is computed (two K buffers used
+    // alternately); V^T has ONE buffer, refilled slice by slice with the next quad's rows as soon as
+    // the current quad's PV has read a slice -- those loads then stay in flight through the next
+    // quad's QK^T and softmax.  (Two full buffers, as in the bf16 kernel, do not fit next to the
+    // operands being converted.)
+    uint4 vbuf[8];
+    // requests the K rows of quad q; returns where this lane's V^T rows of that quad start
+    auto issue_k = [&](int q, QuadK& ld) -> const char* {
+        int k = (q - pages_first) / NW;
+        if (k >= 16) {
+            pages = load_pages(q);
+            pages_first = q;
+            k = 0;
+        }
+        unsigned long long pt[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const unsigned lo = __builtin_amdgcn_readlane((unsigned)pages, 4 * k + b);
+            const unsigned hi = __builtin_amdgcn_readlane((unsigned)(pages >> 32), 4 * k + b);
+            pt[b] = ((unsigned long long)hi << 32) | lo;
+        }
+        const unsigned long long kpage = ktile == 0 ? pt[0] : ktile == 1 ? pt[1] : ktile == 2 ? pt[2] : pt[3];
+        const unsigned long long vpage = j == 0 ? pt[0] : j == 1 ? pt[1] : j == 2 ? pt[2] : pt[3];
+        const char* kp = (const char*)kpage + k_off;
+#pragma unroll
+        for (int ra = 0; ra < 4; ++ra) {
+            ld.k[ra][0] = load_stream16(kp + ra * 4 * D);
+            ld.k[ra][1] = load_stream16(kp + ra * 4 * D + 64);
+        }
+        return (const char*)vpage + v_off;
+    };
+
+    // all of the wave's work on quad q; `refill`: vnext points at the V^T rows of the wave's next quad
+    auto compute = [&](int q, QuadK& ld, auto refill, const char* vnext) {
+        constexpr bool REFILL = decltype(refill)::value;
+        f32x4 sc4[4];
+#pragma unroll
+        for (int ra = 0; ra < 4; ++ra) {
+            f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                Frag k_lo, k_hi;
+                fp8x16_to_bf16(ld.k[ra][c], k_lo, k_hi);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k_lo.v, qf[2 * c].v, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k_hi.v, qf[2 * c + 1].v, acc, 0, 0, 0);
+            }
+            sc4[ra] = acc;
+        }
+        // lane (n, j): scores of head n for tokens tbase + 4 ra + i of the request
+        const int tbase = (tile0 + 4 * q + j) * kBlock;
+        float sc[16];
+#pragma unroll
+        for (int ra = 0; ra < 4; ++ra)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sc[4 * ra + i] = sc4[ra][i] * a.scale_log2;
+        const bool tail = (tile0 + 4 * q + 4) * kBlock > t1;
+        if (tail) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                if (tbase + e >= t1) sc[e] = -INFINITY;
+        }
+        float mx = sc[0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sc[e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float mn = fmaxf(m, mx);                 // finite: the quad has a visible token
+        const float alpha = __builtin_amdgcn_exp2f(m - mn);
+        float ps = 0.f;
+        Frag pf[2];
+        unsigned short pb[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float p = __builtin_amdgcn_exp2f(sc[e] - mn);
+            ps += p;
+            pb[e] = f32_to_bf16_rne(p);
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            pf[h].u = make_uint4(pb[8 * h + 0] | ((unsigned)pb[8 * h + 1] << 16), pb[8 * h + 2] | ((unsigned)pb[8 * h + 3] << 16),
+                                 pb[8 * h + 4] | ((unsigned)pb[8 * h + 5] << 16), pb[8 * h + 6] | ((unsigned)pb[8 * h + 7] << 16));
+        l = l * alpha + ps;
+        m = mn;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) o[s] *= alpha;
+        }
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            Frag vh[2];
+            fp8x16_to_bf16(vbuf[s], vh[0], vh[1]);
+            if (REFILL) vbuf[s] = load_stream16(vnext + s * (16 * kBlock));
+            if (tail) {   // slots past the context may hold anything: zero them (0 * NaN = NaN)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    unsigned w[4] = {vh[h].u.x, vh[h].u.y, vh[h].u.z, vh[h].u.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (tbase + 8 * h + e >= t1) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                    vh[h].u = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+            o[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh[0].v, pf[0].v, o[s], 0, 0, 0);
+            o[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh[1].v, pf[1].v, o[s], 0, 0, 0);
+        }
+    };
+
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(qf[kk].v));
+
+    using Yes = std::integral_constant<bool, true>;
+    using No = std::integral_constant<bool, false>;
+    QuadK kA, kB;
+    int q = wave;
+    if (q < quad_end) {
+        const char* v0 = issue_k(q, kA);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) vbuf[s] = load_stream16(v0 + s * (16 * kBlock));
+        // the last quad is computed on a path of its own, so that the steady-state path always has the
+        // next quad's loads behind the ones it waits for
+        for (;;) {
+            const int q1 = q + NW;
+            if (q1 >= quad_end) { compute(q, kA, No{}, nullptr); break; }
+            const char* v1 = issue_k(q1, kB);
+            compute(q, kA, Yes{}, v1);
+            const int q2 = q1 + NW;
+            if (q2 >= quad_end) { compute(q1, kB, No{}, nullptr); break; }
+            const char* v2 = issue_k(q2, kA);
+            compute(q1, kB, Yes{}, v2);
+            q = q2;
+        }
+    }
+
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (n < G) {
+        if (j == 0) { sm_m[wave * G + n] = m; sm_l[wave * G + n] = l; }
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sm_acc[(wave * G + n) * D + s * 16 + 4 * j + i] = o[s][i];
+    }
+    __syncthreads();
+    finish_item<bf16_t, D, NW>(a, it4.w, part, kvh, seq, nparts, G, sm_m, sm_l, sm_acc);
+}
+
+// ---------------------------------------------------------------------------------------------
 // 3. merge as a launch of its own (large batches): workgroups per (request, kv head); only requests
 //    with more than one partition have work
 // ---------------------------------------------------------------------------------------------
@@ -739,6 +1020,14 @@ int launch_generic(const DecodeArgs& a, dim3 grid, hipStream_t st) {
     return KUN_OK;
 }
 
+int launch_generic_any(const kun_kv_pool* p, const DecodeArgs& a, dim3 grid, hipStream_t st) {
+    if (p->dtype == KUN_BF16)
+        return p->d == 128 ? launch_generic<bf16_t, 128>(a, grid, st) : launch_generic<bf16_t, 64>(a, grid, st);
+    if (p->dtype == KUN_FP8_E4M3)
+        return p->d == 128 ? launch_generic<fp8_t, 128>(a, grid, st) : launch_generic<fp8_t, 64>(a, grid, st);
+    return p->d == 128 ? launch_generic<float, 128>(a, grid, st) : launch_generic<float, 64>(a, grid, st);
+}
+
 // every row is its own request with one partition: item t = (t, 0)
 __global__ __launch_bounds__(256) void rows_plan_kernel(int T, int32_t* __restrict__ n_items,
                                                         int32_t* __restrict__ seq_first, int4* __restrict__ items,
@@ -791,11 +1080,7 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
                        a.seq_first, a.items, ctx_len);
     KUN_HIP_CHECK_LAUNCH();
     const dim3 grid((unsigned)((size_t)T * p->Hkv));
-    int rc;
-    if (p->dtype == KUN_BF16)
-        rc = p->d == 128 ? launch_generic<bf16_t, 128>(a, grid, st) : launch_generic<bf16_t, 64>(a, grid, st);
-    else
-        rc = p->d == 128 ? launch_generic<float, 128>(a, grid, st) : launch_generic<float, 64>(a, grid, st);
+    const int rc = launch_generic_any(p, a, grid, st);
     if (rc != KUN_OK) return rc;
     KUN_HIP_CHECK_LAUNCH();
     return KUN_OK;
@@ -843,7 +1128,7 @@ int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* bloc
     if (!q || !out || !block_table || !ctx_len || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
     const int G = Hq / p->Hkv;
     const bool generic_only = kun_options().decode_generic;
-    const bool mfma = p->dtype == KUN_BF16 && p->d == 128 && !generic_only;
+    const bool mfma = (p->dtype == KUN_BF16 || p->dtype == KUN_FP8_E4M3) && p->d == 128 && !generic_only;
     if (G < 1 || (G > 8 && !(G == 16 && mfma))) return KUN_ERR_UNSUPPORTED;   // 16 heads per KV head: the MFMA kernel only
     ub = default_bound(p, S, ub);
     const int P = choose_part_tokens(p, ub);
@@ -894,20 +1179,25 @@ int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* bloc
         const int nw = kun_options().decode_waves;
         a.xcd_map = !kun_options().decode_flat_map;
         if (a.xcd_map) grid = dim3((unsigned)(((size_t)lay.max_items + 7) / 8 * 8 * p->Hkv));
-        if (nw == 1) hipLaunchKernelGGL((decode_partial_mfma<1>), grid, dim3(64), 0, st, a);
-        else if (nw == 2) hipLaunchKernelGGL((decode_partial_mfma<2>), grid, dim3(128), 0, st, a);
-        else hipLaunchKernelGGL((decode_partial_mfma<4>), grid, dim3(256), 0, st, a);
-    } else if (p->dtype == KUN_BF16) {
-        rc = p->d == 128 ? launch_generic<bf16_t, 128>(a, grid, st) : launch_generic<bf16_t, 64>(a, grid, st);
+        if (p->dtype == KUN_FP8_E4M3) {
+            if (nw == 1) hipLaunchKernelGGL((decode_partial_mfma_fp8<1>), grid, dim3(64), 0, st, a);
+            else if (nw == 2) hipLaunchKernelGGL((decode_partial_mfma_fp8<2>), grid, dim3(128), 0, st, a);
+            else hipLaunchKernelGGL((decode_partial_mfma_fp8<4>), grid, dim3(256), 0, st, a);
+        } else {
+            if (nw == 1) hipLaunchKernelGGL((decode_partial_mfma<1>), grid, dim3(64), 0, st, a);
+            else if (nw == 2) hipLaunchKernelGGL((decode_partial_mfma<2>), grid, dim3(128), 0, st, a);
+            else hipLaunchKernelGGL((decode_partial_mfma<4>), grid, dim3(256), 0, st, a);
+        }
     } else {
-        rc = p->d == 128 ? launch_generic<float, 128>(a, grid, st) : launch_generic<float, 64>(a, grid, st);
+        rc = launch_generic_any(p, a, grid, st);
     }
     if (rc != KUN_OK) return rc;
     KUN_HIP_CHECK_LAUNCH();
     if (!a.fold) {
         const dim3 mgrid((unsigned)((size_t)S * p->Hkv * kMergeSlices));
-        if (p->dtype == KUN_BF16 && p->d == 128) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 128>), mgrid, dim3(256), 0, st, a);
-        else if (p->dtype == KUN_BF16) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 64>), mgrid, dim3(256), 0, st, a);
+        const bool out_bf16 = p->dtype != KUN_F32;     // outputs of bf16 and of FP8 pools are bf16
+        if (out_bf16 && p->d == 128) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 128>), mgrid, dim3(256), 0, st, a);
+        else if (out_bf16) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 64>), mgrid, dim3(256), 0, st, a);
         else if (p->d == 128) hipLaunchKernelGGL((decode_merge_kernel<float, 128>), mgrid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((decode_merge_kernel<float, 64>), mgrid, dim3(256), 0, st, a);
         KUN_HIP_CHECK_LAUNCH();

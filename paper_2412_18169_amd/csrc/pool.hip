@@ -117,7 +117,7 @@ int kun_kv_pool_create(kun_kv_pool** out, void* base, size_t bytes, int dtype, i
                        int head_dim, int block_size) {
     if (!out) return KUN_ERR_INVALID_ARG;
     *out = nullptr;
-    if (dtype != KUN_F32 && dtype != KUN_BF16) return KUN_ERR_INVALID_ARG;
+    if (dtype != KUN_F32 && dtype != KUN_BF16 && dtype != KUN_FP8_E4M3) return KUN_ERR_INVALID_ARG;
     if (num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0) return KUN_ERR_INVALID_ARG;
     if ((block_size != 16 && block_size != 32 && block_size != 64 && block_size != 128) || (head_dim != 64 && head_dim != 128))
         return KUN_ERR_UNSUPPORTED;
@@ -127,7 +127,7 @@ int kun_kv_pool_create(kun_kv_pool** out, void* base, size_t bytes, int dtype, i
     p->Hkv = num_kv_heads;
     p->d = head_dim;
     p->B = block_size;
-    p->elt = dtype == KUN_F32 ? 4 : 2;
+    p->elt = dtype == KUN_F32 ? 4 : dtype == KUN_BF16 ? 2 : 1;
     p->page_bytes = (size_t)2 * block_size * head_dim * p->elt;
     p->block_bytes = p->page_bytes * num_kv_heads;
     p->ranges.n = 0;

@@ -17,7 +17,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkun.so")
 
-KUN_F32, KUN_BF16 = 0, 1
+KUN_F32, KUN_BF16, KUN_FP8_E4M3 = 0, 1, 2
 KUN_MAX_RANGES = 16
 
 SYMBOLS = [

@@ -28,7 +28,7 @@ class DeviceWorkload:
         sh = w.shape
         self.ranges: List[torch.Tensor] = (ranges if ranges is not None
                                            else synth.alloc_ranges(w, self.dev, poison=poison))
-        dt = kun.KUN_F32 if sh.dtype == "f32" else kun.KUN_BF16
+        dt = {"f32": kun.KUN_F32, "bf16": kun.KUN_BF16, "fp8": kun.KUN_FP8_E4M3}[sh.dtype]
         r0 = self.ranges[0]
         r0_bytes = r0.numel() * r0.element_size() if create_bytes is None else int(create_bytes)
         self.pool = kun.kun_kv_pool_create(r0, r0_bytes, dt, sh.Hkv, sh.d, sh.B)
@@ -77,7 +77,7 @@ class DeviceWorkload:
             ctx_bound = int(self.w.decode_lens[:S].astype(np.int64).sum())
         need = kun.kun_decode_workspace_bytes(self.pool, S, sh.Hq, ctx_bound)
         if self._ws_dec is None or self._ws_dec.numel() < need:
-            self._ws_dec = torch.empty(need, dtype=torch.uint8, device=self.dev)
+            self._ws_dec = self._guarded(need, "dec")
         kun.kun_paged_decode(self.pool, self.q_dec, self.out_dec, self.dec_table,
                              self.dec_table.shape[1], self.dec_len, S, sh.Hq, sh.scale, ctx_bound,
                              self._ws_dec, self._ws_dec.numel(), stream)
@@ -90,7 +90,7 @@ class DeviceWorkload:
         need = kun.kun_prefill_workspace_bytes(self.pool, self.n_chunks, sh.Hq, self.total_new,
                                                self.pre_table.shape[1])
         if self._ws_pre is None or self._ws_pre.numel() < need:
-            self._ws_pre = torch.empty(max(need, 256), dtype=torch.uint8, device=self.dev)
+            self._ws_pre = self._guarded(max(need, 256), "pre")
         if max_workgroups > 0:
             kun.kun_paged_prefill_chunk_on(self.pool, self.q_pre, self.out_pre, self.q_start, self.prior,
                                            self.pre_table, self.pre_table.shape[1], self.n_chunks, sh.Hq,
@@ -117,6 +117,26 @@ class DeviceWorkload:
             done = torch.cuda.Event()
             done.record(st)
             cur.wait_event(done)
+
+    # ---- workspaces with guard words -----------------------------------------------------------
+    GUARD = 256          # bytes in front of and behind every workspace, filled with 0xA5
+
+    def _guarded(self, nbytes: int, name: str) -> torch.Tensor:
+        """A workspace of exactly nbytes (256-byte aligned) between two guard areas; check_guards()
+        tells whether a kernel wrote outside the size the library asked for."""
+        raw = torch.empty(nbytes + 2 * self.GUARD, dtype=torch.uint8, device=self.dev)
+        assert raw.data_ptr() % 256 == 0
+        raw[:self.GUARD] = 0xA5
+        raw[self.GUARD + nbytes:] = 0xA5
+        if not hasattr(self, "_guards"):
+            self._guards = {}
+        self._guards[name] = (raw, nbytes)
+        return raw[self.GUARD:self.GUARD + nbytes]
+
+    def check_guards(self) -> None:
+        for name, (raw, nbytes) in getattr(self, "_guards", {}).items():
+            ok = bool((raw[:self.GUARD] == 0xA5).all()) and bool((raw[self.GUARD + nbytes:] == 0xA5).all())
+            assert ok, f"a kernel wrote outside the {name} workspace of {nbytes} bytes"
 
     def close(self):
         if self.pool is not None:

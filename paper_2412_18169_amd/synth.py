@@ -303,10 +303,11 @@ SHAPE_8B = LayerShape(Hq=32, Hkv=8, d=128, B=16, dtype="bf16")
 SHAPE_70B = LayerShape(Hq=64, Hkv=8, d=128, B=16, dtype="bf16")
 
 
-def config(cfg: int, block_size: int = 0, q_heads: int = 0) -> Workload:
+def config(cfg: int, block_size: int = 0, q_heads: int = 0, kv_dtype: str = "") -> Workload:
     """The five benchmark configurations (1-based). Seeds are 1000 + cfg.  `block_size` (0 = the
     configuration's own, 16) builds the same requests over KV blocks of another size (32, 64, 128), `q_heads`
-    (0 = the configuration's own) with another number of query heads over the same KV heads."""
+    (0 = the configuration's own) with another number of query heads over the same KV heads, `kv_dtype`
+    ("" = the configuration's own) with pages of another element type ("fp8": E4M3 pages, bf16 queries)."""
     import dataclasses
     seed = 1000 + cfg
     sh = {1: SHAPE_TINY, 2: SHAPE_8B, 3: SHAPE_8B, 4: SHAPE_8B, 5: SHAPE_70B}.get(cfg, SHAPE_8B)
@@ -314,6 +315,8 @@ def config(cfg: int, block_size: int = 0, q_heads: int = 0) -> Workload:
         sh = dataclasses.replace(sh, B=block_size)
     if q_heads:
         sh = dataclasses.replace(sh, Hq=q_heads)
+    if kv_dtype:
+        sh = dataclasses.replace(sh, dtype=kv_dtype)
     if cfg == 1:
         w = Workload("tiny-decode-f32", 1, seed, sh,
                      np.array([17, 64, 200, 513], dtype=np.int32), [], [64 * 16 // sh.B])

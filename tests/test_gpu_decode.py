@@ -15,7 +15,7 @@ from paper_2412_18169_amd.runner import DeviceWorkload
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-5, "bf16": 2e-2}
+TOL = {"f32": 1e-5, "bf16": 2e-2, "fp8": 2e-2}    # FP8 pages: bf16 queries and outputs, the same bytes on both sides
 
 
 def oracle_pool(dw):
@@ -29,6 +29,7 @@ def check_decode(dw, seqs=None, tol=None, out=None):
     if out is None:
         out = dw.decode(seqs)
     torch.cuda.synchronize()
+    dw.check_guards()                                    # nothing was written outside the workspace asked for
     ref = O.paged_decode(oracle_pool(dw), synth.to_host_bits(dw.q_dec[:S]), w.table_array(range(w.S))[:S],
                          w.decode_lens[:S], sh.Hq, sh.scale)
     got = out[:S].double().cpu().numpy()
@@ -479,4 +480,82 @@ def test_merge_inside_the_partial_kernel_and_as_a_launch_of_its_own_give_the_sam
     bits = torch.int16 if dtype == "bf16" else torch.int32
     assert torch.equal(outs[0][live].view(bits), outs[1][live].view(bits))
     assert torch.equal(outs[0][live].view(bits), outs[2][live].view(bits))
+    dw.close()
+
+
+# ------------------------------------------------------------------------------------------
+# FP8 (E4M3) pages: half the bytes per token; queries and outputs bf16; same tolerance (the
+# oracle reads the same bytes)
+# ------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("kernel", ["mfma", "generic"])
+@pytest.mark.parametrize("G,d,B", [(4, 128, 16), (8, 128, 16), (1, 128, 64), (5, 128, 32), (16, 128, 16), (2, 64, 16), (8, 64, 128)])
+def test_fp8_pages_ragged_lengths(kernel, G, d, B):
+    if kernel == "generic":
+        if G == 16:
+            pytest.skip("16 query heads per KV head: the matrix-core kernel only")
+        kun.kun_set_option("KUN_DECODE_KERNEL", "generic")
+    elif d != 128:
+        pytest.skip("the matrix-core kernel covers head_dim 128 only")
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=B, dtype="fp8")
+    # lengths around tile (16), quad (64) and partition edges; several partitions for the long ones
+    lens = [1, 2, 15, 16, 17, 47, 48, 49, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 511, 513, 777, 1024, 1500, 0]
+    w = synth.custom_workload("fp8-ragged", sh, lens, extra_blocks=7, range_fracs=(0.3, 0.2, 0.5))
+    dw = DeviceWorkload(w)
+    for part in (None, "64", "96"):
+        kun.kun_set_option("KUN_DECODE_PART", part)
+        for waves in ((4, 1, 2) if kernel == "mfma" else (4,)):
+            kun.kun_set_option("KUN_DECODE_WAVES", waves)
+            dw.out_dec.fill_(float("nan"))
+            dw._ws_dec = None
+            check_decode(dw)
+    dw.close()
+
+
+def test_fp8_append_is_bit_exact_and_length_one_returns_v_exactly():
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="fp8")
+    lens = [1, 40, 17]
+    w = synth.custom_workload("fp8-append", sh, lens, extra_blocks=2, range_fracs=(0.5, 0.5))
+    dw = DeviceWorkload(w, fill=False)
+    opool = oracle_pool(dw)                            # NaN codes everywhere
+    ks, vs, seqs, poss = [], [], [], []
+    for s_, L in enumerate(lens):
+        k, v = synth.kv_logical(w, s_, 0, L, "cpu")
+        ks.append(k); vs.append(v); seqs += [s_] * L; poss += list(range(L))
+    k_new, v_new = torch.cat(ks).contiguous(), torch.cat(vs).contiguous()
+    order = np.random.default_rng(3).permutation(len(seqs))
+    k_new, v_new = k_new[order], v_new[order]
+    seqs, poss = np.asarray(seqs, dtype=np.int32)[order], np.asarray(poss, dtype=np.int32)[order]
+    table = w.table_array(range(w.S))
+    O.kv_append(opool, k_new.numpy(), v_new.numpy(), seqs, poss, table)
+    kun.kun_kv_append(dw.pool, k_new.cuda(), v_new.cuda(), torch.from_numpy(seqs).cuda(), torch.from_numpy(poss).cuda(),
+                      len(seqs), torch.from_numpy(table).cuda(), table.shape[1])
+    torch.cuda.synchronize()
+    for r in range(len(dw.ranges)):
+        assert np.array_equal(synth.to_host_bits(dw.ranges[r]).reshape(-1), opool.ranges[r])
+    out = dw.decode()
+    torch.cuda.synchronize()
+    check_decode(dw, out=out)
+    # a context of one token: the output is that token's V, exactly (E4M3 values are bf16 values)
+    _, v0 = synth.kv_logical(w, 0, 0, 1, "cpu")
+    want = v0.view(torch.float8_e4m3fn).to(torch.bfloat16)[0]           # [Hkv, d]
+    got = out[0].cpu().view(sh.Hkv, sh.G, sh.d)
+    for g in range(sh.G):
+        assert torch.equal(got[:, g].view(torch.int16), want.view(torch.int16))
+    dw.close()
+
+
+def test_fp8_scores_that_outgrow_the_running_maximum():
+    kun.kun_set_option("KUN_DECODE_PART", "256")
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="fp8")
+    lens = [700, 1300, 64, 2500, 201]
+    w = synth.custom_workload("fp8-grow", sh, lens, extra_blocks=0)
+    dw = DeviceWorkload(w, fill=False)
+    for s_, L in enumerate(lens):
+        k, v = synth.kv_logical(w, s_, 0, L, dw.dev)
+        t = torch.arange(L, device=dw.dev, dtype=torch.float32)
+        f = torch.where(t < 200, 0.05, 8.0) * torch.where(t >= 640, 4.0, 1.0)     # key magnitude jumps twice
+        k = (k.view(torch.float8_e4m3fn).float() * f[:, None, None]).to(torch.float8_e4m3fn).view(torch.uint8)
+        synth.write_pages(w, dw.ranges, s_, 0, L, k, v)
+    check_decode(dw)
     dw.close()

@@ -168,8 +168,11 @@ def test_seeded_random_shapes_lengths_and_pools(seed):
     dw.close()
 
 
-def test_config5_150GB_pool_sampled():
-    w = synth.config(5)
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
+def test_config5_150GB_pool_sampled(kv_dtype):
+    # sample: the 16 shortest, the 16 longest and 32 random decode requests, every head; first, last and
+    # 128 random rows of every chunk (FP8 pages: a quarter of that, its prefill runs on the vector ALUs)
+    w = synth.config(5, kv_dtype="" if kv_dtype == "bf16" else kv_dtype)
     dw = DeviceWorkload(w, poison=False)
     assert kun.kun_kv_pool_num_ranges(dw.pool) == 5
     assert kun.kun_kv_pool_num_blocks(dw.pool) * w.shape.block_bytes >= 149 * 10**9
@@ -179,7 +182,8 @@ def test_config5_150GB_pool_sampled():
     pre = dw.prefill().clone()
     out = dw.decode().clone()
     torch.cuda.synchronize()
-    rows = sample_rows(w, 8, 16)
+    dw.check_guards()
+    rows = sample_rows(w, 16, 32) if kv_dtype == "bf16" else sample_rows(w, 4, 8)
     err = decode_err(dw, out, rows)
     print(f"cfg5 decode ({len(rows)} sampled requests) max err {err:.3e}")
     assert err <= TOL
@@ -188,7 +192,7 @@ def test_config5_150GB_pool_sampled():
     got = pre.double().cpu().numpy()
     for i, (p, c) in enumerate(w.chunks):
         q0 = int(dw.q_start_host[i])
-        rws = sorted(set([0, c - 1] + rng.choice(c, size=16, replace=False).tolist()))
+        rws = sorted(set([0, c - 1] + rng.choice(c, size=128 if kv_dtype == "bf16" else 32, replace=False).tolist()))
         pool, tab = bridge.compact_pool(dw.ranges, w.range_blocks, [w.block_tables[w.S + i]], [p + c], sh.Hkv, sh.d,
                                         sh.B, sh.dtype)
         ref, _ = O.paged_prefill_chunk(pool, bridge.host_bits(dw.q_pre[q0:q0 + c]), tab[0], p, c, sh.Hq, sh.scale,

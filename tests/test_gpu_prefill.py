@@ -27,6 +27,7 @@ def check_prefill(dw, rows_per_chunk=None, seed=0, only=None):
     w, sh = dw.w, dw.w.shape
     out = dw.prefill()
     torch.cuda.synchronize()
+    dw.check_guards()                                    # nothing was written outside the workspace asked for
     got = out.double().cpu().numpy()
     assert np.isfinite(got).all()
     rng = np.random.default_rng(seed)
@@ -365,4 +366,17 @@ def test_config4_prefill_chunks_sampled_rows():
     dw = DeviceWorkload(w)
     err = check_prefill(dw, rows_per_chunk=48)
     print("cfg4 prefill max err", err)
+    dw.close()
+
+
+@pytest.mark.parametrize("G,d,B", [(4, 128, 16), (2, 64, 64)])
+def test_fp8_pages_run_on_the_vector_alu_kernel(G, d, B):
+    # prefill over FP8 (E4M3) pages: queries bf16, rows served one by one (correct to the same bar, not tuned)
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=B, dtype="fp8")
+    chunks = [(0, 1), (5, 1), (15, 16), (63, 65), (100, 40), (333, 20)]
+    w = synth.custom_workload("fp8-pre", sh, [3], chunks=chunks, extra_blocks=3, range_fracs=(0.5, 0.5))
+    dw = DeviceWorkload(w)
+    dw.out_pre.fill_(float("nan"))
+    err = check_prefill(dw)
+    print("max err", err)
     dw.close()

@@ -1,31 +1,94 @@
 // KV append: scatter the K/V rows of new tokens into their page slots through the block table.
 // A page is a row of tiles of 16 tokens; K rows are contiguous in a tile, V is stored transposed
-// ([dim][token]) behind them, so a token's V row becomes head_dim strided element stores.  Pure copy:
-// results are bit-exact.
+// ([dim][token]) behind them.  Pure copy: results are bit-exact.
 #include "kun_internal.h"
 
 namespace {
 
 constexpr int kTile = 16;       // tokens per tile of a page
 
-template <typename E>
+// Tokens that follow each other in the input AND in a page tile (same request, consecutive positions,
+// same 16-token tile) form a run: a prefill chunk is a sequence of runs of 16, one per tile, a decode
+// token is a run of 1.  A run is written by one workgroup: K rows as 16-byte copies, V staged in LDS
+// and written as whole V^T rows ([dim][16 tokens]: 32 contiguous bytes per dim in bf16) when the run
+// fills its tile, element by element otherwise.  (One 2-byte store per element, as a token-by-token
+// scatter does, made the memory system write five times the bytes moved.)
+//
+// Workgroup (b, kv head) owns the runs whose FIRST token has an input index in [16 b, 16 b + 16); such a
+// run ends at most 15 tokens later, so the workgroup looks at the 31 tokens from 16 b on.
+constexpr int kGroup = 16;                 // run heads per workgroup
+constexpr int kWindow = 2 * kGroup - 1;    // tokens a workgroup may have to move
+
+template <typename E, int D>
 __global__ __launch_bounds__(256) void kv_append_kernel(const KunRanges rt, const E* __restrict__ k_new,
                                                         const E* __restrict__ v_new,
                                                         const int32_t* __restrict__ seq_of_tok,
                                                         const int32_t* __restrict__ pos_of_tok,
                                                         const int32_t* __restrict__ table, int max_blocks,
-                                                        int T, int Hkv, int D, int B,
+                                                        int T, int Hkv, int B,
                                                         unsigned block_bytes, unsigned page_bytes) {
-    for (int i = blockIdx.x; i < T; i += gridDim.x) {
-        const int seq = seq_of_tok[i], pos = pos_of_tok[i];
-        const int blk = table[(size_t)seq * max_blocks + pos / B];
-        const int tile = (pos % B) / kTile, slot = pos % kTile;
-        char* block = kun_block_addr(rt, blk, block_bytes);
-        for (int x = threadIdx.x; x < Hkv * D; x += blockDim.x) {
-            const int h = x / D, j = x - h * D;
-            E* t = (E*)(block + (size_t)h * page_bytes) + (size_t)tile * (2 * kTile * D);
-            t[slot * D + j] = k_new[(size_t)i * Hkv * D + x];
-            t[kTile * D + j * kTile + slot] = v_new[(size_t)i * Hkv * D + x];
+    constexpr int CH = D * sizeof(E) / 16;             // 16-byte chunks per row
+    constexpr int VPR = kTile * sizeof(E) / 16;        // 16-byte stores per full V^T row
+    __shared__ char* s_tile[kWindow];                  // address of the token's page tile (this kv head)
+    __shared__ int s_slot[kWindow], s_head[kWindow];   // slot in the tile; input offset of the token's run head, or -1
+    __shared__ int s_len[kGroup];                      // length of the run that starts at offset t (0: none starts there)
+    __shared__ __attribute__((aligned(16))) E s_v[kWindow][D];
+    const int h = blockIdx.x % Hkv, base = (blockIdx.x / Hkv) * kGroup;
+    const int tid = threadIdx.x;
+    if (tid < kWindow) {
+        const int i = base + tid;
+        char* tile = nullptr;
+        int slot = 0, starts = 0;
+        if (i < T) {
+            const int seq = seq_of_tok[i], pos = pos_of_tok[i];
+            const int blk = table[(size_t)seq * max_blocks + pos / B];
+            tile = kun_block_addr(rt, blk, block_bytes) + (size_t)h * page_bytes +
+                   (size_t)((pos % B) / kTile) * (2 * kTile * D) * sizeof(E);
+            slot = pos % kTile;
+            // a run starts here unless the token before continues into this slot of this tile
+            starts = i == 0 || slot == 0 || seq_of_tok[i - 1] != seq || pos_of_tok[i - 1] != pos - 1;
+        }
+        s_tile[tid] = tile;
+        s_slot[tid] = slot;
+        s_head[tid] = (i < T && starts) ? tid : -1;
+    }
+    if (tid < kGroup) s_len[tid] = 0;
+    __syncthreads();
+    if (tid == 0) {
+        // runs whose head lies in [0, kGroup): tokens before the first head belong to the workgroup before
+        int head = -1;
+        for (int t = 0; t < kWindow; ++t) {
+            if (base + t >= T) { s_head[t] = -1; continue; }
+            if (s_head[t] == t) head = t < kGroup ? t : -1;
+            s_head[t] = head;
+            if (head >= 0) ++s_len[head];
+        }
+    }
+    __syncthreads();
+    // K rows and staging of V rows: 16-byte pieces
+    for (int x = tid; x < kWindow * CH; x += 256) {
+        const int t = x / CH, c = x % CH;
+        if (s_head[t] < 0) continue;
+        const size_t src = ((size_t)(base + t) * Hkv + h) * D * sizeof(E) + (size_t)c * 16;
+        *(uint4*)(s_tile[t] + (size_t)s_slot[t] * D * sizeof(E) + c * 16) = *(const uint4*)((const char*)k_new + src);
+        *(uint4*)((char*)&s_v[t][0] + c * 16) = *(const uint4*)((const char*)v_new + src);
+    }
+    __syncthreads();
+    // V^T: thread = (run head, dim)
+    for (int x = tid; x < kGroup * D; x += 256) {
+        const int hd = x / D, j = x % D;
+        const int len = s_len[hd];
+        if (len == 0) continue;
+        E* row = (E*)(s_tile[hd] + (size_t)kTile * D * sizeof(E)) + (size_t)j * kTile;
+        if (len == kTile) {                            // the run fills its tile: one whole row
+            union { E e[kTile]; uint4 u[VPR]; } r;
+#pragma unroll
+            for (int t = 0; t < kTile; ++t) r.e[t] = s_v[hd + t][j];
+#pragma unroll
+            for (int c = 0; c < VPR; ++c) ((uint4*)row)[c] = r.u[c];
+        } else {
+            const int slot0 = s_slot[hd];
+            for (int t = 0; t < len; ++t) row[slot0 + t] = s_v[hd + t][j];
         }
     }
 }
@@ -77,23 +140,16 @@ extern "C" int kun_kv_append(kun_kv_pool* p, const void* k_new, const void* v_ne
     if (T == 0) return KUN_OK;
     if (!k_new || !v_new || !seq_of_tok || !pos_of_tok || !block_table || max_blocks <= 0)
         return KUN_ERR_INVALID_ARG;
-    const dim3 grid((unsigned)(T < 65536 ? T : 65536));
+    const dim3 grid((unsigned)((size_t)((T + kGroup - 1) / kGroup) * p->Hkv));
     hipStream_t st = (hipStream_t)stream;
-    if (p->elt == 1)
-        hipLaunchKernelGGL(kv_append_kernel<uint8_t>, grid, dim3(256), 0, st, p->ranges,
-                           (const uint8_t*)k_new, (const uint8_t*)v_new, seq_of_tok, pos_of_tok,
-                           block_table, max_blocks, T, p->Hkv, p->d, p->B, (unsigned)p->block_bytes,
-                           (unsigned)p->page_bytes);
-    else if (p->elt == 2)
-        hipLaunchKernelGGL(kv_append_kernel<uint16_t>, grid, dim3(256), 0, st, p->ranges,
-                           (const uint16_t*)k_new, (const uint16_t*)v_new, seq_of_tok, pos_of_tok,
-                           block_table, max_blocks, T, p->Hkv, p->d, p->B, (unsigned)p->block_bytes,
-                           (unsigned)p->page_bytes);
-    else
-        hipLaunchKernelGGL(kv_append_kernel<uint32_t>, grid, dim3(256), 0, st, p->ranges,
-                           (const uint32_t*)k_new, (const uint32_t*)v_new, seq_of_tok, pos_of_tok,
-                           block_table, max_blocks, T, p->Hkv, p->d, p->B, (unsigned)p->block_bytes,
-                           (unsigned)p->page_bytes);
+#define KUN_APPEND(E, DD)                                                                                          \
+    hipLaunchKernelGGL((kv_append_kernel<E, DD>), grid, dim3(256), 0, st, p->ranges, (const E*)k_new,              \
+                       (const E*)v_new, seq_of_tok, pos_of_tok, block_table, max_blocks, T, p->Hkv, p->B,          \
+                       (unsigned)p->block_bytes, (unsigned)p->page_bytes)
+    if (p->elt == 1) { if (p->d == 128) KUN_APPEND(uint8_t, 128); else KUN_APPEND(uint8_t, 64); }
+    else if (p->elt == 2) { if (p->d == 128) KUN_APPEND(uint16_t, 128); else KUN_APPEND(uint16_t, 64); }
+    else { if (p->d == 128) KUN_APPEND(uint32_t, 128); else KUN_APPEND(uint32_t, 64); }
+#undef KUN_APPEND
     KUN_HIP_CHECK_LAUNCH();
     return KUN_OK;
 }

@@ -559,3 +559,45 @@ def test_fp8_scores_that_outgrow_the_running_maximum():
         synth.write_pages(w, dw.ranges, s_, 0, L, k, v)
     check_decode(dw)
     dw.close()
+
+
+@pytest.mark.parametrize("dtype,d,B", [("bf16", 128, 16), ("bf16", 128, 64), ("f32", 64, 16), ("fp8", 128, 32), ("fp8", 64, 16)])
+@pytest.mark.parametrize("order", ["chunks", "reversed-blocks", "interleaved"])
+def test_kv_append_of_runs_is_bit_exact(dtype, d, B, order):
+    # Tokens that follow each other in the input and in a page tile are moved as one run (whole V^T rows
+    # when the run fills its tile).  Chunks that begin and end inside a tile, chunks shorter than a
+    # tile, decode tokens between them, input offsets that are no multiple of 16, runs cut by the order.
+    sh = synth.LayerShape(Hq=4, Hkv=4, d=d, B=B, dtype=dtype)
+    chunks = [(5, 40), (16, 16), (31, 70), (0, 3), (64, 129), (7, 1)]
+    w = synth.custom_workload("runs", sh, [37, 1, 16, 250, 99], chunks=chunks, extra_blocks=5, range_fracs=(0.5, 0.5))
+    dw = DeviceWorkload(w, fill=False)
+    pieces = []                                        # (seq, first position, count): tokens in input order
+    for s_ in range(w.S):
+        pieces.append((s_, int(w.decode_lens[s_]) - 1, 1))          # the decode requests' newest token
+    for i, (p, c) in enumerate(chunks):
+        pieces.append((w.S + i, p, c))
+    if order == "interleaved":                         # a decode token after every chunk, and one chunk cut in two
+        pieces = [pieces[5], pieces[0], pieces[6], pieces[1], (w.S + 2, 31, 33), pieces[2], (w.S + 2, 64, 37), pieces[3],
+                  pieces[8], pieces[9], pieces[4], pieces[10]]
+    seqs, poss = [], []
+    for s_, p0, c in pieces:
+        seqs += [s_] * c
+        poss += list(range(p0, p0 + c))
+    seqs, poss = np.asarray(seqs, dtype=np.int32), np.asarray(poss, dtype=np.int32)
+    if order == "reversed-blocks":                     # blocks of 5 tokens in reverse order: short runs, odd offsets
+        idx = np.concatenate([np.arange(i, min(i + 5, len(seqs))) for i in range(0, len(seqs), 5)][::-1])
+        seqs, poss = seqs[idx], poss[idx]
+    ks, vs = [], []
+    for s_, t in zip(seqs.tolist(), poss.tolist()):
+        k, v = synth.kv_logical(w, s_, t, t + 1)
+        ks.append(k); vs.append(v)
+    k_new, v_new = torch.cat(ks).contiguous(), torch.cat(vs).contiguous()
+    table = w.table_array(range(len(w.seq_lens)))
+    opool = oracle_pool(dw)                            # poisoned pages
+    O.kv_append(opool, synth.to_host_bits(k_new), synth.to_host_bits(v_new), seqs, poss, table)
+    kun.kun_kv_append(dw.pool, k_new.cuda(), v_new.cuda(), torch.from_numpy(seqs).cuda(), torch.from_numpy(poss).cuda(),
+                      len(seqs), torch.from_numpy(table).cuda(), table.shape[1])
+    torch.cuda.synchronize()
+    for r in range(len(dw.ranges)):
+        assert np.array_equal(synth.to_host_bits(dw.ranges[r]).reshape(-1), opool.ranges[r], equal_nan=True)
+    dw.close()

@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--cost-model", action="store_true",
                     help="also fit the chunk cost model (prefix + self attention pairs, tokens, constant) to "
                          "measured prefill calls and report its error on held-out microbatches")
+    ap.add_argument("--prefill-scaling", action="store_true",
+                    help="also run long equal prefill items on all, 128 and 64 compute units and report the rate "
+                         "per compute unit and the shader clock (rocm-smi) of each: is the chip power-limited?")
     ap.add_argument("--vmm", action="store_true",
                     help="also time the decode step over the same pool built as ONE virtual range that grew "
                          "chunk by chunk, and the mapping calls themselves")
@@ -213,6 +216,8 @@ def main():
     if has_prefill and not args.pmc_calibration and not args.no_mixed:
         out["mixed"] = mixed_batch(dw, args.steps)
 
+    if args.prefill_scaling:
+        out["prefill_scaling"] = prefill_scaling_report(sh)
     if args.vmm:
         out["vmm"] = vmm_report(dw, args.steps)
     if args.cost_model:
@@ -275,6 +280,66 @@ def mixed_batch(dw, steps, prefill_workgroups=256):
             "prefill_workgroups": prefill_workgroups}
 
 
+def prefill_scaling_report(sh, seconds=2.0):
+    """Four chunks of 1024 tokens after 30 000 prior tokens each (long, equal work items: the tile loop
+    in steady state) through kun_paged_prefill_chunk_on with 256, 128 and 64 fetching workgroups (one per
+    compute unit): Tflop/s, the same scaled to 256 compute units, and the shader clock rocm-smi shows
+    while the kernel loops.  Equal rates per compute unit would mean the tile loop sets the pace; a rate
+    that rises as compute units go idle, with the clock, means the chip's power limit does."""
+    import json as _json
+    import subprocess
+    import threading
+    import torch
+    from paper_2412_18169_amd import synth
+    from paper_2412_18169_amd.runner import DeviceWorkload
+    w = synth.custom_workload("prefill-scaling", sh, [16], chunks=[(30000, 1024)] * 4, seed=78, extra_blocks=2)
+    dw = DeviceWorkload(w, poison=False)
+    fl = prefill_flops(w)
+    clocks, stop = [], [False]
+
+    def poll():
+        while not stop[0]:
+            try:
+                o = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=5).stdout
+                c = _json.loads(o).get("card0", {})
+                mhz = [int("".join(ch for ch in v if ch.isdigit())) for k, v in c.items() if k.startswith("sclk clock speed")]
+                if mhz:
+                    clocks.append((time.time(), mhz[0]))
+            except Exception:
+                pass
+            time.sleep(0.05)
+
+    th = threading.Thread(target=poll, daemon=True)
+    th.start()
+    rows = []
+    for wgs in (0, 256, 128, 64):
+        for _ in range(3):
+            dw.prefill(max_workgroups=wgs)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        n = 0
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        while time.time() - t0 < seconds:
+            for _ in range(10):
+                dw.prefill(max_workgroups=wgs)
+            torch.cuda.synchronize()
+            n += 10
+        b.record()
+        torch.cuda.synchronize()
+        t1 = time.time()
+        ms = a.elapsed_time(b) / n
+        mid = sorted(m for t, m in clocks if t0 + 0.5 < t < t1)
+        cus = wgs or 256
+        rows.append({"workgroups": wgs or "one per item", "ms": round(ms, 4),
+                     "TFLOP_per_s": round(fl / ms / 1e9, 1),
+                     "TFLOP_per_s_per_256_CUs": round(fl / ms / 1e9 * 256 / cus, 1),
+                     "sclk_MHz_median": mid[len(mid) // 2] if mid else None})
+    stop[0] = True
+    dw.close()
+    return {"chunks": "4 x (30000 prior, 1024 new)", "flops": fl, "runs": rows}
+
+
 def cost_model_report(sh, reps=10):
     """Times kun_paged_prefill_chunk on microbatches of 1-4 chunks over a grid of (prior, chunk) sizes,
     fits the three constants of the chunk cost model with kun_cost_fit on two thirds of them and
@@ -335,9 +400,15 @@ def cost_model_report(sh, reps=10):
         pred = kun.kun_cost_microbatch(model, mbs[k])
         err.append(abs(pred - times[k]) / times[k])
         err_tok.append(abs(tb * sum(c for _, _, c in mbs[k]) + tg - times[k]) / times[k])
+    ktest = sorted(test)
+    worst = ktest[int(np.argmax(err))]
     return {"alpha_s_per_pair": model[0], "beta_s_per_token": model[1], "gamma_s": model[2],
             "fitted_on": len(train), "held_out": len(test),
             "rel_err_mean": round(float(np.mean(err)), 4), "rel_err_max": round(float(np.max(err)), 4),
+            "held_out_within_5_percent": int(sum(e < 0.05 for e in err)),
+            "worst_held_out": {"chunks_prior_tokens": [(p_, c_) for _, p_, c_ in mbs[worst]],
+                               "measured_ms": round(times[worst] * 1e3, 4),
+                               "predicted_ms": round(kun.kun_cost_microbatch(model, mbs[worst]) * 1e3, 4)},
             "token_count_model_rel_err_mean": round(float(np.mean(err_tok)), 4),
             "token_count_model_rel_err_max": round(float(np.max(err_tok)), 4),
             "shape": {"Hq": sh.Hq, "Hkv": sh.Hkv, "head_dim": sh.d}}

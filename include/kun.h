@@ -39,9 +39,9 @@
  *   num_q_heads / num_kv_heads = 1 .. 8 (e.g. 40 query heads over 8 KV heads), or 16 with bf16 and
  *   head_dim 128 (e.g. 64 over 4); dtype f32, bf16 or FP8 E4M3 pages with bf16 queries
  *   (accumulation is always fp32).  Anything else is KUN_ERR_UNSUPPORTED.  bf16 with head_dim 128
- *   runs on the matrix cores (decode and prefill), and so does decode over FP8 pages with head_dim
- *   128 (16 query heads per KV head included); the other combinations -- prefill over FP8 pages
- *   among them -- run on vector-ALU kernels that are correct to the same bar but not tuned.
+ *   runs on the matrix cores (decode and prefill), and so do FP8 pages with head_dim 128 (16 query
+ *   heads per KV head included); the other combinations run on vector-ALU kernels that are correct
+ *   to the same bar but not tuned.
  */
 #ifndef KUN_H
 #define KUN_H
@@ -222,9 +222,9 @@ KUN_API size_t kun_prefill_workspace_bytes(const kun_kv_pool* pool, int n_chunks
  * back to back; q_start: device int32 [n_chunks + 1], row offsets with q_start[n_chunks] ==
  * total_new_tokens; prior_len: device int32 [n_chunks]; block_table: device int32
  * [n_chunks, max_blocks], row i covering the p_i + c_i tokens of chunk i's request.  Row r of
- * chunk i sees logical keys 0 .. p_i + r.  A chunk with c == 0 is skipped.  bf16 pools with
- * head_dim 128 run on the matrix cores; fp32 and head_dim 64 pools are served row by row by the
- * vector-ALU decode kernel (correct to the same bar, not tuned). */
+ * chunk i sees logical keys 0 .. p_i + r.  A chunk with c == 0 is skipped.  bf16 and FP8 pools with
+ * head_dim 128 run on the matrix cores (q, out of FP8 pools: bf16); fp32 and head_dim 64 pools are
+ * served row by row by the vector-ALU decode kernel (correct to the same bar, not tuned). */
 KUN_API int kun_paged_prefill_chunk(kun_kv_pool* pool, const void* q, void* out, const int32_t* q_start,
                             const int32_t* prior_len, const int32_t* block_table, int max_blocks,
                             int n_chunks, int num_q_heads, int total_new_tokens, float scale,

@@ -76,6 +76,21 @@ struct PrefillArgs {
     int sub_shift;           // log2 of the 16-token page tiles per KV block (0 .. 3): page tile i of a request is tile i % 2^shift of block i >> shift
 };
 
+// sixteen FP8 (E4M3) codes -> two MFMA operands of eight bf16 each (codes 0..7, codes 8..15); exact
+__device__ __forceinline__ void fp8x16_to_bf16(const uint4& x, Frag& lo, Frag& hi) {
+    union { bf16x2 h; unsigned u; } c[8];
+    c[0].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.x, 1.0f, false);
+    c[1].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.x, 1.0f, true);
+    c[2].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.y, 1.0f, false);
+    c[3].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.y, 1.0f, true);
+    c[4].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.z, 1.0f, false);
+    c[5].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.z, 1.0f, true);
+    c[6].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.w, 1.0f, false);
+    c[7].h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x.w, 1.0f, true);
+    lo.u = make_uint4(c[0].u, c[1].u, c[2].u, c[3].u);
+    hi.u = make_uint4(c[4].u, c[5].u, c[6].u, c[7].u);
+}
+
 // max of three floats in one instruction.  Plain fmaxf makes the compiler canonicalise every MFMA
 // output first (one extra v_max per value); the instruction itself already handles NaN inputs.
 // The compiler does not add the wait states an MFMA result needs before a vector ALU reads it when
@@ -112,7 +127,7 @@ constexpr int kSplitRows = 256;         // rows of a workgroup of the kernels th
 // head 0.  Entries past a chunk's context are not written (their table entries may hold anything).
 __device__ void resolve_tiles(const KunRanges& rt, const int32_t* __restrict__ q_start,
                               const int32_t* __restrict__ prior, const int32_t* __restrict__ table, int n_chunks,
-                              int max_blocks, int sub_shift, unsigned block_bytes,
+                              int max_blocks, int sub_shift, unsigned block_bytes, unsigned tile_bytes,
                               unsigned long long* __restrict__ page_addr, int first_wg, int n_wgs) {
     const int tiles_per_row = max_blocks << sub_shift;
     const long long total = (long long)n_chunks * tiles_per_row;
@@ -123,7 +138,7 @@ __device__ void resolve_tiles(const KunRanges& rt, const int32_t* __restrict__ q
         if (t * kBlock >= ctx || q_start[ch + 1] == q_start[ch]) continue;
         const int id = table[(size_t)ch * max_blocks + (t >> sub_shift)];
         page_addr[e] = (unsigned long long)kun_block_addr(rt, id, block_bytes) +
-                       (unsigned)(t & ((1 << sub_shift) - 1)) * 8192u;
+                       (unsigned)(t & ((1 << sub_shift) - 1)) * tile_bytes;
     }
 }
 
@@ -132,7 +147,7 @@ struct ResolveArgs {
     const int32_t* table;
     unsigned long long* page_addr;
     int max_blocks, sub_shift, n_wgs;
-    unsigned block_bytes;
+    unsigned block_bytes, tile_bytes;     // tile_bytes: K and V^T of one 16-token page tile (8192 in bf16, 4096 in FP8)
 };
 
 __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const ResolveArgs ra, const int32_t* __restrict__ q_start,
@@ -148,7 +163,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const Resolv
                                                                   int4* __restrict__ desc) {
     if (blockIdx.x > 0) {      // workgroups 1 .. n_wgs resolve the blocks; workgroup 0 makes the work list
         resolve_tiles(ra.rt, q_start, prior, ra.table, n_chunks, ra.max_blocks, ra.sub_shift, ra.block_bytes,
-                      ra.page_addr, 1, ra.n_wgs);
+                      ra.tile_bytes, ra.page_addr, 1, ra.n_wgs);
         return;
     }
     // everything a workgroup needs to know about list entry i, so that it starts with one lookup
@@ -667,11 +682,21 @@ void prefill_ring_kernel(const PrefillArgs a) {
 // (sched_group_barrier); the first four fragments are requested in the vector phase before, so the
 // phase runs at the rate of the matrix pipe from its first instruction.
 // ---------------------------------------------------------------------------------------------
-template <int G, bool PERSIST>
+//
+// F8: the pages hold FP8 (E4M3) codes, one byte per element (queries and outputs stay bf16).  A stage is
+// half as large (K [64 keys][128 B], then V^T [4 page tiles][128 dims][16 B]), a wave brings half of ONE
+// page tile per stage (two loads per lane), and a 16-byte LDS read is sixteen elements = the operands
+// of two MFMAs after conversion to bf16 in the matrix phase (exact).  The contraction over head_dim is
+// permuted to what a 16-byte read of a K row holds (k-steps 2c and 2c + 1 = dims 32c + 16 jh .. + 16, Q
+// loaded in the same order), and S^T rows are mapped to keys so that a lane holds all 16 tokens of one
+// page tile: a 16-byte V^T row of that tile then feeds its two PV MFMAs.
+template <int G, bool PERSIST, bool F8>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void prefill_pp_kernel(const PrefillArgs a) {
     constexpr int NW = 8, ROWS_W = 32, ROWS = NW * ROWS_W, POS = ROWS / G, LIVE = POS * G;
-    constexpr int NSTAGE = 4, STAGE_BYTES = 2 * kBlocksPerTile * 4096, V_OFF = kBlocksPerTile * 4096;
+    constexpr int TILE_B = F8 ? 2048 : 4096;           // bytes of K (or of V^T) of one 16-token page tile
+    constexpr int NSTAGE = 4, STAGE_BYTES = 2 * kBlocksPerTile * TILE_B, V_OFF = kBlocksPerTile * TILE_B;
+    constexpr int LPS = F8 ? 2 : 4;                    // loads per lane and stage
 #ifndef KUN_PP_AHEAD
 #define KUN_PP_AHEAD 4
 #endif
@@ -712,16 +737,22 @@ void prefill_pp_kernel(const PrefillArgs a) {
     const kun_caddr arow = (kun_caddr)(a.page_addr + (size_t)chunk * a.tiles_per_row);
     const int ntile_ctx = (ctx + kBlock - 1) / kBlock;
     const int slot = (wave & 3) * 64 + lane;
-    const unsigned k_src = kvh * a.page_bytes + (slot >> 4) * 256 + (((slot & 15) ^ (slot >> 4)) * 16);
-    const unsigned v_src = kvh * a.page_bytes + 4096 + ((slot ^ ((slot >> 4) & 1)) * 16);
+    // bf16: this lane fills 16-byte slot `slot` of a page tile's K and V^T (K chunk XOR row, V^T halves swapped).
+    // F8: wave w brings half w % 2 of page tile w / 2: K rows 8 (w % 2) + lane / 8, 16-byte chunk lane % 8
+    // XOR row; V^T rows (dims) 64 (w % 2) + lane as they are.
+    const unsigned k_src = F8 ? kvh * a.page_bytes + (8 * (wave & 1) + (lane >> 3)) * 128 + (((lane & 7) ^ (lane >> 3)) * 16)
+                              : kvh * a.page_bytes + (slot >> 4) * 256 + (((slot & 15) ^ (slot >> 4)) * 16);
+    const unsigned v_src = F8 ? kvh * a.page_bytes + 2048 + (64 * (wave & 1) + lane) * 16
+                              : kvh * a.page_bytes + 4096 + ((slot ^ ((slot >> 4) & 1)) * 16);
     auto dma16 = [&](unsigned long long page, unsigned off, unsigned lds_addr) {
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(page), "s"(lds_addr)
                      : "memory", "m0");
     };
     const unsigned ring_addr = (unsigned)(size_t)(kun_lptr)&ring[0][0];
-    // page tiles wave / 4 and wave / 4 + 2 of key tile j (relative to kt0), clamped into the context
+    // bf16: page tiles wave / 4 and wave / 4 + 2 of key tile j (relative to kt0); F8: page tile wave / 2;
+    // clamped into the context
     auto tile_addr = [&](int j, int i) -> unsigned long long {
-        int lb = (kt0 + j) * kBlocksPerTile + (wave_u >> 2) + 2 * i;
+        int lb = (kt0 + j) * kBlocksPerTile + (F8 ? (wave_u >> 1) : (wave_u >> 2) + 2 * i);
         lb = lb < 0 ? 0 : lb;
         return arow[lb < ntile_ctx ? lb : ntile_ctx - 1];
     };
@@ -730,25 +761,31 @@ void prefill_pp_kernel(const PrefillArgs a) {
     unsigned long long kpg0 = tile_addr(0, 0), kpg1 = tile_addr(0, 1), vpg0 = kpg0, vpg1 = kpg1;
     int next_t = 0;                                    // next stage to request
     auto issue = [&]() {
-        const unsigned st = ring_addr + (next_t % NSTAGE) * STAGE_BYTES + (wave_u & 3) * 1024;
-        const unsigned dst0 = st + (wave_u >> 2) * 4096, dst1 = dst0 + 2 * 4096;
-        dma16(kpg0, k_src, dst0);
-        dma16(vpg0, v_src, dst0 + V_OFF);
-        dma16(kpg1, k_src, dst1);
-        dma16(vpg1, v_src, dst1 + V_OFF);
+        if (F8) {
+            const unsigned dst = ring_addr + (next_t % NSTAGE) * STAGE_BYTES + (wave_u >> 1) * TILE_B + (wave_u & 1) * 1024;
+            dma16(kpg0, k_src, dst);
+            dma16(vpg0, v_src, dst + V_OFF);
+        } else {
+            const unsigned st = ring_addr + (next_t % NSTAGE) * STAGE_BYTES + (wave_u & 3) * 1024;
+            const unsigned dst0 = st + (wave_u >> 2) * 4096, dst1 = dst0 + 2 * 4096;
+            dma16(kpg0, k_src, dst0);
+            dma16(vpg0, v_src, dst0 + V_OFF);
+            dma16(kpg1, k_src, dst1);
+            dma16(vpg1, v_src, dst1 + V_OFF);
+        }
         vpg0 = kpg0;
         vpg1 = kpg1;
         ++next_t;
         kpg0 = tile_addr(next_t, 0);
-        kpg1 = tile_addr(next_t, 1);
+        if (!F8) kpg1 = tile_addr(next_t, 1);
     };
     // stages 0 .. nt exist; `landed(t)`: this lane's loads of stage t are complete (stages are requested
     // in order, four loads each, so everything but the 4 * (next_t - 1 - t) youngest loads is waited for)
     auto landed = [&](int t) {
         const int younger = next_t - 1 - t;
-        if (younger >= 3) KUN_WAIT_VMCNT(12);
-        else if (younger == 2) KUN_WAIT_VMCNT(8);
-        else if (younger == 1) KUN_WAIT_VMCNT(4);
+        if (younger >= 3) KUN_WAIT_VMCNT(3 * LPS);
+        else if (younger == 2) KUN_WAIT_VMCNT(2 * LPS);
+        else if (younger == 1) KUN_WAIT_VMCNT(LPS);
         else KUN_WAIT_VMCNT(0);
     };
 
@@ -767,7 +804,8 @@ void prefill_pp_kernel(const PrefillArgs a) {
     {
         const char* qrow = (const char*)a.q + (((size_t)(qs + pos)) * a.Hq + kvh * G + g_head) * (D * 2);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[ks].u = *(const uint4*)(qrow + (2 * ks + jh) * 16);
+        for (int ks = 0; ks < 8; ++ks)
+            qf[ks].u = *(const uint4*)(qrow + (F8 ? 2 * (32 * (ks >> 1) + 16 * jh + 8 * (ks & 1)) : (2 * ks + jh) * 16));
     }
     const int wave_vis_min = p + min(wpos0, c - 1);
 
@@ -778,10 +816,13 @@ void prefill_pp_kernel(const PrefillArgs a) {
         for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
     float m = -INFINITY, l = 0.f;                      // m in log2 units
 
-    const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
-    const int krow_blk = krow >> 4, krow_in = krow & 15;
-    const unsigned k_lane = krow_blk * 4096 + krow_in * 256;
-    const unsigned v_lane = V_OFF + n * 32 + ((jh ^ ((n >> 3) & 1)) * 16);
+    // key (inside a 32-key sub-tile) of row n of an S^T tile.  bf16: accumulator register i of a lane is
+    // key 16 (i / 8) + 8 jh + i % 8; F8: key 16 jh + i (a lane holds the 16 tokens of one page tile).
+    const int krow = F8 ? 16 * ((n >> 2) & 1) + 4 * (n >> 3) + (n & 3)
+                        : 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
+    const int krow_blk = krow >> 4, krow_in = F8 ? (krow & 7) : (krow & 15);
+    const unsigned k_lane = F8 ? krow * 128 : krow_blk * 4096 + krow_in * 256;
+    const unsigned v_lane = F8 ? V_OFF + jh * 2048 + n * 16 : V_OFF + n * 32 + ((jh ^ ((n >> 3) & 1)) * 16);
     const float sl2 = a.scale_log2;
 
     f32x16 sa, sb;                                     // S^T of the tile between its M and its V phase
@@ -793,6 +834,7 @@ void prefill_pp_kernel(const PrefillArgs a) {
     // used kPre MFMAs later.
     Frag vpre[kPre];
     auto prefetch_v = [&](int t) {
+        if (F8) return;                                // (the FP8 matrix phase reads all its fragments itself)
         const unsigned char* vbase = &ring[t % NSTAGE][0] + v_lane;
 #pragma unroll
         for (int i = 0; i < kPre; ++i) vpre[i].u = *(const uint4*)(vbase + (i >> 2) * 4096 + (i & 3) * 1024);
@@ -802,6 +844,61 @@ void prefill_pp_kernel(const PrefillArgs a) {
         const unsigned char* vbase = stage + v_lane;
         const unsigned char* kbase = stage + k_lane;
         constexpr bool PV = decltype(do_pv)::value, QK = decltype(do_qk)::value;
+        if constexpr (F8) {
+            // sixteen raw reads (8 of V^T: sub-tile x 32 dims; 8 of K: sub-tile x chunk), each converted to
+            // the operands of two MFMAs
+            uint4 vraw[2][4], kraw[2][4];
+            if (PV) {
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                    for (int dt = 0; dt < 4; ++dt) vraw[sub][dt] = *(const uint4*)(vbase + sub * 4096 + dt * 512);
+            }
+            if (QK) {
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+                    for (int sub = 0; sub < 2; ++sub)
+                        kraw[sub][cc] = *(const uint4*)(kbase + sub * 4096 + (((2 * cc + jh) ^ krow_in) * 16));
+            }
+            if (PV) {
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                    for (int dt = 0; dt < 4; ++dt) {
+                        Frag lo, hi, p0, p1;
+                        fp8x16_to_bf16(vraw[sub][dt], lo, hi);
+                        p0.u = cv.u[2 * sub];
+                        p1.u = cv.u[2 * sub + 1];
+                        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.v, p0.v, o[dt], 0, 0, 0);
+                        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi.v, p1.v, o[dt], 0, 0, 0);
+                    }
+            }
+            if (QK) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { sa[i] = 0.f; sb[i] = 0.f; }
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    Frag lo, hi;
+                    fp8x16_to_bf16(kraw[0][cc], lo, hi);
+                    sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.v, qf[2 * cc].v, sa, 0, 0, 0);
+                    sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi.v, qf[2 * cc + 1].v, sa, 0, 0, 0);
+                    fp8x16_to_bf16(kraw[1][cc], lo, hi);
+                    sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.v, qf[2 * cc].v, sb, 0, 0, 0);
+                    sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi.v, qf[2 * cc + 1].v, sb, 0, 0, 0);
+                }
+            }
+            // two reads ahead, then per fragment: its eight conversions, its two MFMAs, the next read
+            constexpr int NF = (PV ? 8 : 0) + (QK ? 8 : 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+            for (int i = 0; i < NF; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                if (i + 2 < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            return;
+        }
         Frag vf[16], ka[8], kb[8];
         if (PV) {
 #pragma unroll
@@ -850,6 +947,27 @@ void prefill_pp_kernel(const PrefillArgs a) {
     auto pv_tail = [&](int t) {
         const unsigned char* vbase = &ring[t % NSTAGE][0] + v_lane;
         const int key0 = (kt0 + t - 1) * BN;
+        if constexpr (F8) {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) {
+                    Frag vh[2], pb[2];
+                    fp8x16_to_bf16(*(const uint4*)(vbase + sub * 4096 + dt * 512), vh[0], vh[1]);
+                    const int t0 = key0 + 32 * sub + 16 * jh;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        unsigned x[4] = {vh[h].u.x, vh[h].u.y, vh[h].u.z, vh[h].u.w};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (t0 + 8 * h + e >= ctx) x[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                        vh[h].u = make_uint4(x[0], x[1], x[2], x[3]);
+                        pb[h].u = cv.u[2 * sub + h];
+                        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vh[h].v, pb[h].v, o[dt], 0, 0, 0);
+                    }
+                }
+            return;
+        }
 #pragma unroll
         for (int h = 0; h < 4; ++h) {
             Frag pb;
@@ -898,7 +1016,7 @@ void prefill_pp_kernel(const PrefillArgs a) {
             if (!plain) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int key = kt * BN + 16 * (i >> 3) + 8 * jh + (i & 7);
+                    const int key = F8 ? kt * BN + 16 * jh + i : kt * BN + 16 * (i >> 3) + 8 * jh + (i & 7);
                     if (key > vis) sa[i] = -INFINITY;
                     if (key + 32 > vis) sb[i] = -INFINITY;
                 }
@@ -1072,7 +1190,7 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(const int32_t* __rest
     }
 }
 
-bool mfma_shape(const kun_kv_pool* p) { return p->dtype == KUN_BF16 && p->d == 128; }
+bool mfma_shape(const kun_kv_pool* p) { return (p->dtype == KUN_BF16 || p->dtype == KUN_FP8_E4M3) && p->d == 128; }
 
 // compute units of the current device (one fetching workgroup each)
 int device_compute_units() {
@@ -1083,13 +1201,16 @@ int device_compute_units() {
 }
 
 template <int G>
-void launch_tiles(const PrefillArgs& a, dim3 grid, bool persistent, bool ring, hipStream_t st) {
-    if (ring) {
+void launch_tiles(const PrefillArgs& a, dim3 grid, bool persistent, bool ring, bool fp8, hipStream_t st) {
+    if (fp8) {
+        if (persistent) hipLaunchKernelGGL((prefill_pp_kernel<G, true, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((prefill_pp_kernel<G, false, true>), grid, dim3(512), 0, st, a);
+    } else if (ring) {
         if (persistent) hipLaunchKernelGGL((prefill_ring_kernel<G, true>), grid, dim3(512), 0, st, a);
         else hipLaunchKernelGGL((prefill_ring_kernel<G, false>), grid, dim3(512), 0, st, a);
     } else {
-        if (persistent) hipLaunchKernelGGL((prefill_pp_kernel<G, true>), grid, dim3(512), 0, st, a);
-        else hipLaunchKernelGGL((prefill_pp_kernel<G, false>), grid, dim3(512), 0, st, a);
+        if (persistent) hipLaunchKernelGGL((prefill_pp_kernel<G, true, false>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((prefill_pp_kernel<G, false, false>), grid, dim3(512), 0, st, a);
     }
 }
 
@@ -1213,6 +1334,7 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     ra.max_blocks = max_blocks;
     ra.sub_shift = a.sub_shift;
     ra.block_bytes = a.block_bytes;
+    ra.tile_bytes = (unsigned)(2 * kBlock * D * p->elt);
     const size_t n_entries = (size_t)n_chunks * (size_t)a.tiles_per_row;
     ra.n_wgs = (int)((n_entries + kPlanThreads - 1) / kPlanThreads < 1024 ? (n_entries + kPlanThreads - 1) / kPlanThreads : 1024);
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1 + ra.n_wgs), dim3(kPlanThreads), 0, st, ra, q_start, prior_len,
@@ -1229,15 +1351,15 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     const dim3 grid((unsigned)wgs);
     const bool ring = kun_options().prefill_shape >= 2;     // the one-barrier-per-tile kernel (cross-check)
     switch (G) {
-        case 1: launch_tiles<1>(a, grid, persistent, ring, st); break;
-        case 2: launch_tiles<2>(a, grid, persistent, ring, st); break;
-        case 3: launch_tiles<3>(a, grid, persistent, ring, st); break;
-        case 4: launch_tiles<4>(a, grid, persistent, ring, st); break;
-        case 5: launch_tiles<5>(a, grid, persistent, ring, st); break;
-        case 6: launch_tiles<6>(a, grid, persistent, ring, st); break;
-        case 7: launch_tiles<7>(a, grid, persistent, ring, st); break;
-        case 8: launch_tiles<8>(a, grid, persistent, ring, st); break;
-        default: launch_tiles<16>(a, grid, persistent, ring, st); break;
+        case 1: launch_tiles<1>(a, grid, persistent, ring, p->dtype == KUN_FP8_E4M3, st); break;
+        case 2: launch_tiles<2>(a, grid, persistent, ring, p->dtype == KUN_FP8_E4M3, st); break;
+        case 3: launch_tiles<3>(a, grid, persistent, ring, p->dtype == KUN_FP8_E4M3, st); break;
+        case 4: launch_tiles<4>(a, grid, persistent, ring, p->dtype == KUN_FP8_E4M3, st); break;
+        case 5: launch_tiles<5>(a, grid, persistent, ring, p->dtype == KUN_FP8_E4M3, st); break;
+        case 6: launch_tiles<6>(a, grid, persistent, ring, p->dtype == KUN_FP8_E4M3, st); break;
+        case 7: launch_tiles<7>(a, grid, persistent, ring, p->dtype == KUN_FP8_E4M3, st); break;
+        case 8: launch_tiles<8>(a, grid, persistent, ring, p->dtype == KUN_FP8_E4M3, st); break;
+        default: launch_tiles<16>(a, grid, persistent, ring, p->dtype == KUN_FP8_E4M3, st); break;
     }
     KUN_HIP_CHECK_LAUNCH();
     if (can_split) {

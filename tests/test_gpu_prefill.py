@@ -369,8 +369,52 @@ def test_config4_prefill_chunks_sampled_rows():
     dw.close()
 
 
-@pytest.mark.parametrize("G,d,B", [(4, 128, 16), (2, 64, 64)])
-def test_fp8_pages_run_on_the_vector_alu_kernel(G, d, B):
+@pytest.mark.parametrize("mode", ["default", "persistent", "on16", "split"])
+@pytest.mark.parametrize("G,B", [(8, 16), (4, 64), (1, 16), (5, 32), (16, 128)])
+def test_fp8_pages_on_the_matrix_cores(G, B, mode):
+    # FP8 (E4M3) pages, bf16 queries: the ping-pong kernel with E4M3 tiles in the ring.  Chunks around
+    # block, sub-tile, tile and workgroup-tile edges; launches small enough to split the keys; a limited
+    # number of fetching workgroups (bit-identical to the plain launch)
+    if mode == "persistent":
+        kun.kun_set_option("KUN_PREFILL_SHAPE", "persistent")
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=128, B=B, dtype="fp8")
+    sets = ([(3000, 40)], [(5000, 200), (17, 3)], [(1500, 64), (64, 64), (9000, 5)]) if mode == "split" else \
+        ([(0, 1), (0, 17), (5, 1), (15, 16), (16, 33), (31, 64), (63, 65), (64, 129), (100, 200), (0, 300), (333, 77),
+          (700, 257), (1000, 31), (0, 1100)],)
+    for chunks in sets:
+        w = synth.custom_workload("fp8-mfma", sh, [3], chunks=chunks, extra_blocks=3, range_fracs=(0.4, 0.6))
+        dw = DeviceWorkload(w)
+        dw.out_pre.fill_(float("nan"))
+        if mode == "on16":
+            ref = dw.prefill().clone()
+            dw.out_pre.fill_(float("nan"))
+            got = dw.prefill(max_workgroups=16)
+            torch.cuda.synchronize()
+            assert torch.equal(got.view(torch.int16), ref.view(torch.int16))
+        err = check_prefill(dw, rows_per_chunk=64)
+        print(chunks[:2], "max err", err)
+        dw.close()
+
+
+def test_fp8_pages_scores_that_outgrow_the_running_maximum():
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="fp8")
+    chunks = [(0, 700), (512, 300), (900, 64)]
+    w = synth.custom_workload("fp8-grow", sh, [], chunks=chunks, extra_blocks=0)
+    dw = DeviceWorkload(w, fill=False)
+    for i, (p, c) in enumerate(chunks):
+        L = p + c
+        k, v = synth.kv_logical(w, i, 0, L, dw.dev)
+        t = torch.arange(L, device=dw.dev, dtype=torch.float32)
+        f = torch.where(t < 200, 0.05, 8.0) * torch.where(t >= 640, 4.0, 1.0)       # key magnitude jumps twice
+        k = (k.view(torch.float8_e4m3fn).float() * f[:, None, None]).to(torch.float8_e4m3fn).view(torch.uint8)
+        synth.write_pages(w, dw.ranges, i, 0, L, k, v)
+    err = check_prefill(dw)
+    print("max err", err)
+    dw.close()
+
+
+@pytest.mark.parametrize("G,d,B", [(2, 64, 64), (7, 64, 16)])
+def test_fp8_pages_with_head_dim_64_run_on_the_vector_alu_kernel(G, d, B):
     # prefill over FP8 (E4M3) pages: queries bf16, rows served one by one (correct to the same bar, not tuned)
     sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=B, dtype="fp8")
     chunks = [(0, 1), (5, 1), (15, 16), (63, 65), (100, 40), (333, 20)]

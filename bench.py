@@ -556,9 +556,14 @@ ORACLE_TOKENS_PER_S = 80000.0      # rough speed of the numpy oracle, only used 
 OTHER_CONFIGS = (3, 4, 2)          # reported under "others" after the default workload
 # HBM bytes per decode launch from rocprofv3 --pmc runs of an EARLIER session (not of this run), keyed by
 # (config, block size, query heads, page dtype): (bytes, where the figure comes from).
-TRAFFIC = {(5, 16, 64, "bf16"): (17322737541, "profiles/bench_cfg5_70b_stage_kernels.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
-                                       "of decode_partial_mfma in an earlier session, 1.015 x the algorithmic bytes; "
-                                       "not measured in this run")}
+TRAFFIC = {
+    (5, 16, 64, "bf16"): (17134246810, "profiles/bench_cfg5_70b_stage_kernels.md: rocprofv3 --pmc FETCH_SIZE (x2.0) + WRITE_SIZE of "
+                                       "decode_partial_mfma in an earlier session of this build, 1.004 x the algorithmic bytes; not "
+                                       "measured in this run"),
+    (5, 16, 64, "fp8"): (8612556800, "profiles/bench_cfg5_fp8_pages_kernels.md: rocprofv3 --pmc FETCH_SIZE (x2.0) of "
+                                     "decode_partial_mfma_fp8 in an earlier session of this build (reads only), 1.009 x the "
+                                     "algorithmic bytes; not measured in this run"),
+}
 
 if __name__ == "__main__":
     main()

@@ -63,7 +63,7 @@ struct PrefillArgs {
                               // and (chunk tokens, first key tile, key tiles, partial-result slot or -1), for the ring kernels
     const unsigned long long* page_addr;   // workspace: [chunk][16-token tile of the request] device address of the tile of
                                            // KV head 0 (block resolution done once per tile, by the plan launch)
-    int tiles_per_row;        // entries per chunk in page_addr: max_blocks * (block_size / 16)
+    int tiles_per_row;        // entries per chunk in page_addr (page_row_entries)
     int4* split_items;        // workspace: (chunk, position tile, nsplit, first slot) of every split item
     int32_t* n_split_items;   // workspace
     float* part_o;            // workspace: [slot, kvh, 256 rows, 128] unnormalised outputs of a key range
@@ -123,19 +123,30 @@ constexpr int kMinTilesPerSplit = 8;    // ... of at least this many 64-key tile
 constexpr int kSplitRows = 256;         // rows of a workgroup of the kernels that can split (8 waves x 32)
 
 // Block resolution for the whole launch, once per 16-token tile instead of once per (tile, query tile,
-// kv head): entry (chunk i, tile t) = address of tile t % (B / 16) of block table[i][t / (B / 16)], KV
-// head 0.  Entries past a chunk's context are not written (their table entries may hold anything).
+// kv head).  A chunk's row has four entries per 64-key tile, for every key tile that its table row can
+// hold and one more; the entry of page tile s of key tile kt sits at 4 kt + kTilePlace[s], so that the
+// two page tiles a wave loads (s and s + 2) lie side by side and come with one 16-byte scalar load.
+// Entry = address (KV head 0) of 16-token tile min(4 kt + s, last tile of the context) of the request:
+// tile t is tile t % (B / 16) of block table[i][t / (B / 16)].  Tiles past the context repeat the last
+// one, so the kernels index without a clamp (and every lane issues the same number of loads per tile).
+__device__ __host__ constexpr int kun_tile_place(int s) { return s == 1 ? 2 : s == 2 ? 1 : s; }   // its own inverse
+__device__ __host__ inline int page_row_entries(int max_blocks, int sub_shift) {
+    return (((max_blocks << sub_shift) + kBlocksPerTile - 1) / kBlocksPerTile + 1) * kBlocksPerTile;
+}
 __device__ void resolve_tiles(const KunRanges& rt, const int32_t* __restrict__ q_start,
                               const int32_t* __restrict__ prior, const int32_t* __restrict__ table, int n_chunks,
                               int max_blocks, int sub_shift, unsigned block_bytes, unsigned tile_bytes,
                               unsigned long long* __restrict__ page_addr, int first_wg, int n_wgs) {
-    const int tiles_per_row = max_blocks << sub_shift;
+    const int tiles_per_row = page_row_entries(max_blocks, sub_shift);
     const long long total = (long long)n_chunks * tiles_per_row;
     for (long long e = (long long)(blockIdx.x - first_wg) * blockDim.x + threadIdx.x; e < total;
          e += (long long)n_wgs * blockDim.x) {
-        const int ch = (int)(e / tiles_per_row), t = (int)(e % tiles_per_row);
+        const int ch = (int)(e / tiles_per_row), place = (int)(e % tiles_per_row);
         const int ctx = prior[ch] + q_start[ch + 1] - q_start[ch];
-        if (t * kBlock >= ctx || q_start[ch + 1] == q_start[ch]) continue;
+        if (q_start[ch + 1] == q_start[ch] || ctx <= 0) continue;
+        const int last = (ctx - 1) / kBlock;
+        int t = (place & ~(kBlocksPerTile - 1)) + kun_tile_place(place & (kBlocksPerTile - 1));
+        t = t < last ? t : last;
         const int id = table[(size_t)ch * max_blocks + (t >> sub_shift)];
         page_addr[e] = (unsigned long long)kun_block_addr(rt, id, block_bytes) +
                        (unsigned)(t & ((1 << sub_shift) - 1)) * tile_bytes;
@@ -389,8 +400,7 @@ void prefill_ring_kernel(const PrefillArgs a) {
     // tiles wave / 4 and wave / 4 + 2.  Tiles past the context re-read the last one (every lane issues the
     // same number of loads per tile, so the wait counts stay exact).
     auto tile_addr = [&](int j, int i) -> unsigned long long {     // j: tile index relative to kt0
-        const int lb = (kt0 + j) * kBlocksPerTile + (wave_u >> 2) + 2 * i;
-        return arow[lb < ntile_ctx ? lb : ntile_ctx - 1];
+        return arow[(kt0 + j) * kBlocksPerTile + kun_tile_place((wave_u >> 2) + 2 * i)];
     };
     unsigned long long pg0 = tile_addr(0, 0), pg1 = tile_addr(0, 1);      // of the tile to be issued next
     auto issue = [&](int j) {
@@ -735,7 +745,6 @@ void prefill_pp_kernel(const PrefillArgs a) {
     const int wpos_end = pos0 + min((wave_u * ROWS_W + ROWS_W - 1) / G, POS - 1) + 1;
 
     const kun_caddr arow = (kun_caddr)(a.page_addr + (size_t)chunk * a.tiles_per_row);
-    const int ntile_ctx = (ctx + kBlock - 1) / kBlock;
     const int slot = (wave & 3) * 64 + lane;
     // bf16: this lane fills 16-byte slot `slot` of a page tile's K and V^T (K chunk XOR row, V^T halves swapped).
     // F8: wave w brings half w % 2 of page tile w / 2: K rows 8 (w % 2) + lane / 8, 16-byte chunk lane % 8
@@ -751,15 +760,23 @@ void prefill_pp_kernel(const PrefillArgs a) {
     const unsigned ring_addr = (unsigned)(size_t)(kun_lptr)&ring[0][0];
     // bf16: page tiles wave / 4 and wave / 4 + 2 of key tile j (relative to kt0); F8: page tile wave / 2;
     // clamped into the context
-    auto tile_addr = [&](int j, int i) -> unsigned long long {
-        int lb = (kt0 + j) * kBlocksPerTile + (F8 ? (wave_u >> 1) : (wave_u >> 2) + 2 * i);
-        lb = lb < 0 ? 0 : lb;
-        return arow[lb < ntile_ctx ? lb : ntile_ctx - 1];
+    // (the table repeats the context's last page tile behind it; bf16: both addresses with one scalar load)
+    typedef unsigned long long AddrPair __attribute__((ext_vector_type(2)));
+    unsigned long long kpg0, kpg1;
+    auto tile_addr = [&](int j) {
+        if (F8) {
+            kpg0 = kpg1 = arow[(kt0 + j) * kBlocksPerTile + kun_tile_place(wave_u >> 1)];
+        } else {
+            const AddrPair pr = *(const __attribute__((address_space(4))) AddrPair*)(arow + (kt0 + j) * kBlocksPerTile + 2 * (wave_u >> 2));
+            kpg0 = pr.x;
+            kpg1 = pr.y;
+        }
     };
     // Stage t: K of key tile t and V^T of key tile t - 1.  kpg: page tiles of key tile `next_t`, vpg: of
     // key tile next_t - 1 (what the next call of issue() sends).
-    unsigned long long kpg0 = tile_addr(0, 0), kpg1 = tile_addr(0, 1), vpg0 = kpg0, vpg1 = kpg1;
-    int next_t = 0;                                    // next stage to request
+    tile_addr(0);
+    unsigned long long vpg0 = kpg0, vpg1 = kpg1;
+    unsigned next_t = 0;                               // next stage to request
     auto issue = [&]() {
         if (F8) {
             const unsigned dst = ring_addr + (next_t % NSTAGE) * STAGE_BYTES + (wave_u >> 1) * TILE_B + (wave_u & 1) * 1024;
@@ -776,15 +793,14 @@ void prefill_pp_kernel(const PrefillArgs a) {
         vpg0 = kpg0;
         vpg1 = kpg1;
         ++next_t;
-        kpg0 = tile_addr(next_t, 0);
-        if (!F8) kpg1 = tile_addr(next_t, 1);
+        tile_addr((int)next_t);
     };
     // stages 0 .. nt exist; `landed(t)`: this lane's loads of stage t are complete (stages are requested
     // in order, four loads each, so everything but the 4 * (next_t - 1 - t) youngest loads is waited for)
     auto landed = [&](int t) {
-        const int younger = next_t - 1 - t;
-        if (younger >= 3) KUN_WAIT_VMCNT(3 * LPS);
-        else if (younger == 2) KUN_WAIT_VMCNT(2 * LPS);
+        const int younger = (int)next_t - 1 - t;
+        if (younger == 2) KUN_WAIT_VMCNT(2 * LPS);     // (the usual case first)
+        else if (younger >= 3) KUN_WAIT_VMCNT(3 * LPS);
         else if (younger == 1) KUN_WAIT_VMCNT(LPS);
         else KUN_WAIT_VMCNT(0);
     };
@@ -835,12 +851,12 @@ void prefill_pp_kernel(const PrefillArgs a) {
     Frag vpre[kPre];
     auto prefetch_v = [&](int t) {
         if (F8) return;                                // (the FP8 matrix phase reads all its fragments itself)
-        const unsigned char* vbase = &ring[t % NSTAGE][0] + v_lane;
+        const unsigned char* vbase = &ring[t & (NSTAGE - 1)][0] + v_lane;
 #pragma unroll
         for (int i = 0; i < kPre; ++i) vpre[i].u = *(const uint4*)(vbase + (i >> 2) * 4096 + (i & 3) * 1024);
     };
     auto mphase = [&](int t, auto do_pv, auto do_qk) {
-        const unsigned char* stage = &ring[t % NSTAGE][0];
+        const unsigned char* stage = &ring[t & (NSTAGE - 1)][0];
         const unsigned char* vbase = stage + v_lane;
         const unsigned char* kbase = stage + k_lane;
         constexpr bool PV = decltype(do_pv)::value, QK = decltype(do_qk)::value;
@@ -945,7 +961,7 @@ void prefill_pp_kernel(const PrefillArgs a) {
     };
     // PV of the context's last key tile when it holds keys past the context (once per item at most)
     auto pv_tail = [&](int t) {
-        const unsigned char* vbase = &ring[t % NSTAGE][0] + v_lane;
+        const unsigned char* vbase = &ring[t & (NSTAGE - 1)][0] + v_lane;
         const int key0 = (kt0 + t - 1) * BN;
         if constexpr (F8) {
 #pragma unroll
@@ -1071,14 +1087,14 @@ void prefill_pp_kernel(const PrefillArgs a) {
         __builtin_amdgcn_s_barrier();                  // b(2t + 1) / b(2t + 2)
         __builtin_amdgcn_sched_barrier(0);
         // M(t) of both groups is over once group 1 is here; group 0 learns that one barrier later
-        if (group == 1 && next_t <= nt) issue();       // stage t + 4
+        if (group == 1 && (int)next_t <= nt) issue();       // stage t + 4
         if (prefetch) prefetch_v(t + 1);
         vphase(t);
         if (group == 1) landed(min(t + 2, nt));        // group 1 arrives at b(2t + 3): stage t + 2
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_barrier();                  // b(2t + 2) / b(2t + 3)
         __builtin_amdgcn_sched_barrier(0);
-        if (group == 0 && next_t <= nt) issue();       // stage t + 4
+        if (group == 0 && (int)next_t <= nt) issue();       // stage t + 4
     };
     for (int t = 0; t + 1 < nt; ++t) {
         vector_part(t, true);
@@ -1241,7 +1257,7 @@ PrefillLayout prefill_layout(const kun_kv_pool* p, int n_chunks, int Hq, int tot
     size_t o = 256;
     lay.off_items = o;        o += align256(sizeof(int2) * (size_t)lay.cap_entries);
     lay.off_desc = o;         o += align256(sizeof(int4) * 2 * (size_t)lay.cap_entries);
-    lay.off_pages = o;        o += align256(sizeof(unsigned long long) * (size_t)n_chunks * ((size_t)max_blocks << sub_shift_of(p)));
+    lay.off_pages = o;        o += align256(sizeof(unsigned long long) * (size_t)n_chunks * (size_t)page_row_entries(max_blocks, sub_shift_of(p)));
     lay.off_split_info = o;   if (lay.may_split) o += align256(sizeof(int2) * (size_t)lay.cap_entries);
     lay.off_split_items = o;  if (lay.may_split) o += align256(sizeof(int4) * (size_t)(kSplitTarget + 1));
     const size_t part_wgs = 2 * (size_t)kSplitTarget + p->Hkv;       // (key range, kv head) workgroups of split items
@@ -1310,7 +1326,7 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     a.items = (int2*)(ws + lay.off_items);
     a.desc = (const int4*)(ws + lay.off_desc);
     a.page_addr = (const unsigned long long*)(ws + lay.off_pages);
-    a.tiles_per_row = max_blocks << sub_shift_of(p);
+    a.tiles_per_row = page_row_entries(max_blocks, sub_shift_of(p));
     a.split_info = can_split ? (const int2*)(ws + lay.off_split_info) : nullptr;
     a.split_items = (int4*)(ws + lay.off_split_items);
     a.part_ml = (float*)(ws + lay.off_part_ml);

@@ -693,19 +693,24 @@ void prefill_ring_kernel(const PrefillArgs a) {
 // phase runs at the rate of the matrix pipe from its first instruction.
 // ---------------------------------------------------------------------------------------------
 //
-// F8: the pages hold FP8 (E4M3) codes, one byte per element (queries and outputs stay bf16).  A stage is
-// half as large (K [64 keys][128 B], then V^T [4 page tiles][128 dims][16 B]), a wave brings half of ONE
-// page tile per stage (two loads per lane), and a 16-byte LDS read is sixteen elements = the operands
-// of two MFMAs after conversion to bf16 in the matrix phase (exact).  The contraction over head_dim is
-// permuted to what a 16-byte read of a K row holds (k-steps 2c and 2c + 1 = dims 32c + 16 jh .. + 16, Q
-// loaded in the same order), and S^T rows are mapped to keys so that a lane holds all 16 tokens of one
-// page tile: a 16-byte V^T row of that tile then feeds its two PV MFMAs.
+// F8: the pages hold FP8 (E4M3) codes, one byte per element (queries and outputs stay bf16).  Every
+// stage is widened to bf16 ONCE, into a ring of three bf16 stages with the layout of the bf16 kernel,
+// so the matrix phases are the bf16 kernel's own.  (A matrix phase that widens the fragments it reads
+// does the work eight times over, once per wave: 256 conversions per wave and tile against 32 here.)
+// The codes land in a small ring of the wave's own (three stages of 2 KiB per wave: the half page tile
+// of K and of V^T that the wave requests, two loads per lane and stage), and a lane widens the two
+// 16-byte pieces it requested itself: between landing and widening there is nothing to agree on with
+// other waves, only the wave's own vmcnt.  The widening sits between the MFMAs of a full matrix phase
+// (two LDS reads, sixteen conversions, four LDS writes per lane): waves 0-3 widen stage t + 2 in their
+// M(t + 1), waves 4-7 stage t + 3 in theirs, both one barrier before the first read of that stage.
 template <int G, bool PERSIST, bool F8>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void prefill_pp_kernel(const PrefillArgs a) {
     constexpr int NW = 8, ROWS_W = 32, ROWS = NW * ROWS_W, POS = ROWS / G, LIVE = POS * G;
-    constexpr int TILE_B = F8 ? 2048 : 4096;           // bytes of K (or of V^T) of one 16-token page tile
-    constexpr int NSTAGE = 4, STAGE_BYTES = 2 * kBlocksPerTile * TILE_B, V_OFF = kBlocksPerTile * TILE_B;
+    constexpr int TILE_B = 4096;                       // bytes of K (or of V^T) of one 16-token page tile in the ring
+    constexpr int NSTAGE = F8 ? 3 : 4, STAGE_BYTES = 2 * kBlocksPerTile * TILE_B, V_OFF = kBlocksPerTile * TILE_B;
+    // F8: the ring the codes land in: per stage, wave w owns bytes [2048 w, 2048 w + 2048): 1 KiB of K, 1 KiB of V^T
+    constexpr int LAND_STAGE = 8 * 2048, LAND_V = 1024;
     constexpr int LPS = F8 ? 2 : 4;                    // loads per lane and stage
 #ifndef KUN_PP_AHEAD
 #define KUN_PP_AHEAD 4
@@ -718,6 +723,7 @@ void prefill_pp_kernel(const PrefillArgs a) {
     static_assert(G >= 1 && G <= 16, "1 to 8 or 16 query heads per KV head");
 
     __shared__ __attribute__((aligned(16))) unsigned char ring[NSTAGE][STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char land[F8 ? NSTAGE : 1][F8 ? LAND_STAGE : 16];
     __shared__ int s_next;
     int wi = blockIdx.x;
     for (;;) {
@@ -747,9 +753,8 @@ void prefill_pp_kernel(const PrefillArgs a) {
     const kun_caddr arow = (kun_caddr)(a.page_addr + (size_t)chunk * a.tiles_per_row);
     const int slot = (wave & 3) * 64 + lane;
     // bf16: this lane fills 16-byte slot `slot` of a page tile's K and V^T (K chunk XOR row, V^T halves swapped).
-    // F8: wave w brings half w % 2 of page tile w / 2: K rows 8 (w % 2) + lane / 8, 16-byte chunk lane % 8
-    // XOR row; V^T rows (dims) 64 (w % 2) + lane as they are.
-    const unsigned k_src = F8 ? kvh * a.page_bytes + (8 * (wave & 1) + (lane >> 3)) * 128 + (((lane & 7) ^ (lane >> 3)) * 16)
+    // F8: wave w brings half w % 2 of page tile w / 2, K and V^T as they lie in the page.
+    const unsigned k_src = F8 ? kvh * a.page_bytes + (64 * (wave & 1) + lane) * 16
                               : kvh * a.page_bytes + (slot >> 4) * 256 + (((slot & 15) ^ (slot >> 4)) * 16);
     const unsigned v_src = F8 ? kvh * a.page_bytes + 2048 + (64 * (wave & 1) + lane) * 16
                               : kvh * a.page_bytes + 4096 + ((slot ^ ((slot >> 4) & 1)) * 16);
@@ -757,7 +762,7 @@ void prefill_pp_kernel(const PrefillArgs a) {
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(page), "s"(lds_addr)
                      : "memory", "m0");
     };
-    const unsigned ring_addr = (unsigned)(size_t)(kun_lptr)&ring[0][0];
+    const unsigned ring_addr = F8 ? (unsigned)(size_t)(kun_lptr)&land[0][0] : (unsigned)(size_t)(kun_lptr)&ring[0][0];
     // bf16: page tiles wave / 4 and wave / 4 + 2 of key tile j (relative to kt0); F8: page tile wave / 2;
     // clamped into the context
     // (the table repeats the context's last page tile behind it; bf16: both addresses with one scalar load)
@@ -779,11 +784,11 @@ void prefill_pp_kernel(const PrefillArgs a) {
     unsigned next_t = 0;                               // next stage to request
     auto issue = [&]() {
         if (F8) {
-            const unsigned dst = ring_addr + (next_t % NSTAGE) * STAGE_BYTES + (wave_u >> 1) * TILE_B + (wave_u & 1) * 1024;
+            const unsigned dst = ring_addr + (next_t % NSTAGE) * LAND_STAGE + wave_u * 2048;
             dma16(kpg0, k_src, dst);
-            dma16(vpg0, v_src, dst + V_OFF);
+            dma16(vpg0, v_src, dst + LAND_V);
         } else {
-            const unsigned st = ring_addr + (next_t % NSTAGE) * STAGE_BYTES + (wave_u & 3) * 1024;
+            const unsigned st = ring_addr + (next_t & 3) * STAGE_BYTES + (wave_u & 3) * 1024;
             const unsigned dst0 = st + (wave_u >> 2) * 4096, dst1 = dst0 + 2 * 4096;
             dma16(kpg0, k_src, dst0);
             dma16(vpg0, v_src, dst0 + V_OFF);
@@ -809,7 +814,7 @@ void prefill_pp_kernel(const PrefillArgs a) {
     issue();
     if (nt >= 1) issue();
     if (nt >= 2) issue();
-    if (nt >= 3) issue();
+    if (!F8 && nt >= 3) issue();                       // (F8: the landing ring has three stages)
 
     Frag qf[8];
     int pos = pos0 + (wave * ROWS_W + n) / G;
@@ -821,7 +826,7 @@ void prefill_pp_kernel(const PrefillArgs a) {
         const char* qrow = (const char*)a.q + (((size_t)(qs + pos)) * a.Hq + kvh * G + g_head) * (D * 2);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
-            qf[ks].u = *(const uint4*)(qrow + (F8 ? 2 * (32 * (ks >> 1) + 16 * jh + 8 * (ks & 1)) : (2 * ks + jh) * 16));
+            qf[ks].u = *(const uint4*)(qrow + (2 * ks + jh) * 16);
     }
     const int wave_vis_min = p + min(wpos0, c - 1);
 
@@ -832,14 +837,27 @@ void prefill_pp_kernel(const PrefillArgs a) {
         for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
     float m = -INFINITY, l = 0.f;                      // m in log2 units
 
-    // key (inside a 32-key sub-tile) of row n of an S^T tile.  bf16: accumulator register i of a lane is
-    // key 16 (i / 8) + 8 jh + i % 8; F8: key 16 jh + i (a lane holds the 16 tokens of one page tile).
-    const int krow = F8 ? 16 * ((n >> 2) & 1) + 4 * (n >> 3) + (n & 3)
-                        : 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
-    const int krow_blk = krow >> 4, krow_in = F8 ? (krow & 7) : (krow & 15);
-    const unsigned k_lane = F8 ? krow * 128 : krow_blk * 4096 + krow_in * 256;
-    const unsigned v_lane = F8 ? V_OFF + jh * 2048 + n * 16 : V_OFF + n * 32 + ((jh ^ ((n >> 3) & 1)) * 16);
+    // key (inside a 32-key sub-tile) of row n of an S^T tile: accumulator register i of a lane is key
+    // 16 (i / 8) + 8 jh + i % 8
+    const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
+    const int krow_blk = krow >> 4, krow_in = krow & 15;
+    const unsigned k_lane = krow_blk * 4096 + krow_in * 256;
+    const unsigned v_lane = V_OFF + n * 32 + ((jh ^ ((n >> 3) & 1)) * 16);
     const float sl2 = a.scale_log2;
+    // F8: the two 16-byte pieces of codes this lane requests and widens per stage, and where their halves
+    // go in the bf16 stage.  Wave w has half w % 2 of page tile w / 2.  K piece: key row 8 (w % 2) +
+    // lane / 8, dims 16 (lane % 8) .. + 16 -> two 16-byte chunks, placed XOR the row like the bf16 loads
+    // place them; V^T piece: the sixteen tokens of dim 64 (w % 2) + lane -> the dim's two halves, swapped
+    // where the bf16 loads swap them.
+    // (the second half of a piece goes to the neighbouring chunk: its offset is the first one's XOR 16)
+    unsigned w_src = 0, w_dst_k = 0, w_dst_v = 0;
+    if (F8) {
+        const int pt = wave >> 1, hf = wave & 1;
+        const int row = 8 * hf + (lane >> 3), c = lane & 7, dim = 64 * hf + lane, sw = (dim >> 3) & 1;
+        w_src = wave * 2048 + lane * 16;
+        w_dst_k = pt * 4096 + row * 256 + (((2 * c) ^ row) * 16);
+        w_dst_v = V_OFF + pt * 4096 + (((2 * dim) ^ sw) * 16);
+    }
 
     f32x16 sa, sb;                                     // S^T of the tile between its M and its V phase
     union { bf16x2 h[16]; uint4 u[4]; } cv;            // P^T of the tile between its V and the next M phase
@@ -850,70 +868,21 @@ void prefill_pp_kernel(const PrefillArgs a) {
     // used kPre MFMAs later.
     Frag vpre[kPre];
     auto prefetch_v = [&](int t) {
-        if (F8) return;                                // (the FP8 matrix phase reads all its fragments itself)
-        const unsigned char* vbase = &ring[t & (NSTAGE - 1)][0] + v_lane;
+        const unsigned char* vbase = &ring[F8 ? t % NSTAGE : t & 3][0] + v_lane;
 #pragma unroll
         for (int i = 0; i < kPre; ++i) vpre[i].u = *(const uint4*)(vbase + (i >> 2) * 4096 + (i & 3) * 1024);
     };
     auto mphase = [&](int t, auto do_pv, auto do_qk) {
-        const unsigned char* stage = &ring[t & (NSTAGE - 1)][0];
+        const unsigned char* stage = &ring[F8 ? t % NSTAGE : t & 3][0];
         const unsigned char* vbase = stage + v_lane;
         const unsigned char* kbase = stage + k_lane;
         constexpr bool PV = decltype(do_pv)::value, QK = decltype(do_qk)::value;
-        if constexpr (F8) {
-            // sixteen raw reads (8 of V^T: sub-tile x 32 dims; 8 of K: sub-tile x chunk), each converted to
-            // the operands of two MFMAs
-            uint4 vraw[2][4], kraw[2][4];
-            if (PV) {
-#pragma unroll
-                for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                    for (int dt = 0; dt < 4; ++dt) vraw[sub][dt] = *(const uint4*)(vbase + sub * 4096 + dt * 512);
-            }
-            if (QK) {
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc)
-#pragma unroll
-                    for (int sub = 0; sub < 2; ++sub)
-                        kraw[sub][cc] = *(const uint4*)(kbase + sub * 4096 + (((2 * cc + jh) ^ krow_in) * 16));
-            }
-            if (PV) {
-#pragma unroll
-                for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                    for (int dt = 0; dt < 4; ++dt) {
-                        Frag lo, hi, p0, p1;
-                        fp8x16_to_bf16(vraw[sub][dt], lo, hi);
-                        p0.u = cv.u[2 * sub];
-                        p1.u = cv.u[2 * sub + 1];
-                        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.v, p0.v, o[dt], 0, 0, 0);
-                        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi.v, p1.v, o[dt], 0, 0, 0);
-                    }
-            }
-            if (QK) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { sa[i] = 0.f; sb[i] = 0.f; }
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                    Frag lo, hi;
-                    fp8x16_to_bf16(kraw[0][cc], lo, hi);
-                    sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.v, qf[2 * cc].v, sa, 0, 0, 0);
-                    sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi.v, qf[2 * cc + 1].v, sa, 0, 0, 0);
-                    fp8x16_to_bf16(kraw[1][cc], lo, hi);
-                    sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.v, qf[2 * cc].v, sb, 0, 0, 0);
-                    sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi.v, qf[2 * cc + 1].v, sb, 0, 0, 0);
-                }
-            }
-            // two reads ahead, then per fragment: its eight conversions, its two MFMAs, the next read
-            constexpr int NF = (PV ? 8 : 0) + (QK ? 8 : 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-#pragma unroll
-            for (int i = 0; i < NF; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                if (i + 2 < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            return;
+        constexpr bool W = F8 && PV && QK;             // the full phase also widens this lane's pieces of stage t + 1 + group
+        uint4 raw0, raw1;
+        if constexpr (W) {
+            const unsigned char* src = &land[F8 ? (t + 1 + group) % NSTAGE : 0][0] + w_src;
+            raw0 = *(const uint4*)src;
+            raw1 = *(const uint4*)(src + LAND_V);
         }
         Frag vf[16], ka[8], kb[8];
         if (PV) {
@@ -948,10 +917,22 @@ void prefill_pp_kernel(const PrefillArgs a) {
                 sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[ks].v, qf[ks].v, sb, 0, 0, 0);
             }
         }
+        if constexpr (W) {
+            unsigned char* dst = &ring[(t + 1 + group) % NSTAGE][0];
+            Frag lo, hi;
+            fp8x16_to_bf16(raw0, lo, hi);
+            *(uint4*)(dst + w_dst_k) = lo.u;
+            *(uint4*)(dst + (w_dst_k ^ 16)) = hi.u;
+            fp8x16_to_bf16(raw1, lo, hi);
+            *(uint4*)(dst + w_dst_v) = lo.u;
+            *(uint4*)(dst + (w_dst_v ^ 16)) = hi.u;
+        }
         constexpr int NM = (PV ? 16 : 0) + (QK ? 16 : 0);       // MFMAs
         constexpr int NR = (PV ? 16 - kPre : 0) + (QK ? 16 : 0);   // fragment reads inside the phase
         constexpr int LEAD = PV ? 0 : kAhead;                   // reads in front of the first MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, LEAD, 0);
+        // (W: the two reads of codes first; the conversions fall between the MFMAs, the four writes of the
+        // widened pieces behind MFMAs 12, 16, 20 and 24)
+        __builtin_amdgcn_sched_group_barrier(0x100, LEAD + (W ? 2 : 0), 0);
 #pragma unroll
         for (int i = 0; i < NR - LEAD; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -961,29 +942,8 @@ void prefill_pp_kernel(const PrefillArgs a) {
     };
     // PV of the context's last key tile when it holds keys past the context (once per item at most)
     auto pv_tail = [&](int t) {
-        const unsigned char* vbase = &ring[t & (NSTAGE - 1)][0] + v_lane;
+        const unsigned char* vbase = &ring[F8 ? t % NSTAGE : t & 3][0] + v_lane;
         const int key0 = (kt0 + t - 1) * BN;
-        if constexpr (F8) {
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    Frag vh[2], pb[2];
-                    fp8x16_to_bf16(*(const uint4*)(vbase + sub * 4096 + dt * 512), vh[0], vh[1]);
-                    const int t0 = key0 + 32 * sub + 16 * jh;
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        unsigned x[4] = {vh[h].u.x, vh[h].u.y, vh[h].u.z, vh[h].u.w};
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (t0 + 8 * h + e >= ctx) x[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                        vh[h].u = make_uint4(x[0], x[1], x[2], x[3]);
-                        pb[h].u = cv.u[2 * sub + h];
-                        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vh[h].v, pb[h].v, o[dt], 0, 0, 0);
-                    }
-                }
-            return;
-        }
 #pragma unroll
         for (int h = 0; h < 4; ++h) {
             Frag pb;
@@ -1030,9 +990,11 @@ void prefill_pp_kernel(const PrefillArgs a) {
         }
         if (redo) {
             if (!plain) {
+                int jb = kt * BN + 8 * jh;
+                asm volatile("" : "+v"(jb));           // (made here: sixteen key offsets kept in registers across the tile loop cost more)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int key = F8 ? kt * BN + 16 * jh + i : kt * BN + 16 * (i >> 3) + 8 * jh + (i & 7);
+                    const int key = jb + 16 * (i >> 3) + (i & 7);
                     if (key > vis) sa[i] = -INFINITY;
                     if (key + 32 > vis) sb[i] = -INFINITY;
                 }
@@ -1067,41 +1029,73 @@ void prefill_pp_kernel(const PrefillArgs a) {
     using T1 = std::integral_constant<bool, true>;
     using T0 = std::integral_constant<bool, false>;
 
-    // Both groups walk the same list of phases; group 1 does it one barrier later.  Stage s is complete
-    // (every wave's part landed) at barrier b(2s - 1), one phase before group 0's M(s), so that both
-    // groups can prefetch from it in the vector phase before their M(s).
-    if (group == 1) {
-        landed(1 < nt ? 1 : nt);                       // its parts of stages 0 and 1
-        __builtin_amdgcn_s_barrier();                  // b0
+    // F8, prologue: this lane's pieces of stage t -> bf16, outside a matrix phase
+    auto widen = [&](int t) {
+        const unsigned char* src = &land[F8 ? t % NSTAGE : 0][0] + w_src;
+        unsigned char* dst = &ring[t % NSTAGE][0];
+        Frag lo, hi;
+        fp8x16_to_bf16(*(const uint4*)src, lo, hi);
+        *(uint4*)(dst + w_dst_k) = lo.u;
+        *(uint4*)(dst + (w_dst_k ^ 16)) = hi.u;
+        fp8x16_to_bf16(*(const uint4*)(src + LAND_V), lo, hi);
+        *(uint4*)(dst + w_dst_v) = lo.u;
+        *(uint4*)(dst + (w_dst_v ^ 16)) = hi.u;
+        __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0): read, before the slot is requested again; written
+    };
+
+    // Both groups walk the same list of phases; group 1 does it one barrier later.
+    // bf16: stage s is complete (every wave's part landed) at barrier b(2s - 1), one phase before group
+    // 0's M(s), so that both groups can prefetch from it in the vector phase before their M(s).
+    // F8: a wave keeps three stages of codes in flight; it requests a stage as soon as it has widened the
+    // stage three before it.  Here: stages 0 and 1 (waves 4-7: and 2), the rest in the matrix phases.
+    if constexpr (F8) {
+        landed(0);
+        widen(0);
+        if (nt >= 3) issue();                          // stage 3
+        landed(min(1, nt));
+        widen(1);                                      // (stage 1 always exists: nt >= 1)
+        if (group == 1) {
+            if (nt >= 4) issue();                      // stage 4
+            if (nt >= 2) { landed(2); widen(2); }
+            __builtin_amdgcn_s_barrier();              // b0
+        }
+        __builtin_amdgcn_s_barrier();                  // b0 (group 0) / b1 (group 1): stages 0 and 1 are bf16
+    } else {
+        if (group == 1) {
+            landed(1 < nt ? 1 : nt);                   // its parts of stages 0 and 1
+            __builtin_amdgcn_s_barrier();              // b0
+        }
+        landed(0);
+        __builtin_amdgcn_s_barrier();                  // b0 (group 0) / b1 (group 1)
     }
-    landed(0);
-    __builtin_amdgcn_s_barrier();                      // b0 (group 0) / b1 (group 1)
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(1);
     mphase(0, T0{}, T1{});
     __builtin_amdgcn_s_setprio(0);
-    if (group == 0) landed(1 < nt ? 1 : nt);           // group 0 arrives at b1: stage 1
+    if (!F8 && group == 0) landed(min(1, nt));         // group 0 arrives at b1: stage 1
     // vector phase of key tile t between two barriers; requests stage t + 4 when `more`
     auto vector_part = [&](int t, bool prefetch) {
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_barrier();                  // b(2t + 1) / b(2t + 2)
         __builtin_amdgcn_sched_barrier(0);
         // M(t) of both groups is over once group 1 is here; group 0 learns that one barrier later
-        if (group == 1 && (int)next_t <= nt) issue();       // stage t + 4
+        if (group == 1 && (int)next_t <= nt) issue();       // stage t + 4 (F8: t + 5)
         if (prefetch) prefetch_v(t + 1);
         vphase(t);
-        if (group == 1) landed(min(t + 2, nt));        // group 1 arrives at b(2t + 3): stage t + 2
+        if (!F8 && group == 1) landed(min(t + 2, nt));  // bf16: group 1 arrives at b(2t + 3): stage t + 2
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_barrier();                  // b(2t + 2) / b(2t + 3)
         __builtin_amdgcn_sched_barrier(0);
         if (group == 0 && (int)next_t <= nt) issue();       // stage t + 4
+        if (F8) landed(min(t + 2 + group, nt));        // F8: the codes this wave widens in the matrix phase that follows
     };
     for (int t = 0; t + 1 < nt; ++t) {
         vector_part(t, true);
         __builtin_amdgcn_s_setprio(1);
         mphase(t + 1, T1{}, T1{});
         __builtin_amdgcn_s_setprio(0);
-        if (group == 0) landed(min(t + 2, nt));        // group 0 arrives at b(2t + 3): stage t + 2
+        if (F8) __builtin_amdgcn_s_waitcnt(0xc07f);    // lgkmcnt(0): the widened pieces are written
+        else if (group == 0) landed(min(t + 2, nt));   // group 0 arrives at b(2t + 3): stage t + 2
     }
     // the last key tile: its vector phase, then M(nt) = its PV
     vector_part(nt - 1, !last_is_tail);

@@ -43,6 +43,9 @@ def parse():
                     help="element type of the KV pages (default: the configuration's own, bf16); fp8 = E4M3 pages "
                          "with bf16 queries: 2 048 instead of 4 096 algorithmic bytes per token")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--plan-per-call", action="store_true",
+                    help="decode with kun_paged_decode (plan launch inside every call) instead of one "
+                         "kun_decode_plan per step and kun_paged_decode_planned")
     ap.add_argument("--no-others", action="store_true",
                     help="skip the shorter runs of configurations 3, 4 and 2 that follow the default workload")
     ap.add_argument("--no-mixed", action="store_true",
@@ -115,16 +118,24 @@ def time_steps(cfg, args, block_size=0, q_heads=0, kv_dtype=""):
         dws.append(DeviceWorkload(w, poison=True))
     step_no = [0]
 
+    # The decode work list depends on the context lengths only: a serving step makes it once
+    # (kun_decode_plan) and every layer's decode call runs against it (kun_paged_decode_planned).  The
+    # step does the same: plan first, then append, prefill and the planned decode call, so the plan's
+    # launch is part of the step but not of the decode call.  --plan-per-call: kun_paged_decode instead.
+    planned = not args.plan_per_call
+
     def step(ev=None):
         d = dws[step_no[0] % len(dws)]
         step_no[0] += 1
         if ev: ev[0].record()
+        if planned:
+            d.decode(steps="plan")
         kun.kun_kv_append(d.pool, k_new, v_new, seq_of, pos_of, T_new, all_table, all_table.shape[1])
         if ev: ev[1].record()
         if has_prefill:
             d.prefill()
         if ev: ev[2].record()
-        d.decode()
+        d.decode(steps="planned" if planned else "both")
         if ev: ev[3].record()
 
     if args.pmc_calibration:
@@ -163,8 +174,10 @@ def time_steps(cfg, args, block_size=0, q_heads=0, kv_dtype=""):
         "decode": {"ms": round(t_dec, 4), "ms_median": round(t_dec_med, 4), "algorithmic_bytes": dbytes,
                    "GB_per_s": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
                    "requests_per_s": round(w.S / (t_dec * 1e-3), 1),
-                   "kv_tokens_per_s": round(w.decode_kv_tokens / (t_dec * 1e-3), 1)},
-        "append": {"ms": round(t_app, 4), "tokens": T_new},
+                   "kv_tokens_per_s": round(w.decode_kv_tokens / (t_dec * 1e-3), 1),
+                   "plan": "once per step (kun_decode_plan at the step's start, timed with the append; "
+                           "kun_paged_decode_planned is the call)" if planned else "in every call (kun_paged_decode)"},
+        "append": {"ms": round(t_app, 4), "tokens": T_new, "with_decode_plan": planned},
         "setup_s": round(t_setup, 1),
     }
     if has_prefill:
@@ -207,7 +220,10 @@ def main():
                      "traffic": traffic[0] if traffic else None,
                      "traffic_source": traffic[1] if traffic else None,
                      "kernel": ("decode_partial_mfma_fp8" if sh.dtype == "fp8" else "decode_partial_mfma") +
-                               " (timed with the plan launch in front of it and the merge behind it)"},
+                               (" (the planned call: the kernel, and the merge launch behind it when the batch is "
+                                "large enough to have one; the step's plan launch is timed with the append)"
+                                if not args.plan_per_call else
+                                " (timed with the plan launch in front of it and the merge behind it)")},
         "setup_s": rep["setup_s"],
     }
     if has_prefill:

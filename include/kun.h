@@ -191,6 +191,27 @@ KUN_API int kun_paged_decode(kun_kv_pool* pool, const void* q, void* out, const 
                      int64_t total_ctx_upper_bound, void* workspace, size_t workspace_bytes,
                      void* stream);
 
+/* kun_paged_decode in two steps, for callers that decode the same batch more than once: the work list
+ * of a decode step (which partitions of which request's context a workgroup reads, and where its
+ * partial result goes) depends on the context lengths only, not on q, the pages or the block ids, so
+ * a serving step makes it once and every layer of the model runs against it (Section 2.1: one
+ * batch passes through all layers).  kun_decode_plan writes the list into the workspace (one small
+ * launch); kun_paged_decode_planned is kun_paged_decode without that launch.  Between the two, and
+ * between one planned call and the next, the first kun_decode_workspace_bytes-sized part of the
+ * workspace must be left alone; a planned call must be given the ctx_len contents, S, num_q_heads and
+ * total_ctx_upper_bound of the plan and a pool with the plan's pool's num_kv_heads, head_dim and
+ * dtype (the pool itself, its blocks and the block table may differ: another layer's cache).
+ * Planned calls on one workspace must not overlap in time.  Results are those of kun_paged_decode
+ * bit for bit.  A planned call on a workspace without a matching plan reads an arbitrary list: its
+ * results are undefined (nothing outside out, the workspace and the pool's pages is accessed only as
+ * long as the list is a plan's). */
+KUN_API int kun_decode_plan(kun_kv_pool* pool, const int32_t* ctx_len, int S, int num_q_heads,
+                    int64_t total_ctx_upper_bound, void* workspace, size_t workspace_bytes, void* stream);
+KUN_API int kun_paged_decode_planned(kun_kv_pool* pool, const void* q, void* out, const int32_t* block_table,
+                             int max_blocks, const int32_t* ctx_len, int S, int num_q_heads, float scale,
+                             int64_t total_ctx_upper_bound, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
 /* kun_paged_decode for callers that cannot allocate a workspace (code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc): same operation, arguments, kernels and results,
  * but the split-K records go to a fixed array of KUN_STATIC_SCRATCH_BYTES inside the library's device

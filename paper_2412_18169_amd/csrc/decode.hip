@@ -304,6 +304,10 @@ __device__ __forceinline__ void finish_item(const DecodeArgs& a, int slot, int p
                                         __HIP_MEMORY_SCOPE_AGENT) == nparts - 1;
     __syncthreads();
     if (!s_last) return;
+    // Nobody else touches the counter any more: back to zero, so that a plan (which cleared the
+    // counters once) serves any number of calls.
+    if (threadIdx.x == 0)
+        __hip_atomic_store(&a.arrived[(size_t)seq * a.Hkv + kvh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     merge_records<T, D, true>(a, slot - part, nparts, kvh, seq, G, threadIdx.x, blockDim.x);
 }
 
@@ -1087,9 +1091,10 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
 }
 
 namespace {
+enum DecodeSteps { kPlanAndRun = 0, kPlanOnly = 1, kRunOnly = 2 };
 int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* block_table, int max_blocks,
                    const int32_t* ctx_len, int S, int Hq, float scale, int64_t ub, void* workspace,
-                   size_t workspace_bytes, void* stream);
+                   size_t workspace_bytes, void* stream, DecodeSteps steps = kPlanAndRun);
 }
 
 extern "C" {
@@ -1116,16 +1121,30 @@ int kun_paged_decode(kun_kv_pool* p, const void* q, void* out, const int32_t* bl
                           stream);
 }
 
+int kun_decode_plan(kun_kv_pool* p, const int32_t* ctx_len, int S, int Hq, int64_t ub, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    return decode_enqueue(p, nullptr, nullptr, nullptr, 0, ctx_len, S, Hq, 1.0f, ub, workspace, workspace_bytes,
+                          stream, kPlanOnly);
+}
+
+int kun_paged_decode_planned(kun_kv_pool* p, const void* q, void* out, const int32_t* block_table,
+                             int max_blocks, const int32_t* ctx_len, int S, int Hq, float scale,
+                             int64_t ub, void* workspace, size_t workspace_bytes, void* stream) {
+    return decode_enqueue(p, q, out, block_table, max_blocks, ctx_len, S, Hq, scale, ub, workspace, workspace_bytes,
+                          stream, kRunOnly);
+}
+
 }  // extern "C"
 
 namespace {
 
 int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* block_table,
                    int max_blocks, const int32_t* ctx_len, int S, int Hq, float scale,
-                   int64_t ub, void* workspace, size_t workspace_bytes, void* stream) {
+                   int64_t ub, void* workspace, size_t workspace_bytes, void* stream, DecodeSteps steps) {
     if (!decode_shape_ok(p, S, Hq)) return KUN_ERR_INVALID_ARG;
     if (S == 0) return KUN_OK;
-    if (!q || !out || !block_table || !ctx_len || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
+    if (!ctx_len) return KUN_ERR_INVALID_ARG;
+    if (steps != kPlanOnly && (!q || !out || !block_table || max_blocks <= 0)) return KUN_ERR_INVALID_ARG;
     const int G = Hq / p->Hkv;
     const bool generic_only = kun_options().decode_generic;
     const bool mfma = (p->dtype == KUN_BF16 || p->dtype == KUN_FP8_E4M3) && p->d == 128 && !generic_only;
@@ -1169,9 +1188,12 @@ int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* bloc
     const int merge_opt = kun_options().decode_merge;
     a.fold = merge_opt == 1 || (merge_opt == 0 && ub <= kFoldMaxTokens);
 
-    hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(1024), 0, st, ctx_len, S, P, lay.max_items,
-                       a.n_items, a.seq_first, a.items, a.arrived, S * p->Hkv);
-    KUN_HIP_CHECK_LAUNCH();
+    if (steps != kRunOnly) {
+        hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(1024), 0, st, ctx_len, S, P, lay.max_items,
+                           a.n_items, a.seq_first, a.items, a.arrived, S * p->Hkv);
+        KUN_HIP_CHECK_LAUNCH();
+    }
+    if (steps == kPlanOnly) return KUN_OK;
 
     dim3 grid((unsigned)((size_t)lay.max_items * p->Hkv));
     int rc = KUN_OK;

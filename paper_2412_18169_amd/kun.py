@@ -24,7 +24,8 @@ SYMBOLS = [
     "kun_status_string", "kun_last_hip_error", "kun_set_option", "kun_kv_pool_create", "kun_kv_pool_extend", "kun_kv_pool_num_blocks",
     "kun_kv_pool_num_ranges", "kun_kv_pool_block_bytes", "kun_kv_pool_resolve",
     "kun_kv_pool_destroy", "kun_validate_block_table", "kun_slot_map", "kun_kv_append",
-    "kun_decode_workspace_bytes", "kun_paged_decode", "kun_paged_decode_static", "kun_prefill_workspace_bytes",
+    "kun_decode_workspace_bytes", "kun_paged_decode", "kun_decode_plan", "kun_paged_decode_planned", "kun_paged_decode_static",
+    "kun_prefill_workspace_bytes",
     "kun_paged_prefill_chunk", "kun_paged_prefill_chunk_on", "kun_kv_pool_resize_tail",
     "kun_vmm_region_create", "kun_vmm_region_info", "kun_vmm_region_grow", "kun_vmm_region_move_tail",
     "kun_vmm_region_shrink", "kun_vmm_region_destroy",
@@ -94,6 +95,8 @@ def lib() -> ctypes.CDLL:
     L.kun_decode_workspace_bytes.restype = sz
     L.kun_decode_workspace_bytes.argtypes = [vp, i32, i32, i64]
     L.kun_paged_decode.argtypes = [vp, vp, vp, vp, i32, vp, i32, i32, f32, i64, vp, sz, vp]
+    L.kun_decode_plan.argtypes = [vp, vp, i32, i32, i64, vp, sz, vp]
+    L.kun_paged_decode_planned.argtypes = [vp, vp, vp, vp, i32, vp, i32, i32, f32, i64, vp, sz, vp]
     L.kun_paged_decode_static.argtypes = [vp, vp, vp, vp, i32, vp, i32, i32, f32, i64, vp]
     L.kun_prefill_workspace_bytes.restype = sz
     L.kun_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
@@ -275,6 +278,21 @@ def kun_paged_decode(pool: int, q, out, block_table, max_blocks: int, ctx_len, S
                                   _ptr(ctx_len), int(S), int(num_q_heads), float(scale),
                                   int(total_ctx_upper_bound), _ptr(workspace), int(workspace_bytes),
                                   _stream(stream)), "kun_paged_decode")
+
+
+def kun_decode_plan(pool: int, ctx_len, S: int, num_q_heads: int, total_ctx_upper_bound: int, workspace,
+                    workspace_bytes: int, stream=None) -> None:
+    _check(lib().kun_decode_plan(pool, _ptr(ctx_len), int(S), int(num_q_heads), int(total_ctx_upper_bound),
+                                 _ptr(workspace), int(workspace_bytes), _stream(stream)), "kun_decode_plan")
+
+
+def kun_paged_decode_planned(pool: int, q, out, block_table, max_blocks: int, ctx_len, S: int,
+                             num_q_heads: int, scale: float, total_ctx_upper_bound: int, workspace,
+                             workspace_bytes: int, stream=None) -> None:
+    _check(lib().kun_paged_decode_planned(pool, _ptr(q), _ptr(out), _ptr(block_table), int(max_blocks),
+                                          _ptr(ctx_len), int(S), int(num_q_heads), float(scale),
+                                          int(total_ctx_upper_bound), _ptr(workspace), int(workspace_bytes),
+                                          _stream(stream)), "kun_paged_decode_planned")
 
 
 KUN_STATIC_SCRATCH_BYTES = 32 << 20

@@ -69,8 +69,10 @@ class DeviceWorkload:
 
     # ---- decode ------------------------------------------------------------------------------
     def decode(self, seqs: Optional[Sequence[int]] = None, ctx_bound: Optional[int] = None,
-               stream=None) -> torch.Tensor:
-        """One decode step over all decode requests (or the first `seqs` ones given as a count)."""
+               stream=None, steps: str = "both") -> torch.Tensor:
+        """One decode step over all decode requests (or the first `seqs` ones given as a count).
+        steps: "both" (kun_paged_decode), "plan" (kun_decode_plan only) or "planned"
+        (kun_paged_decode_planned, after a "plan" call with the same arguments)."""
         sh = self.w.shape
         S = self.S if seqs is None else int(seqs)
         if ctx_bound is None:
@@ -78,9 +80,13 @@ class DeviceWorkload:
         need = kun.kun_decode_workspace_bytes(self.pool, S, sh.Hq, ctx_bound)
         if self._ws_dec is None or self._ws_dec.numel() < need:
             self._ws_dec = self._guarded(need, "dec")
-        kun.kun_paged_decode(self.pool, self.q_dec, self.out_dec, self.dec_table,
-                             self.dec_table.shape[1], self.dec_len, S, sh.Hq, sh.scale, ctx_bound,
-                             self._ws_dec, self._ws_dec.numel(), stream)
+        if steps == "plan":
+            kun.kun_decode_plan(self.pool, self.dec_len, S, sh.Hq, ctx_bound, self._ws_dec, self._ws_dec.numel(),
+                                stream)
+            return self.out_dec
+        fn = kun.kun_paged_decode_planned if steps == "planned" else kun.kun_paged_decode
+        fn(self.pool, self.q_dec, self.out_dec, self.dec_table, self.dec_table.shape[1], self.dec_len, S, sh.Hq,
+           sh.scale, ctx_bound, self._ws_dec, self._ws_dec.numel(), stream)
         return self.out_dec
 
     # ---- prefill -----------------------------------------------------------------------------

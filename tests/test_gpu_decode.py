@@ -483,6 +483,63 @@ def test_merge_inside_the_partial_kernel_and_as_a_launch_of_its_own_give_the_sam
     dw.close()
 
 
+@pytest.mark.parametrize("merge", ["fold", "kernel"])
+@pytest.mark.parametrize("dtype,d,G", [("bf16", 128, 4), ("fp8", 128, 8), ("f32", 64, 2)])
+def test_one_plan_serves_many_calls_bit_for_bit(dtype, d, G, merge):
+    # kun_decode_plan + kun_paged_decode_planned = kun_paged_decode: the work list depends on the context
+    # lengths only, so one plan serves every layer of a step.  The planned call runs three times on one
+    # plan (the arrival counters of the folded merge go back to zero by themselves), the second time with
+    # other queries, and once against another pool of the same shape (another layer's cache: other
+    # contents, other block ids) through the first pool's workspace.
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=16, dtype=dtype)
+    lens = [1, 255, 256, 257, 700, 1025, 2049, 3000, 64, 0, 513]
+    w = synth.custom_workload("planned", sh, lens, extra_blocks=3, range_fracs=(0.4, 0.6))
+    w2 = synth.custom_workload("planned-layer-2", sh, lens, seed=11, extra_blocks=9, range_fracs=(0.7, 0.3))
+    kun.kun_set_option("KUN_DECODE_PART", "256")
+    kun.kun_set_option("KUN_DECODE_MERGE", merge)
+    dw, dw2 = DeviceWorkload(w), DeviceWorkload(w2)
+    bits = torch.int32 if dtype == "f32" else torch.int16
+    live = torch.tensor([L > 0 for L in lens], device=dw.dev)
+    q_a = dw.q_dec.clone()
+    q_b = (-2.0 * q_a.float()).to(q_a.dtype)
+    want = {}
+    for name, q in (("a", q_a), ("b", q_b)):
+        dw.q_dec.copy_(q)
+        dw.out_dec.fill_(float("nan"))
+        check_decode(dw)
+        want[name] = dw.out_dec.clone()
+    dw2.out_dec.fill_(float("nan"))
+    check_decode(dw2)
+    want2 = dw2.out_dec.clone()
+
+    dw.decode(steps="plan")
+    for name, q in (("a", q_a), ("b", q_b), ("a", q_a)):
+        dw.q_dec.copy_(q)
+        dw.out_dec.fill_(float("nan"))
+        dw.decode(steps="planned")
+        torch.cuda.synchronize()
+        dw.check_guards()
+        assert torch.equal(dw.out_dec[live].view(bits), want[name][live].view(bits)), name
+        assert torch.isnan(dw.out_dec[~live].float()).all()            # the request of length 0 is left alone
+    # the other pool, through the first one's plan and workspace
+    sh2 = w2.shape
+    ctx_bound = int(np.asarray(lens, dtype=np.int64).sum())
+    dw2.out_dec.fill_(float("nan"))
+    kun.kun_paged_decode_planned(dw2.pool, dw2.q_dec, dw2.out_dec, dw2.dec_table, dw2.dec_table.shape[1], dw.dec_len,
+                                 len(lens), sh2.Hq, sh2.scale, ctx_bound, dw._ws_dec, dw._ws_dec.numel())
+    torch.cuda.synchronize()
+    dw.check_guards()
+    assert torch.equal(dw2.out_dec[live].view(bits), want2[live].view(bits))
+    # and the first pool once more on the same plan
+    dw.q_dec.copy_(q_b)
+    dw.out_dec.fill_(float("nan"))
+    dw.decode(steps="planned")
+    torch.cuda.synchronize()
+    assert torch.equal(dw.out_dec[live].view(bits), want["b"][live].view(bits))
+    dw.close()
+    dw2.close()
+
+
 # ------------------------------------------------------------------------------------------
 # FP8 (E4M3) pages: half the bytes per token; queries and outputs bf16; same tolerance (the
 # oracle reads the same bytes)

@@ -202,9 +202,11 @@ KUN_API int kun_paged_decode(kun_kv_pool* pool, const void* q, void* out, const 
  * total_ctx_upper_bound of the plan and a pool with the plan's pool's num_kv_heads, head_dim and
  * dtype (the pool itself, its blocks and the block table may differ: another layer's cache).
  * Planned calls on one workspace must not overlap in time.  Results are those of kun_paged_decode
- * bit for bit.  A planned call on a workspace without a matching plan reads an arbitrary list: its
- * results are undefined (nothing outside out, the workspace and the pool's pages is accessed only as
- * long as the list is a plan's). */
+ * bit for bit.  The plan leaves a tag of its batch shape in the workspace; a planned call that does not
+ * find the tag it expects (no plan, the plan of another S / bound / head count) launches kernels that
+ * compute nothing, and out is left as it was -- no error is returned, the check is on the device.  A
+ * plan of the same shape made for other lengths cannot be told apart: the call then computes the
+ * attention of the plan's lengths (list entries longer than the block table covers are skipped). */
 KUN_API int kun_decode_plan(kun_kv_pool* pool, const int32_t* ctx_len, int S, int num_q_heads,
                     int64_t total_ctx_upper_bound, void* workspace, size_t workspace_bytes, void* stream);
 KUN_API int kun_paged_decode_planned(kun_kv_pool* pool, const void* q, void* out, const int32_t* block_table,

@@ -55,7 +55,16 @@ struct DecodeArgs {
     unsigned block_bytes, page_bytes;
     int xcd_map;             // MFMA kernel: the KV heads of a work item run on one XCD
     int fold;                // the last workgroup of a (request, kv head) merges its records (else decode_merge_kernel does)
+    int plan_tag;            // what the plan launch left behind n_items: a call on a workspace that holds no plan for
+                             // this batch shape (kun_paged_decode_planned without its plan) computes nothing
 };
+
+// The header of the workspace: list length, tag of the plan that wrote it.
+struct PlanHeader { int n_items, tag; };
+__device__ __forceinline__ PlanHeader load_plan_header(const DecodeArgs& a) {
+    const int2 h = *(const int2*)a.n_items;
+    return PlanHeader{h.x, h.y};
+}
 
 // ---------------------------------------------------------------------------------------------
 // 1. plan
@@ -72,8 +81,9 @@ __global__ __launch_bounds__(1024) void decode_plan_kernel(const int32_t* __rest
                                                          int32_t* __restrict__ n_items,
                                                          int32_t* __restrict__ seq_first,
                                                          int4* __restrict__ items,
-                                                         int32_t* __restrict__ arrived, int n_arrived) {
+                                                         int32_t* __restrict__ arrived, int n_arrived, int tag) {
     for (int i = threadIdx.x; i < n_arrived; i += 1024) arrived[i] = 0;
+    if (threadIdx.x == 0) n_items[1] = tag;
     __shared__ int wave_tot[16], wave_full[16];
     __shared__ int carry_s, carry_full;
     __shared__ int bucket[kLenBuckets];
@@ -330,8 +340,10 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
     __shared__ float sm_acc[NW * G * D];
 
     const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
-    const int n_items = *a.n_items;                    // both loads go out together: the list is as long as the grid
+    const PlanHeader hdr = load_plan_header(a);        // both loads go out together: the list is as long as the grid
+    const int n_items = hdr.n_items;
     const int4 it4 = a.items[item];                    // the length rides along: one dependent load less
+    if (hdr.tag != a.plan_tag || it4.z > a.max_blocks * a.B) return;   // no plan of this batch, or not of this table
     if (item >= n_items || it4.w >= a.max_items) return;   // (a record slot beyond the workspace: the caller's bound was too small)
     const int seq = it4.x, part = it4.y;
     const int L = it4.z;
@@ -495,8 +507,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         item = blockIdx.x / a.Hkv;
         kvh = blockIdx.x % a.Hkv;
     }
-    const int n_items = *a.n_items;                    // both loads go out together
+    const PlanHeader hdr = load_plan_header(a);        // both loads go out together
+    const int n_items = hdr.n_items;
     const int4 it4 = a.items[item < a.max_items ? item : a.max_items - 1];   // the length rides along: one dependent load less
+    if (hdr.tag != a.plan_tag || it4.z > a.max_blocks * a.B) return;   // no plan of this batch, or not of this table
     if (item >= n_items || it4.w >= a.max_items) return;   // (a record slot beyond the workspace: the caller's bound was too small)
     const int seq = it4.x, part = it4.y;
     const int G = a.G;
@@ -736,8 +750,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         item = blockIdx.x / a.Hkv;
         kvh = blockIdx.x % a.Hkv;
     }
-    const int n_items = *a.n_items;
+    const PlanHeader hdr = load_plan_header(a);
+    const int n_items = hdr.n_items;
     const int4 it4 = a.items[item < a.max_items ? item : a.max_items - 1];
+    if (hdr.tag != a.plan_tag || it4.z > a.max_blocks * a.B) return;   // no plan of this batch, or not of this table
     if (item >= n_items || it4.w >= a.max_items) return;
     const int seq = it4.x, part = it4.y;
     const int G = a.G;
@@ -947,6 +963,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a) {
     const int slice = blockIdx.x % kMergeSlices;
     const int seq = blockIdx.x / kMergeSlices / a.Hkv, kvh = blockIdx.x / kMergeSlices % a.Hkv;
+    if (load_plan_header(a).tag != a.plan_tag) return;
     const int L = a.ctx_len[seq];
     const int nparts = (L + a.part_tokens - 1) / a.part_tokens;
     if (nparts <= 1) return;
@@ -964,6 +981,15 @@ constexpr int64_t kFoldMaxTokens = 2000000;   // context tokens up to which the 
 constexpr int kPartDivisor = 1024;    // aim at >= this many (partition, kv head) workgroups
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// What identifies the plan a call expects to find in its workspace (never 0).
+int plan_tag_of(int S, int P, int max_items, int Hkv, int G) {
+    uint32_t h = 0x9e3779b9u;
+    for (uint32_t v : {(uint32_t)S, (uint32_t)P, (uint32_t)max_items, (uint32_t)Hkv, (uint32_t)G}) {
+        h ^= v + 0x9e3779b9u + (h << 6) + (h >> 2);
+    }
+    return (int)(h | 1u);
+}
 
 int64_t default_bound(const kun_kv_pool* p, int S, int64_t ub) {
     const int64_t cap = (int64_t)p->ranges.first[p->ranges.n] * p->B;
@@ -1035,11 +1061,11 @@ int launch_generic_any(const kun_kv_pool* p, const DecodeArgs& a, dim3 grid, hip
 // every row is its own request with one partition: item t = (t, 0)
 __global__ __launch_bounds__(256) void rows_plan_kernel(int T, int32_t* __restrict__ n_items,
                                                         int32_t* __restrict__ seq_first, int4* __restrict__ items,
-                                                        const int32_t* __restrict__ ctx_len) {
+                                                        const int32_t* __restrict__ ctx_len, int tag) {
     for (int t = blockIdx.x * blockDim.x + threadIdx.x; t <= T; t += gridDim.x * blockDim.x) {
         seq_first[t] = t;
         if (t < T) items[t] = make_int4(t, 0, ctx_len[t], 0);
-        if (t == 0) *n_items = T;
+        if (t == 0) { n_items[0] = T; n_items[1] = tag; }
     }
 }
 
@@ -1079,9 +1105,10 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
     a.page_bytes = (unsigned)p->page_bytes;
     a.xcd_map = 0;
     a.fold = 0;
+    a.plan_tag = plan_tag_of(T, 0, T, p->Hkv, a.G);
     const int nb = (T + 256) / 256;
     hipLaunchKernelGGL(rows_plan_kernel, dim3((unsigned)(nb < 1024 ? nb : 1024)), dim3(256), 0, st, T, a.n_items,
-                       a.seq_first, a.items, ctx_len);
+                       a.seq_first, a.items, ctx_len, a.plan_tag);
     KUN_HIP_CHECK_LAUNCH();
     const dim3 grid((unsigned)((size_t)T * p->Hkv));
     const int rc = launch_generic_any(p, a, grid, st);
@@ -1187,10 +1214,11 @@ int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* bloc
     // of every workgroup costs more than the launch: 4 % of a 2.6 ms call).
     const int merge_opt = kun_options().decode_merge;
     a.fold = merge_opt == 1 || (merge_opt == 0 && ub <= kFoldMaxTokens);
+    a.plan_tag = plan_tag_of(S, P, lay.max_items, p->Hkv, G);
 
     if (steps != kRunOnly) {
         hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(1024), 0, st, ctx_len, S, P, lay.max_items,
-                           a.n_items, a.seq_first, a.items, a.arrived, S * p->Hkv);
+                           a.n_items, a.seq_first, a.items, a.arrived, S * p->Hkv, a.plan_tag);
         KUN_HIP_CHECK_LAUNCH();
     }
     if (steps == kPlanOnly) return KUN_OK;

@@ -540,6 +540,36 @@ def test_one_plan_serves_many_calls_bit_for_bit(dtype, d, G, merge):
     dw2.close()
 
 
+def test_a_planned_call_without_its_plan_computes_nothing():
+    # kun_paged_decode_planned on a workspace that holds no plan, or the plan of another batch shape,
+    # finds the wrong tag behind the list length and leaves the outputs alone (no list entry is followed)
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
+    lens = [300, 17, 1025, 64]
+    w = synth.custom_workload("no-plan", sh, lens, extra_blocks=2)
+    kun.kun_set_option("KUN_DECODE_PART", "256")
+    dw = DeviceWorkload(w)
+    dw.decode()                                           # sizes the workspace
+    torch.cuda.synchronize()
+    want = dw.out_dec.clone()
+    for fill in (0x00, 0xFF, 0x5A):                       # no plan at all: arbitrary bytes
+        dw._ws_dec.fill_(fill)
+        dw.out_dec.fill_(float("nan"))
+        dw.decode(steps="planned")
+        torch.cuda.synchronize()
+        dw.check_guards()
+        assert torch.isnan(dw.out_dec.float()).all()
+    dw.decode(seqs=3, steps="plan")                       # the plan of another batch (3 requests)
+    dw.out_dec.fill_(float("nan"))
+    dw.decode(steps="planned")
+    torch.cuda.synchronize()
+    assert torch.isnan(dw.out_dec.float()).all()
+    dw.decode(steps="plan")                               # its own plan: the result of the one-call form
+    dw.decode(steps="planned")
+    torch.cuda.synchronize()
+    assert torch.equal(dw.out_dec.view(torch.int16), want.view(torch.int16))
+    dw.close()
+
+
 # ------------------------------------------------------------------------------------------
 # FP8 (E4M3) pages: half the bytes per token; queries and outputs bf16; same tolerance (the
 # oracle reads the same bytes)

@@ -115,6 +115,14 @@ def test_error_paths():
     assert status(kun.kun_paged_decode, p, BASE, BASE, BASE, 4, BASE, 2, 32, 1.0, 0, BASE, 16, 0) == -6       # workspace small
     assert status(kun.kun_paged_decode, p, BASE, BASE, BASE, 4, BASE, 2, 32, 1.0, 0, BASE + 4, 1 << 30, 0) == -6
     assert status(kun.kun_paged_decode, p, 0, BASE, BASE, 4, BASE, 2, 32, 1.0, 0, BASE, 1 << 30, 0) == -1
+    # ... and so do those of the two-step form
+    assert status(kun.kun_decode_plan, p, 0, 2, 32, 0, BASE, 1 << 30, 0) == -1                  # no lengths
+    assert status(kun.kun_decode_plan, p, BASE, 2, 30, 0, BASE, 1 << 30, 0) == -1               # 30 % 8 != 0
+    assert status(kun.kun_decode_plan, p, BASE, 2, 32, 0, BASE, 16, 0) == -6                    # workspace small
+    assert status(kun.kun_paged_decode_planned, p, 0, BASE, BASE, 4, BASE, 2, 32, 1.0, 0, BASE, 1 << 30, 0) == -1
+    assert status(kun.kun_paged_decode_planned, p, BASE, BASE, BASE, 4, BASE, 2, 32, 1.0, 0, BASE, 16, 0) == -6
+    kun.kun_decode_plan(p, 0, 0, 32, 0, 0, 0, 0)                                               # S == 0: no-op
+    kun.kun_paged_decode_planned(p, 0, 0, 0, 0, 0, 0, 32, 1.0, 0, 0, 0, 0)
     assert status(kun.kun_kv_append, p, 0, BASE, BASE, BASE, 3, BASE, 4, 0) == -1
     kun.kun_kv_append(p, 0, 0, 0, 0, 0, 0, 0, 0)                                               # T == 0: no-op
     kun.kun_paged_decode(p, 0, 0, 0, 0, 0, 0, 32, 1.0, 0, 0, 0, 0)                             # S == 0: no-op

@@ -44,8 +44,8 @@ def parse():
                          "with bf16 queries: 2 048 instead of 4 096 algorithmic bytes per token")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plan-per-call", action="store_true",
-                    help="decode with kun_paged_decode (plan launch inside every call) instead of one "
-                         "kun_decode_plan per step and kun_paged_decode_planned")
+                    help="kun_paged_decode and kun_paged_prefill_chunk (plan launch inside every call) instead "
+                         "of the plans at the step's start and the planned calls")
     ap.add_argument("--no-others", action="store_true",
                     help="skip the shorter runs of configurations 3, 4 and 2 that follow the default workload")
     ap.add_argument("--no-mixed", action="store_true",
@@ -119,9 +119,11 @@ def time_steps(cfg, args, block_size=0, q_heads=0, kv_dtype=""):
     step_no = [0]
 
     # The decode work list depends on the context lengths only: a serving step makes it once
-    # (kun_decode_plan) and every layer's decode call runs against it (kun_paged_decode_planned).  The
-    # step does the same: plan first, then append, prefill and the planned decode call, so the plan's
-    # launch is part of the step but not of the decode call.  --plan-per-call: kun_paged_decode instead.
+    # (kun_decode_plan) and every layer's decode call runs against it (kun_paged_decode_planned); the
+    # prefill plan (work list + resolved block table) needs neither q nor the pages and can be made
+    # ahead of the append.  The step does the same: both plans first, then append and the two planned
+    # calls, so the plan launches are part of the step but not of the calls they serve.
+    # --plan-per-call: kun_paged_decode and kun_paged_prefill_chunk instead.
     planned = not args.plan_per_call
 
     def step(ev=None):
@@ -130,10 +132,12 @@ def time_steps(cfg, args, block_size=0, q_heads=0, kv_dtype=""):
         if ev: ev[0].record()
         if planned:
             d.decode(steps="plan")
+            if has_prefill:
+                d.prefill(steps="plan")
         kun.kun_kv_append(d.pool, k_new, v_new, seq_of, pos_of, T_new, all_table, all_table.shape[1])
         if ev: ev[1].record()
         if has_prefill:
-            d.prefill()
+            d.prefill(steps="planned" if planned else "both")
         if ev: ev[2].record()
         d.decode(steps="planned" if planned else "both")
         if ev: ev[3].record()
@@ -177,7 +181,7 @@ def time_steps(cfg, args, block_size=0, q_heads=0, kv_dtype=""):
                    "kv_tokens_per_s": round(w.decode_kv_tokens / (t_dec * 1e-3), 1),
                    "plan": "once per step (kun_decode_plan at the step's start, timed with the append; "
                            "kun_paged_decode_planned is the call)" if planned else "in every call (kun_paged_decode)"},
-        "append": {"ms": round(t_app, 4), "tokens": T_new, "with_decode_plan": planned},
+        "append": {"ms": round(t_app, 4), "tokens": T_new, "with_the_plan_launches": planned},
         "setup_s": round(t_setup, 1),
     }
     if has_prefill:
@@ -185,7 +189,10 @@ def time_steps(cfg, args, block_size=0, q_heads=0, kv_dtype=""):
         tf = fl / (t_pre * 1e-3) / 1e12
         rep["prefill"] = {"ms": round(t_pre, 4), "flops": fl, "TFLOP_per_s": round(tf, 1),
                           "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                          "new_tokens_per_s": round(dw.total_new / (t_pre * 1e-3), 1)}
+                          "new_tokens_per_s": round(dw.total_new / (t_pre * 1e-3), 1),
+                          "plan": "at the step's start (kun_prefill_plan, timed with the append; "
+                                  "kun_paged_prefill_chunk_planned is the call)" if planned
+                                  else "in every call (kun_paged_prefill_chunk)"}
     return rep, dw, dws
 
 

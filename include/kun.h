@@ -253,6 +253,25 @@ KUN_API int kun_paged_prefill_chunk(kun_kv_pool* pool, const void* q, void* out,
                             int n_chunks, int num_q_heads, int total_new_tokens, float scale,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* kun_paged_prefill_chunk in two steps.  kun_prefill_plan makes the call's work list and resolves the
+ * block table into page addresses (one small launch; it reads q_start, prior_len, block_table and the
+ * pool's ranges, not q or the pages, so it can be enqueued before the kun_kv_append of the same step,
+ * or on another stream while the layer before runs); kun_paged_prefill_chunk_planned is the rest of
+ * the call and finds that plan in the workspace.  Unlike a decode plan it holds addresses: it serves
+ * this pool as it is (extending the pool afterwards is fine, moving its tail is not) and this block
+ * table; the planned call takes the same q_start, prior_len, block_table, max_blocks, n_chunks,
+ * num_q_heads and total_new_tokens, and the workspace must be left alone in between.  Results are
+ * those of kun_paged_prefill_chunk bit for bit; a planned call that does not find the tag of a plan of
+ * its batch shape computes nothing and leaves out as it was.  Pools served row by row (fp32,
+ * head_dim 64) plan inside the planned call; kun_prefill_plan is a no-op for them. */
+KUN_API int kun_prefill_plan(kun_kv_pool* pool, const int32_t* q_start, const int32_t* prior_len,
+                     const int32_t* block_table, int max_blocks, int n_chunks, int num_q_heads,
+                     int total_new_tokens, void* workspace, size_t workspace_bytes, void* stream);
+KUN_API int kun_paged_prefill_chunk_planned(kun_kv_pool* pool, const void* q, void* out, const int32_t* q_start,
+                                    const int32_t* prior_len, const int32_t* block_table, int max_blocks,
+                                    int n_chunks, int num_q_heads, int total_new_tokens, float scale,
+                                    void* workspace, size_t workspace_bytes, void* stream);
+
 /* Mixed batches (Section 2.1: prefill is compute-bound, decode memory-bound, and serving systems
  * batch the two): the same operation, results and workspace as kun_paged_prefill_chunk, but run by
  * at most max_workgroups workgroups (> 0; rounded down to a multiple of 8, at least 8) that fetch

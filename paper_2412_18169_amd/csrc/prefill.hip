@@ -74,6 +74,8 @@ struct PrefillArgs {
     float scale_log2;
     unsigned block_bytes, page_bytes;
     int sub_shift;           // log2 of the 16-token page tiles per KV block (0 .. 3): page tile i of a request is tile i % 2^shift of block i >> shift
+    int plan_tag;            // what the plan launch left behind n_items: a call on a workspace without a plan of this
+                             // batch shape (kun_paged_prefill_chunk_planned without its plan) computes nothing
 };
 
 // sixteen FP8 (E4M3) codes -> two MFMA operands of eight bf16 each (codes 0..7, codes 8..15); exact
@@ -171,7 +173,8 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const Resolv
                                                                   int2* __restrict__ split_info,
                                                                   int4* __restrict__ split_items,
                                                                   int32_t* __restrict__ n_split_items,
-                                                                  int4* __restrict__ desc) {
+                                                                  int4* __restrict__ desc, int tag) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) n_items[1] = tag;
     if (blockIdx.x > 0) {      // workgroups 1 .. n_wgs resolve the blocks; workgroup 0 makes the work list
         resolve_tiles(ra.rt, q_start, prior, ra.table, n_chunks, ra.max_blocks, ra.sub_shift, ra.block_bytes,
                       ra.tile_bytes, ra.page_addr, 1, ra.n_wgs);
@@ -363,8 +366,10 @@ void prefill_ring_kernel(const PrefillArgs a) {
         wi = s_next;
     }
     const int item = wi / a.Hkv, kvh = wi % a.Hkv;
-    if (PERSIST && item >= *a.n_items) return;         // (fetched indices can run past the list's capacity)
-    const int n_items = PERSIST ? item + 1 : *a.n_items;   // plain launch: the grid is within the capacity, so the
+    const int2 hdr = *(const int2*)a.n_items;          // list length, tag of the plan that wrote it
+    if (hdr.y != a.plan_tag) return;
+    if (PERSIST && item >= hdr.x) return;              // (fetched indices can run past the list's capacity)
+    const int n_items = PERSIST ? item + 1 : hdr.x;        // plain launch: the grid is within the capacity, so the
     const int4 d0 = a.desc[2 * item], d1 = a.desc[2 * item + 1];     // entry is read together with the list's length
     if (item >= n_items) return;
     const int chunk = d0.x, qt = d0.y, p = d0.z, qs = d0.w, c = d1.x;
@@ -735,8 +740,10 @@ void prefill_pp_kernel(const PrefillArgs a) {
     }
     wi = __builtin_amdgcn_readfirstlane(wi);
     const int item = wi / a.Hkv, kvh = wi % a.Hkv;
-    if (PERSIST && item >= *a.n_items) return;
-    const int n_items = PERSIST ? item + 1 : *a.n_items;
+    const int2 hdr = *(const int2*)a.n_items;          // list length, tag of the plan that wrote it
+    if (hdr.y != a.plan_tag) return;
+    if (PERSIST && item >= hdr.x) return;
+    const int n_items = PERSIST ? item + 1 : hdr.x;
     const int4 d0 = a.desc[2 * item], d1 = a.desc[2 * item + 1];
     if (item >= n_items) return;
     const int chunk = d0.x, qt = d0.y, p = d0.z, qs = d0.w, c = d1.x;
@@ -1140,7 +1147,7 @@ __global__ __launch_bounds__(kSplitRows) void prefill_merge_kernel(const Prefill
     constexpr int NDC = D / kMergeDims;
     const int dc = blockIdx.x % NDC;
     const int si = blockIdx.x / NDC / a.Hkv, kvh = blockIdx.x / NDC % a.Hkv;
-    if (si >= *a.n_split_items) return;
+    if (a.n_items[1] != a.plan_tag || si >= *a.n_split_items) return;
     const int4 it = a.split_items[si];
     const int chunk = it.x, qt = it.y, nsplit = it.z, slot0 = it.w;
     const int qs = a.q_start[chunk];
@@ -1279,17 +1286,33 @@ namespace {
 // max_workgroups == 0: one workgroup per work item (or, with the option "persistent", one fetching
 // workgroup per compute unit); otherwise that many workgroups (rounded down to a multiple of 8, at
 // least 8) fetch the items.
+// steps: the plan launch and the rest (kPlanAndRun), or one of the two.
+enum PrefillSteps { kPlanAndRun = 0, kPlanOnly = 1, kRunOnly = 2 };
+
+// What identifies the plan a call expects to find in its workspace (never 0).
+int prefill_plan_tag(int n_chunks, int total_new_tokens, int max_blocks, int Hkv, int G, int sub_shift) {
+    uint32_t h = 0x85ebca6bu;
+    for (uint32_t v : {(uint32_t)n_chunks, (uint32_t)total_new_tokens, (uint32_t)max_blocks, (uint32_t)Hkv, (uint32_t)G,
+                       (uint32_t)sub_shift}) {
+        h ^= v + 0x9e3779b9u + (h << 6) + (h >> 2);
+    }
+    return (int)(h | 1u);
+}
+
 int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_start, const int32_t* prior_len,
                     const int32_t* block_table, int max_blocks, int n_chunks, int Hq, int total_new_tokens,
-                    float scale, int max_workgroups, void* workspace, size_t workspace_bytes, void* stream) {
+                    float scale, int max_workgroups, void* workspace, size_t workspace_bytes, void* stream,
+                    PrefillSteps steps = kPlanAndRun) {
     if (!prefill_shape_ok(p, n_chunks, Hq, total_new_tokens, max_blocks) || max_workgroups < 0) return KUN_ERR_INVALID_ARG;
     if (n_chunks == 0 || total_new_tokens == 0) return KUN_OK;
-    if (!q || !out || !q_start || !prior_len || !block_table || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
+    if (!q_start || !prior_len || !block_table || max_blocks <= 0) return KUN_ERR_INVALID_ARG;
+    if (steps != kPlanOnly && (!q || !out)) return KUN_ERR_INVALID_ARG;
     const int G = Hq / p->Hkv;
     if (G < 1 || (G > 8 && !(G == 16 && mfma_shape(p)))) return KUN_ERR_UNSUPPORTED;   // 16: the MFMA kernels only
     const size_t need = kun_prefill_workspace_bytes(p, n_chunks, Hq, total_new_tokens, max_blocks);
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < need) return KUN_ERR_WORKSPACE;
     if (!mfma_shape(p)) {
+        if (steps == kPlanOnly) return KUN_OK;             // (row by row: the rows' list is made by the call itself)
         const size_t col = align256(sizeof(int32_t) * (size_t)total_new_tokens);
         int32_t* ctx_len = (int32_t*)((char*)workspace + 256);
         int32_t* row_of_seq = (int32_t*)((char*)workspace + 256 + col);
@@ -1301,7 +1324,9 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
                                        scale, (char*)workspace + 256 + 2 * col, st);
     }
 
-    bool persistent = max_workgroups > 0 || kun_options().prefill_shape == 1 || kun_options().prefill_shape == 3;
+    // (fetching workgroups count through the list with counters that only the plan launch clears)
+    bool persistent = steps == kPlanAndRun &&
+                      (max_workgroups > 0 || kun_options().prefill_shape == 1 || kun_options().prefill_shape == 3);
     if (persistent && max_workgroups == 0) max_workgroups = device_compute_units();
     const int pos_per_tile = kSplitRows / G;
     const PrefillLayout lay = prefill_layout(p, n_chunks, Hq, total_new_tokens, max_blocks);
@@ -1347,11 +1372,15 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     ra.tile_bytes = (unsigned)(2 * kBlock * D * p->elt);
     const size_t n_entries = (size_t)n_chunks * (size_t)a.tiles_per_row;
     ra.n_wgs = (int)((n_entries + kPlanThreads - 1) / kPlanThreads < 1024 ? (n_entries + kPlanThreads - 1) / kPlanThreads : 1024);
-    hipLaunchKernelGGL(prefill_plan_kernel, dim3(1 + ra.n_wgs), dim3(kPlanThreads), 0, st, ra, q_start, prior_len,
-                       n_chunks, pos_per_tile, a.max_items, a.n_items, a.next_item, a.items, p->Hkv,
-                       can_split ? kSplitTarget : 0, lay.cap_entries, (int2*)(ws + lay.off_split_info), a.split_items,
-                       a.n_split_items, (int4*)(ws + lay.off_desc));
-    KUN_HIP_CHECK_LAUNCH();
+    a.plan_tag = prefill_plan_tag(n_chunks, total_new_tokens, max_blocks, p->Hkv, G, a.sub_shift);
+    if (steps != kRunOnly) {
+        hipLaunchKernelGGL(prefill_plan_kernel, dim3(1 + ra.n_wgs), dim3(kPlanThreads), 0, st, ra, q_start, prior_len,
+                           n_chunks, pos_per_tile, a.max_items, a.n_items, a.next_item, a.items, p->Hkv,
+                           can_split ? kSplitTarget : 0, lay.cap_entries, (int2*)(ws + lay.off_split_info),
+                           a.split_items, a.n_split_items, (int4*)(ws + lay.off_desc), a.plan_tag);
+        KUN_HIP_CHECK_LAUNCH();
+    }
+    if (steps == kPlanOnly) return KUN_OK;
     size_t wgs = (size_t)(can_split ? lay.cap_entries : lay.max_items) * p->Hkv;
     if (persistent) {
         const size_t lim = max_workgroups < 8 ? 8 : (size_t)(max_workgroups & ~7);
@@ -1389,6 +1418,21 @@ extern "C" int kun_paged_prefill_chunk(kun_kv_pool* p, const void* q, void* out,
                                        void* workspace, size_t workspace_bytes, void* stream) {
     return prefill_enqueue(p, q, out, q_start, prior_len, block_table, max_blocks, n_chunks, Hq, total_new_tokens,
                            scale, 0, workspace, workspace_bytes, stream);
+}
+
+extern "C" int kun_prefill_plan(kun_kv_pool* p, const int32_t* q_start, const int32_t* prior_len,
+                               const int32_t* block_table, int max_blocks, int n_chunks, int Hq,
+                               int total_new_tokens, void* workspace, size_t workspace_bytes, void* stream) {
+    return prefill_enqueue(p, nullptr, nullptr, q_start, prior_len, block_table, max_blocks, n_chunks, Hq,
+                           total_new_tokens, 1.0f, 0, workspace, workspace_bytes, stream, kPlanOnly);
+}
+
+extern "C" int kun_paged_prefill_chunk_planned(kun_kv_pool* p, const void* q, void* out, const int32_t* q_start,
+                                               const int32_t* prior_len, const int32_t* block_table, int max_blocks,
+                                               int n_chunks, int Hq, int total_new_tokens, float scale,
+                                               void* workspace, size_t workspace_bytes, void* stream) {
+    return prefill_enqueue(p, q, out, q_start, prior_len, block_table, max_blocks, n_chunks, Hq, total_new_tokens,
+                           scale, 0, workspace, workspace_bytes, stream, kRunOnly);
 }
 
 extern "C" int kun_paged_prefill_chunk_on(kun_kv_pool* p, const void* q, void* out, const int32_t* q_start,

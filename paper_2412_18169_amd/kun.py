@@ -26,7 +26,7 @@ SYMBOLS = [
     "kun_kv_pool_destroy", "kun_validate_block_table", "kun_slot_map", "kun_kv_append",
     "kun_decode_workspace_bytes", "kun_paged_decode", "kun_decode_plan", "kun_paged_decode_planned", "kun_paged_decode_static",
     "kun_prefill_workspace_bytes",
-    "kun_paged_prefill_chunk", "kun_paged_prefill_chunk_on", "kun_kv_pool_resize_tail",
+    "kun_paged_prefill_chunk", "kun_prefill_plan", "kun_paged_prefill_chunk_planned", "kun_paged_prefill_chunk_on", "kun_kv_pool_resize_tail",
     "kun_vmm_region_create", "kun_vmm_region_info", "kun_vmm_region_grow", "kun_vmm_region_move_tail",
     "kun_vmm_region_shrink", "kun_vmm_region_destroy",
     "kun_cost_chunk", "kun_cost_microbatch", "kun_cost_fit", "kun_lookahead", "kun_drop_plan",
@@ -101,6 +101,8 @@ def lib() -> ctypes.CDLL:
     L.kun_prefill_workspace_bytes.restype = sz
     L.kun_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     L.kun_paged_prefill_chunk.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]
+    L.kun_prefill_plan.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
+    L.kun_paged_prefill_chunk_planned.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]
     L.kun_paged_prefill_chunk_on.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, sz, vp]
     for name in SYMBOLS:
         if name not in ("kun_status_string", "kun_last_hip_error", "kun_decode_workspace_bytes",
@@ -319,6 +321,23 @@ def kun_paged_prefill_chunk(pool: int, q, out, q_start, prior_len, block_table, 
                                          int(num_q_heads), int(total_new_tokens), float(scale),
                                          _ptr(workspace), int(workspace_bytes), _stream(stream)),
            "kun_paged_prefill_chunk")
+
+
+def kun_prefill_plan(pool: int, q_start, prior_len, block_table, max_blocks: int, n_chunks: int,
+                     num_q_heads: int, total_new_tokens: int, workspace, workspace_bytes: int, stream=None) -> None:
+    _check(lib().kun_prefill_plan(pool, _ptr(q_start), _ptr(prior_len), _ptr(block_table), int(max_blocks),
+                                  int(n_chunks), int(num_q_heads), int(total_new_tokens), _ptr(workspace),
+                                  int(workspace_bytes), _stream(stream)), "kun_prefill_plan")
+
+
+def kun_paged_prefill_chunk_planned(pool: int, q, out, q_start, prior_len, block_table, max_blocks: int,
+                                    n_chunks: int, num_q_heads: int, total_new_tokens: int, scale: float,
+                                    workspace, workspace_bytes: int, stream=None) -> None:
+    _check(lib().kun_paged_prefill_chunk_planned(pool, _ptr(q), _ptr(out), _ptr(q_start), _ptr(prior_len),
+                                                 _ptr(block_table), int(max_blocks), int(n_chunks),
+                                                 int(num_q_heads), int(total_new_tokens), float(scale),
+                                                 _ptr(workspace), int(workspace_bytes), _stream(stream)),
+           "kun_paged_prefill_chunk_planned")
 
 
 def kun_paged_prefill_chunk_on(pool: int, q, out, q_start, prior_len, block_table, max_blocks: int,

@@ -90,13 +90,25 @@ class DeviceWorkload:
         return self.out_dec
 
     # ---- prefill -----------------------------------------------------------------------------
-    def prefill(self, stream=None, max_workgroups: int = 0) -> torch.Tensor:
-        """All prefill chunks; max_workgroups > 0 runs them on that many workgroups (mixed batches)."""
+    def prefill(self, stream=None, max_workgroups: int = 0, steps: str = "both") -> torch.Tensor:
+        """All prefill chunks; max_workgroups > 0 runs them on that many workgroups (mixed batches).
+        steps: "both" (kun_paged_prefill_chunk), "plan" (kun_prefill_plan only) or "planned"
+        (kun_paged_prefill_chunk_planned, after a "plan" call)."""
         sh = self.w.shape
         need = kun.kun_prefill_workspace_bytes(self.pool, self.n_chunks, sh.Hq, self.total_new,
                                                self.pre_table.shape[1])
         if self._ws_pre is None or self._ws_pre.numel() < need:
             self._ws_pre = self._guarded(max(need, 256), "pre")
+        if steps == "plan":
+            kun.kun_prefill_plan(self.pool, self.q_start, self.prior, self.pre_table, self.pre_table.shape[1],
+                                 self.n_chunks, sh.Hq, self.total_new, self._ws_pre, self._ws_pre.numel(), stream)
+            return self.out_pre
+        if steps == "planned":
+            kun.kun_paged_prefill_chunk_planned(self.pool, self.q_pre, self.out_pre, self.q_start, self.prior,
+                                                self.pre_table, self.pre_table.shape[1], self.n_chunks, sh.Hq,
+                                                self.total_new, sh.scale, self._ws_pre, self._ws_pre.numel(),
+                                                stream)
+            return self.out_pre
         if max_workgroups > 0:
             kun.kun_paged_prefill_chunk_on(self.pool, self.q_pre, self.out_pre, self.q_start, self.prior,
                                            self.pre_table, self.pre_table.shape[1], self.n_chunks, sh.Hq,

@@ -123,6 +123,17 @@ def test_error_paths():
     assert status(kun.kun_paged_decode_planned, p, BASE, BASE, BASE, 4, BASE, 2, 32, 1.0, 0, BASE, 16, 0) == -6
     kun.kun_decode_plan(p, 0, 0, 32, 0, 0, 0, 0)                                               # S == 0: no-op
     kun.kun_paged_decode_planned(p, 0, 0, 0, 0, 0, 0, 32, 1.0, 0, 0, 0, 0)
+    # prefill: the same checks, in one call and in two
+    assert kun.kun_prefill_workspace_bytes(p, 2, 30, 64, 8) == 0                               # 30 % 8 != 0
+    for fn in (kun.kun_paged_prefill_chunk, kun.kun_paged_prefill_chunk_planned):
+        assert status(fn, p, BASE, BASE, BASE, BASE, BASE, 8, 2, 30, 64, 1.0, BASE, 1 << 30, 0) == -1
+        assert status(fn, p, BASE, BASE, BASE, BASE, BASE, 8, 2, 72, 64, 1.0, BASE, 1 << 30, 0) == -8   # G = 9
+        assert status(fn, p, 0, BASE, BASE, BASE, BASE, 8, 2, 32, 64, 1.0, BASE, 1 << 30, 0) == -1      # no q
+        assert status(fn, p, BASE, BASE, BASE, BASE, BASE, 8, 2, 32, 64, 1.0, BASE, 16, 0) == -6        # workspace small
+        fn(p, 0, 0, 0, 0, 0, 0, 0, 32, 0, 1.0, 0, 0, 0)                                        # nothing to do
+    assert status(kun.kun_prefill_plan, p, 0, BASE, BASE, 8, 2, 32, 64, BASE, 1 << 30, 0) == -1    # no q_start
+    assert status(kun.kun_prefill_plan, p, BASE, BASE, BASE, 8, 2, 32, 64, BASE + 8, 1 << 30, 0) == -6
+    kun.kun_prefill_plan(p, 0, 0, 0, 0, 0, 32, 0, 0, 0, 0)
     assert status(kun.kun_kv_append, p, 0, BASE, BASE, BASE, 3, BASE, 4, 0) == -1
     kun.kun_kv_append(p, 0, 0, 0, 0, 0, 0, 0, 0)                                               # T == 0: no-op
     kun.kun_paged_decode(p, 0, 0, 0, 0, 0, 0, 32, 1.0, 0, 0, 0, 0)                             # S == 0: no-op

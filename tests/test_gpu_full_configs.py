@@ -171,7 +171,7 @@ def test_seeded_random_shapes_lengths_and_pools(seed):
 @pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
 def test_config5_150GB_pool_sampled(kv_dtype):
     # sample: the 16 shortest, the 16 longest and 32 random decode requests, every head; first, last and
-    # 128 random rows of every chunk (FP8 pages: a quarter of that, its prefill runs on the vector ALUs)
+    # 128 random rows of every chunk (FP8 pages: a quarter of that)
     w = synth.config(5, kv_dtype="" if kv_dtype == "bf16" else kv_dtype)
     dw = DeviceWorkload(w, poison=False)
     assert kun.kun_kv_pool_num_ranges(dw.pool) == 5
@@ -179,10 +179,20 @@ def test_config5_150GB_pool_sampled(kv_dtype):
     used = np.concatenate(w.block_tables).astype(np.int64)
     r, _ = synth.range_of_blocks(w.range_blocks, used)
     assert set(np.unique(r)) == {0, 1, 2, 3, 4} and used.max() > 2**21     # ids beyond 2^21: 64-bit offsets matter
-    pre = dw.prefill().clone()
-    out = dw.decode().clone()
+    # as bench.py launches them: both plans first, then the planned calls ...
+    dw.decode(steps="plan")
+    dw.prefill(steps="plan")
+    pre = dw.prefill(steps="planned").clone()
+    out = dw.decode(steps="planned").clone()
+    # ... and the one-call forms: the same bits
+    dw.out_pre.fill_(float("nan"))
+    dw.out_dec.fill_(float("nan"))
+    pre1 = dw.prefill().clone()
+    out1 = dw.decode().clone()
     torch.cuda.synchronize()
     dw.check_guards()
+    assert torch.equal(pre.view(torch.int16), pre1.view(torch.int16))
+    assert torch.equal(out.view(torch.int16), out1.view(torch.int16))
     rows = sample_rows(w, 16, 32) if kv_dtype == "bf16" else sample_rows(w, 4, 8)
     err = decode_err(dw, out, rows)
     print(f"cfg5 decode ({len(rows)} sampled requests) max err {err:.3e}")

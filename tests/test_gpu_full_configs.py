@@ -260,9 +260,12 @@ def test_slot_map_matches_oracle_for_every_token(dtype, d, B):
     dw.close()
 
 
-def test_step_captured_in_a_hip_graph_replays_bit_identically():
+@pytest.mark.parametrize("form", ["one-call", "plans-in-the-graph", "plans-before-the-graph"])
+def test_step_captured_in_a_hip_graph_replays_bit_identically(form):
     # append + prefill + decode only enqueue kernels (no allocation, no memset nodes), so a step can be
-    # captured once and replayed; every replay, with eager work in between, gives the eager bits
+    # captured once and replayed; every replay, with eager work in between, gives the eager bits.  The
+    # two-step forms: with the plan launches captured too, or made once before the capture (every replay
+    # then runs the planned calls against the same plans: the decode counters clean up after themselves)
     sh = synth.SHAPE_8B
     w = synth.custom_workload("graph", sh, [900, 3000, 17, 1500, 64] * 6, chunks=[(0, 300), (1024, 512), (300, 100)],
                               extra_blocks=4, range_fracs=(0.5, 0.5))
@@ -276,16 +279,25 @@ def test_step_captured_in_a_hip_graph_replays_bit_identically():
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
+    if form == "plans-before-the-graph":
+        dw.decode(steps="plan")
+        dw.prefill(steps="plan")
+        torch.cuda.synchronize()
     with torch.cuda.graph(g, stream=side):
+        if form == "plans-in-the-graph":
+            dw.decode(steps="plan")
+            dw.prefill(steps="plan")
         kun.kun_kv_append(dw.pool, k, v, seq_of, pos_of, 1, table, table.shape[1])
-        dw.prefill()
-        dw.decode()
+        dw.prefill(steps="both" if form == "one-call" else "planned")
+        dw.decode(steps="both" if form == "one-call" else "planned")
     for rep in range(4):
         dw.out_pre.fill_(float("nan"))
         dw.out_dec.fill_(float("nan"))
-        if rep % 2:
+        if rep % 2 and form != "plans-before-the-graph":  # (eager calls would overwrite the plans in the workspaces)
             dw.decode(5)                                  # eager work between replays, on the same buffers
             dw.out_dec.fill_(float("nan"))
+        elif rep % 2:
+            dw.q_dec.add_(0)                              # some eager work on the same stream
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()

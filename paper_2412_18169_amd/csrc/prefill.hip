@@ -1,5 +1,5 @@
-// Chunked prefill over paged K/V: bf16, head_dim 128, pages of 16-token tiles (blocks of 16 to 128
-// tokens), MFMA 32x32x16 with fp32 accumulation.
+// Chunked prefill over paged K/V: bf16 or FP8 (E4M3) pages, bf16 queries, head_dim 128, pages of
+// 16-token tiles (blocks of 16 to 128 tokens), MFMA 32x32x16 bf16 with fp32 accumulation.
 //
 // A chunk of c new tokens after p prior tokens attends to keys 0 .. p + r for its row r
 // (Section 4.3, Eq. 1: prefix attention p*c plus causal self attention (c*c + c)/2 pairs).  This is
@@ -7,8 +7,8 @@
 //
 // Work item = (chunk, tile of query positions, kv head).  The G query heads that share the kv head
 // are stacked into the row dimension (row = position * G + head), so a K/V tile staged in LDS
-// serves all of them.  A workgroup has 8 waves (4 or 12 in the variants); each wave owns 32 (* NQ)
-// rows and walks the keys in tiles of 64 (four page tiles), flash-attention style:
+// serves all of them.  A workgroup has 8 waves; each wave owns 32 rows and walks the keys in tiles
+// of 64 (four page tiles), flash-attention style:
 //
 //   S^T[key][row]  = K[key][:] . Q[row][:]          A = K fragment from LDS, B = Q in registers
 //   online softmax over keys, per row: each lane column holds one row, so max/sum are in-lane
@@ -126,7 +126,7 @@ constexpr int kSplitRows = 256;         // rows of a workgroup of the kernels th
 
 // Block resolution for the whole launch, once per 16-token tile instead of once per (tile, query tile,
 // kv head).  A chunk's row has four entries per 64-key tile, for every key tile that its table row can
-// hold and one more; the entry of page tile s of key tile kt sits at 4 kt + kTilePlace[s], so that the
+// hold and one more; the entry of page tile s of key tile kt sits at 4 kt + kun_tile_place(s), so that the
 // two page tiles a wave loads (s and s + 2) lie side by side and come with one 16-byte scalar load.
 // Entry = address (KV head 0) of 16-token tile min(4 kt + s, last tile of the context) of the request:
 // tile t is tile t % (B / 16) of block table[i][t / (B / 16)].  Tiles past the context repeat the last
@@ -316,8 +316,9 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const Resolv
 }
 
 // ---------------------------------------------------------------------------------------------
-// Ring variant (default): 8 waves x 32 rows, 64-key tiles in a 4-stage LDS ring filled by direct
-// global->LDS loads (no registers, no LDS stores), three tiles in flight, ONE barrier per tile.
+// Ring variant (the cross-check of the ping-pong kernel further down, which is the default): 8 waves
+// x 32 rows, 64-key tiles in a 4-stage LDS ring filled by direct global->LDS loads (no registers, no
+// LDS stores), three tiles in flight, ONE barrier per tile.
 //
 // Every q tile of a (chunk, kv head) walks the same keys at about the same time, so a tile load sees
 // close to the full memory latency, not an L2 hit; the ring keeps ~96 KiB in flight per CU to cover it.

@@ -1,6 +1,7 @@
 """Seeded random workloads against the CPU oracle through the C ABI: every page type, head_dim, block
 size and group size the library takes, ragged lengths (zero included), one to three pool ranges, any
-split-K partition size and merge mode, the one-call and the planned forms of decode and prefill.
+split-K partition size and merge mode, the one-call and the planned forms of decode and prefill, decode
+out of the library's fixed scratch array and prefill on a capped number of workgroups.
 Tolerances as in the other GPU tests (1e-5 fp32, 2e-2 bf16 and FP8 pages)."""
 import numpy as np
 import pytest
@@ -69,4 +70,20 @@ def test_random_workloads(seed):
                 assert torch.equal(got.view(torch.int16), dw.out_pre.view(torch.int16))
             else:
                 check_prefill(dw)
+            if on_matrix_cores and bool(rng.integers(0, 2)):        # fetching workgroups: the bits of the plain launch
+                ref = dw.out_pre.clone()
+                got = dw.prefill(max_workgroups=int(rng.choice([8, 24, 64, 512])))
+                torch.cuda.synchronize()
+                assert torch.equal(got.view(torch.int16), ref.view(torch.int16))
+        if bool(rng.integers(0, 2)):                                # no workspace argument: same kernels, same bits
+            bound = int(w.decode_lens.astype(np.int64).sum())
+            if 0 < kun.kun_decode_workspace_bytes(dw.pool, w.S, sh.Hq, bound) <= kun.KUN_STATIC_SCRATCH_BYTES:
+                ref = dw.decode().clone()
+                out = torch.full_like(dw.q_dec, 3.0)
+                kun.kun_paged_decode_static(dw.pool, dw.q_dec, out, dw.dec_table, dw.dec_table.shape[1], dw.dec_len,
+                                            w.S, sh.Hq, sh.scale, bound)
+                torch.cuda.synchronize()
+                live = torch.tensor(w.decode_lens > 0, device=out.device)
+                assert torch.equal(out[live].view(torch.uint8), ref[live].view(torch.uint8))
+                assert (out[~live] == 3.0).all()
         dw.close()

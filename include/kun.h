@@ -179,7 +179,8 @@ KUN_API size_t kun_decode_workspace_bytes(const kun_kv_pool* pool, int S, int nu
  * and is memory-bound).  q, out: device [S, num_q_heads, head_dim] in the pool's dtype (bf16 for FP8 pools); request s
  * has ctx_len[s] tokens in its pages INCLUDING the token being decoded, whose query is row s of q;
  * out[s] = softmax(scale * q K^T) V over those tokens.  ctx_len: device int32 [S]; a request with
- * ctx_len 0 is skipped and its output row left untouched.  block_table: device int32
+ * ctx_len 0 (or below, or above the max_blocks * block_size tokens its table row can hold) is
+ * skipped and its output row left untouched.  block_table: device int32
  * [S, max_blocks].  total_ctx_upper_bound: host-known bound on sum(ctx_len) (0 = full pool); it
  * sizes the launch and must be the value used for kun_decode_workspace_bytes or smaller; the
  * split-K partition size is chosen from it, so a bound close to the real sum is faster than 0.  If
@@ -245,7 +246,11 @@ KUN_API size_t kun_prefill_workspace_bytes(const kun_kv_pool* pool, int n_chunks
  * back to back; q_start: device int32 [n_chunks + 1], row offsets with q_start[n_chunks] ==
  * total_new_tokens; prior_len: device int32 [n_chunks]; block_table: device int32
  * [n_chunks, max_blocks], row i covering the p_i + c_i tokens of chunk i's request.  Row r of
- * chunk i sees logical keys 0 .. p_i + r.  A chunk with c == 0 is skipped.  bf16 and FP8 pools with
+ * chunk i sees logical keys 0 .. p_i + r.  A chunk with c == 0 is skipped, and so is -- checked on the
+ * device, no error is returned -- a chunk whose lengths do not fit together: rows outside
+ * [0, total_new_tokens), c_i < 0, p_i < 0, or p_i + c_i beyond the max_blocks * block_size tokens its
+ * table row can hold; its rows of out stay untouched and nothing is read on its behalf.
+ * bf16 and FP8 pools with
  * head_dim 128 run on the matrix cores (q, out of FP8 pools: bf16); fp32 and head_dim 64 pools are
  * served row by row by the vector-ALU decode kernel (correct to the same bar, not tuned). */
 KUN_API int kun_paged_prefill_chunk(kun_kv_pool* pool, const void* q, void* out, const int32_t* q_start,

@@ -343,7 +343,8 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
     const PlanHeader hdr = load_plan_header(a);        // both loads go out together: the list is as long as the grid
     const int n_items = hdr.n_items;
     const int4 it4 = a.items[item];                    // the length rides along: one dependent load less
-    if (hdr.tag != a.plan_tag || it4.z > a.max_blocks * a.B) return;   // no plan of this batch, or not of this table
+    if (hdr.tag != a.plan_tag || it4.z > (long long)a.max_blocks * a.B) return;   // no plan of this batch, or not of this table
+    if (it4.z <= 0) return;                            // (a row list may hold rows without a context)
     if (item >= n_items || it4.w >= a.max_items) return;   // (a record slot beyond the workspace: the caller's bound was too small)
     const int seq = it4.x, part = it4.y;
     const int L = it4.z;
@@ -510,7 +511,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const PlanHeader hdr = load_plan_header(a);        // both loads go out together
     const int n_items = hdr.n_items;
     const int4 it4 = a.items[item < a.max_items ? item : a.max_items - 1];   // the length rides along: one dependent load less
-    if (hdr.tag != a.plan_tag || it4.z > a.max_blocks * a.B) return;   // no plan of this batch, or not of this table
+    if (hdr.tag != a.plan_tag || it4.z > (long long)a.max_blocks * a.B) return;   // no plan of this batch, or not of this table
     if (item >= n_items || it4.w >= a.max_items) return;   // (a record slot beyond the workspace: the caller's bound was too small)
     const int seq = it4.x, part = it4.y;
     const int G = a.G;
@@ -753,7 +754,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const PlanHeader hdr = load_plan_header(a);
     const int n_items = hdr.n_items;
     const int4 it4 = a.items[item < a.max_items ? item : a.max_items - 1];
-    if (hdr.tag != a.plan_tag || it4.z > a.max_blocks * a.B) return;   // no plan of this batch, or not of this table
+    if (hdr.tag != a.plan_tag || it4.z > (long long)a.max_blocks * a.B) return;   // no plan of this batch, or not of this table
     if (item >= n_items || it4.w >= a.max_items) return;
     const int seq = it4.x, part = it4.y;
     const int G = a.G;
@@ -965,6 +966,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a) {
     const int seq = blockIdx.x / kMergeSlices / a.Hkv, kvh = blockIdx.x / kMergeSlices % a.Hkv;
     if (load_plan_header(a).tag != a.plan_tag) return;
     const int L = a.ctx_len[seq];
+    if (L > (long long)a.max_blocks * a.B) return;      // left out by the partial kernel: no records to merge
     const int nparts = (L + a.part_tokens - 1) / a.part_tokens;
     if (nparts <= 1) return;
     const int first = a.seq_first[seq];

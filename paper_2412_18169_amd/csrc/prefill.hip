@@ -135,17 +135,28 @@ __device__ __host__ constexpr int kun_tile_place(int s) { return s == 1 ? 2 : s 
 __device__ __host__ inline int page_row_entries(int max_blocks, int sub_shift) {
     return (((max_blocks << sub_shift) + kBlocksPerTile - 1) / kBlocksPerTile + 1) * kBlocksPerTile;
 }
+// New tokens of chunk ch, or 0 if its lengths do not fit together: rows outside [0, total_new), a negative
+// prior length, or a context that the chunk's block-table row cannot hold.  Such a chunk is left out
+// like an empty one (no kernel then reads a table entry, a query row or a page on its behalf).
+__device__ __forceinline__ int chunk_tokens(const int32_t* __restrict__ q_start, const int32_t* __restrict__ prior,
+                                            int ch, int total_new, long long row_tokens) {
+    const int qs = q_start[ch], qe = q_start[ch + 1], p = prior[ch];
+    const bool ok = qs >= 0 && qe > qs && qe <= total_new && p >= 0 && (long long)p + (qe - qs) <= row_tokens;
+    return ok ? qe - qs : 0;
+}
+
 __device__ void resolve_tiles(const KunRanges& rt, const int32_t* __restrict__ q_start,
                               const int32_t* __restrict__ prior, const int32_t* __restrict__ table, int n_chunks,
                               int max_blocks, int sub_shift, unsigned block_bytes, unsigned tile_bytes,
-                              unsigned long long* __restrict__ page_addr, int first_wg, int n_wgs) {
+                              unsigned long long* __restrict__ page_addr, int first_wg, int n_wgs, int total_new) {
     const int tiles_per_row = page_row_entries(max_blocks, sub_shift);
     const long long total = (long long)n_chunks * tiles_per_row;
     for (long long e = (long long)(blockIdx.x - first_wg) * blockDim.x + threadIdx.x; e < total;
          e += (long long)n_wgs * blockDim.x) {
         const int ch = (int)(e / tiles_per_row), place = (int)(e % tiles_per_row);
-        const int ctx = prior[ch] + q_start[ch + 1] - q_start[ch];
-        if (q_start[ch + 1] == q_start[ch] || ctx <= 0) continue;
+        const int c = chunk_tokens(q_start, prior, ch, total_new, ((long long)max_blocks * kBlock) << sub_shift);
+        if (c == 0) continue;
+        const int ctx = prior[ch] + c;
         const int last = (ctx - 1) / kBlock;
         int t = (place & ~(kBlocksPerTile - 1)) + kun_tile_place(place & (kBlocksPerTile - 1));
         t = t < last ? t : last;
@@ -160,6 +171,7 @@ struct ResolveArgs {
     const int32_t* table;
     unsigned long long* page_addr;
     int max_blocks, sub_shift, n_wgs;
+    int total_new;                        // query rows of the call: chunks must lie inside
     unsigned block_bytes, tile_bytes;     // tile_bytes: K and V^T of one 16-token page tile (8192 in bf16, 4096 in FP8)
 };
 
@@ -177,7 +189,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const Resolv
     if (blockIdx.x == 0 && threadIdx.x == 0) n_items[1] = tag;
     if (blockIdx.x > 0) {      // workgroups 1 .. n_wgs resolve the blocks; workgroup 0 makes the work list
         resolve_tiles(ra.rt, q_start, prior, ra.table, n_chunks, ra.max_blocks, ra.sub_shift, ra.block_bytes,
-                      ra.tile_bytes, ra.page_addr, 1, ra.n_wgs);
+                      ra.tile_bytes, ra.page_addr, 1, ra.n_wgs, ra.total_new);
         return;
     }
     // everything a workgroup needs to know about list entry i, so that it starts with one lookup
@@ -202,7 +214,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const Resolv
         const int ch = c0 + tid;
         int nt = 0, c = 0, p = 0;
         if (ch < n_chunks) {
-            c = q_start[ch + 1] - q_start[ch];
+            c = chunk_tokens(q_start, prior, ch, ra.total_new, ((long long)ra.max_blocks * kBlock) << ra.sub_shift);
             p = prior[ch];
             nt = (c + pos_per_tile - 1) / pos_per_tile;
         }
@@ -1195,16 +1207,27 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Shapes the MFMA kernels do not cover (fp32, head_dim 64): row r of chunk i is the decode of a
 // request of p_i + r + 1 tokens behind table row i.
+// Every query row looks its chunk up (q_start ascends; a row that no consistent chunk covers gets
+// length 0 and is skipped like an empty request), so each entry is written exactly once.
 __global__ __launch_bounds__(256) void prefill_rows_kernel(const int32_t* __restrict__ q_start,
                                                            const int32_t* __restrict__ prior, int n_chunks,
+                                                           int total_new, long long row_tokens,
                                                            int32_t* __restrict__ ctx_len,
                                                            int32_t* __restrict__ row_of_seq) {
-    for (int i = blockIdx.x; i < n_chunks; i += gridDim.x) {
-        const int qs = q_start[i], c = q_start[i + 1] - qs, p = prior[i];
-        for (int r = threadIdx.x; r < c; r += blockDim.x) {
-            ctx_len[qs + r] = p + r + 1;
-            row_of_seq[qs + r] = i;
+    for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < total_new; t += gridDim.x * blockDim.x) {
+        int lo = 0, hi = n_chunks;                         // last chunk that starts at or before row t
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (q_start[mid] <= t) lo = mid; else hi = mid;
         }
+        int len = 0;
+        if (n_chunks > 0) {
+            const int c = chunk_tokens(q_start, prior, lo, total_new, row_tokens);
+            const int r = t - q_start[lo];
+            if (c > 0 && r >= 0 && r < c) len = prior[lo] + r + 1;
+        }
+        ctx_len[t] = len;
+        row_of_seq[t] = lo;
     }
 }
 
@@ -1318,8 +1341,10 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
         int32_t* ctx_len = (int32_t*)((char*)workspace + 256);
         int32_t* row_of_seq = (int32_t*)((char*)workspace + 256 + col);
         hipStream_t st = (hipStream_t)stream;
-        hipLaunchKernelGGL(prefill_rows_kernel, dim3((unsigned)(n_chunks < 4096 ? n_chunks : 4096)), dim3(256), 0, st,
-                           q_start, prior_len, n_chunks, ctx_len, row_of_seq);
+        const int row_wgs = (total_new_tokens + 255) / 256;
+        hipLaunchKernelGGL(prefill_rows_kernel, dim3((unsigned)(row_wgs < 4096 ? row_wgs : 4096)), dim3(256), 0, st,
+                           q_start, prior_len, n_chunks, total_new_tokens, (long long)max_blocks * p->B, ctx_len,
+                           row_of_seq);
         KUN_HIP_CHECK_LAUNCH();
         return kun_attend_rows_generic(p, q, out, block_table, max_blocks, ctx_len, row_of_seq, total_new_tokens, Hq,
                                        scale, (char*)workspace + 256 + 2 * col, st);
@@ -1368,6 +1393,7 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     ra.table = block_table;
     ra.page_addr = (unsigned long long*)(ws + lay.off_pages);
     ra.max_blocks = max_blocks;
+    ra.total_new = total_new_tokens;
     ra.sub_shift = a.sub_shift;
     ra.block_bytes = a.block_bytes;
     ra.tile_bytes = (unsigned)(2 * kBlock * D * p->elt);

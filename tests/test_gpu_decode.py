@@ -295,6 +295,42 @@ def test_length_one_returns_v_exactly_and_zero_length_is_skipped():
         dw.close()
 
 
+@pytest.mark.parametrize("dtype,d,merge", [("bf16", 128, "fold"), ("bf16", 128, "kernel"), ("fp8", 128, "fold"),
+                                           ("f32", 64, "kernel")])
+def test_a_context_longer_than_the_table_row_is_left_out(dtype, d, merge):
+    """ctx_len above max_blocks * block_size cannot be served from the table row: the request is skipped
+    (row untouched), the others come out bit for bit as before."""
+    kun.kun_set_option("KUN_DECODE_MERGE", merge)
+    kun.kun_set_option("KUN_DECODE_PART", "256")
+    try:
+        sh = synth.LayerShape(Hq=8, Hkv=2, d=d, B=16, dtype=dtype)
+        lens = [700, 33, 1300, 5, 260]
+        # (spare blocks: the bound on sum(ctx_len) is capped by the pool's capacity, and the corrupted sum must fit)
+        w = synth.custom_workload("toolong", sh, lens, extra_blocks=100, range_fracs=(0.6, 0.4))
+        dw = DeviceWorkload(w)
+        row_tokens = dw.dec_table.shape[1] * sh.B
+        bound = sum(lens) + row_tokens + 1
+        ref = dw.decode(ctx_bound=bound).clone()
+        torch.cuda.synchronize()
+        for bad in (2, 3):
+            print(f"[gpu-case] {dtype} merge={merge}: request {bad} longer than its table row", flush=True)
+            keep = dw.dec_len.clone()
+            dw.dec_len[bad] = row_tokens + 1
+            dw.out_dec.fill_(5.0)
+            got = dw.decode(ctx_bound=bound)
+            torch.cuda.synchronize()
+            for s_ in range(len(lens)):
+                if s_ == bad:
+                    assert (got[s_] == 5.0).all()
+                else:
+                    assert torch.equal(got[s_].view(torch.uint8), ref[s_].view(torch.uint8)), s_
+            dw.dec_len.copy_(keep)
+        dw.close()
+    finally:
+        kun.kun_set_option("KUN_DECODE_MERGE", None)
+        kun.kun_set_option("KUN_DECODE_PART", None)
+
+
 def test_block_permutation_gives_bit_identical_output():
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     lens = [3, 100, 700, 1300]

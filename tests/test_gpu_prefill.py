@@ -363,6 +363,45 @@ def test_empty_chunk_is_skipped_and_first_row_returns_v():
     dw.close()
 
 
+@pytest.mark.parametrize("dtype,d,G", [("bf16", 128, 4), ("fp8", 128, 2), ("f32", 64, 2)])
+def test_chunks_whose_lengths_do_not_fit_together_are_left_out(dtype, d, G):
+    """A prior length below zero or beyond what the table row holds, or rows beyond the call's: the kernels
+    skip that chunk (no table entry, query row or page is read for it), its output rows stay as they were
+    and every other chunk comes out bit for bit as before."""
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=16, dtype=dtype)
+    chunks = [(0, 40), (100, 70), (33, 20), (250, 64)]
+    w = synth.custom_workload("misfit", sh, [3], chunks=chunks, extra_blocks=3, range_fracs=(0.5, 0.5))
+    dw = DeviceWorkload(w)
+    ref = dw.prefill().clone()
+    torch.cuda.synchronize()
+    row_tokens = dw.pre_table.shape[1] * sh.B
+    q_start0, prior0 = dw.q_start.clone(), dw.prior.clone()
+    starts = [int(x) for x in dw.q_start_host]
+    misfits = [("prior beyond the table row", 1, lambda: dw.prior.__setitem__(1, row_tokens - 70 + 1)),
+               ("negative prior", 2, lambda: dw.prior.__setitem__(2, -5)),
+               ("rows beyond the call", 3, lambda: dw.q_start.__setitem__(4, dw.total_new + 9))]
+    for what, bad, corrupt in misfits:
+        print(f"[gpu-case] {dtype} {what}", flush=True)
+        corrupt()
+        dw.out_pre.fill_(9.0)
+        for steps in (("both",) if d == 64 else ("both", "plan+planned")):
+            if steps == "both":
+                got = dw.prefill()
+            else:
+                dw.prefill(steps="plan")
+                got = dw.prefill(steps="planned")
+            torch.cuda.synchronize()
+            for i in range(len(chunks)):
+                rows = slice(starts[i], starts[i + 1])
+                if i == bad:
+                    assert (got[rows] == 9.0).all(), (what, i)
+                else:
+                    assert torch.equal(got[rows].view(torch.int16), ref[rows].view(torch.int16)), (what, i)
+        dw.q_start.copy_(q_start0)
+        dw.prior.copy_(prior0)
+    dw.close()
+
+
 def test_chunk_rows_equal_unchunked_prefill_on_gpu():
     # a later chunk also attends to the earlier ones: rows of chunk (p, c) == rows p..p+c-1 of (0, p+c)
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")

@@ -153,7 +153,8 @@ KUN_API int kun_validate_block_table(const kun_kv_pool* pool, const int32_t* hos
  *   k_off_out[i]  byte offset inside that range of K[position][0]          (device int64 [T])
  *   v_off_out[i]  byte offset inside that range of V[position][0]; element j of the V row sits
  *                 j * 16 elements further on (the tile's row stride)       (device int64 [T])
- * Integer outputs, exact.  T == 0 is a no-op. */
+ * Integer outputs, exact; all three are -1 for a pair the table cannot place (see kun_kv_append).
+ * T == 0 is a no-op. */
 KUN_API int kun_slot_map(const kun_kv_pool* pool, const int32_t* seq_of_tok, const int32_t* pos_of_tok,
                  int T, const int32_t* block_table, int max_blocks, int kv_head,
                  int32_t* range_out, int64_t* k_off_out, int64_t* v_off_out, void* stream);
@@ -163,7 +164,11 @@ KUN_API int kun_slot_map(const kun_kv_pool* pool, const int32_t* seq_of_tok, con
 /* k_new, v_new: device [T, num_kv_heads, head_dim] in the pool's dtype (FP8 pools: one byte per element).  Token i belongs to row
  * seq_of_tok[i] of block_table (device int32 [rows, max_blocks]) at logical position
  * pos_of_tok[i] (device int32 [T]); it lands in block block_table[seq][pos / block_size], slot
- * pos % block_size.  T == 0 is a no-op. */
+ * pos % block_size.  T == 0 is a no-op.  Checked on the device, without an error code: a token whose
+ * row or position is below zero, whose position is beyond the max_blocks * block_size tokens of a table
+ * row, or whose table entry is not a block of the pool (e.g. -1) is left out -- nothing is written for
+ * it.  (The number of table rows is not known to the call: a row index beyond the table is the
+ * caller's to avoid.) */
 KUN_API int kun_kv_append(kun_kv_pool* pool, const void* k_new, const void* v_new,
                   const int32_t* seq_of_tok, const int32_t* pos_of_tok, int T,
                   const int32_t* block_table, int max_blocks, void* stream);

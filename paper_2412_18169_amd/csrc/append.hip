@@ -41,16 +41,23 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const KunRanges rt, cons
         int slot = 0, starts = 0;
         if (i < T) {
             const int seq = seq_of_tok[i], pos = pos_of_tok[i];
-            const int blk = table[(size_t)seq * max_blocks + pos / B];
-            tile = kun_block_addr(rt, blk, block_bytes) + (size_t)h * page_bytes +
-                   (size_t)((pos % B) / kTile) * (2 * kTile * D) * sizeof(E);
-            slot = pos % kTile;
-            // a run starts here unless the token before continues into this slot of this tile
-            starts = i == 0 || slot == 0 || seq_of_tok[i - 1] != seq || pos_of_tok[i - 1] != pos - 1;
+            // A token that its table row cannot place -- row or position below zero, position beyond the
+            // row's max_blocks * B tokens, a block id outside the pool -- is left out: nothing is written
+            // for it.  (The tokens of one run share their table entry, so a run is placed or left out as
+            // a whole.)
+            const int blk = (seq >= 0 && pos >= 0 && pos < (long long)max_blocks * B)
+                                ? table[(size_t)seq * max_blocks + pos / B] : -1;
+            if (blk >= 0 && blk < rt.first[rt.n]) {
+                tile = kun_block_addr(rt, blk, block_bytes) + (size_t)h * page_bytes +
+                       (size_t)((pos % B) / kTile) * (2 * kTile * D) * sizeof(E);
+                slot = pos % kTile;
+                // a run starts here unless the token before continues into this slot of this tile
+                starts = i == 0 || slot == 0 || seq_of_tok[i - 1] != seq || pos_of_tok[i - 1] != pos - 1;
+            }
         }
         s_tile[tid] = tile;
         s_slot[tid] = slot;
-        s_head[tid] = (i < T && starts) ? tid : -1;
+        s_head[tid] = (tile && starts) ? tid : -1;
     }
     if (tid < kGroup) s_len[tid] = 0;
     __syncthreads();
@@ -58,7 +65,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const KunRanges rt, cons
         // runs whose head lies in [0, kGroup): tokens before the first head belong to the workgroup before
         int head = -1;
         for (int t = 0; t < kWindow; ++t) {
-            if (base + t >= T) { s_head[t] = -1; continue; }
+            if (base + t >= T || !s_tile[t]) { s_head[t] = -1; head = -1; continue; }
             if (s_head[t] == t) head = t < kGroup ? t : -1;
             s_head[t] = head;
             if (head >= 0) ++s_len[head];
@@ -102,7 +109,14 @@ __global__ __launch_bounds__(256) void slot_map_kernel(const KunRanges rt, const
                                                        int64_t* __restrict__ k_off, int64_t* __restrict__ v_off) {
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < T; i += gridDim.x * blockDim.x) {
         const int seq = seq_of_tok[i], pos = pos_of_tok[i];
-        const int blk = table[(size_t)seq * max_blocks + pos / B];
+        const int blk = (seq >= 0 && pos >= 0 && pos < (long long)max_blocks * B)
+                            ? table[(size_t)seq * max_blocks + pos / B] : -1;
+        if (blk < 0 || blk >= rt.first[rt.n]) {            // a token the table row cannot place
+            range_out[i] = -1;
+            k_off[i] = -1;
+            v_off[i] = -1;
+            continue;
+        }
         const int tile = (pos % B) / kTile, slot = pos % kTile;
         const char* page = kun_block_addr(rt, blk, block_bytes) + (size_t)h * page_bytes +
                            (size_t)tile * (2 * kTile * D) * elt;

@@ -454,6 +454,55 @@ def test_kv_append_is_bit_exact(dtype, d):
     dw.close()
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_kv_append_leaves_out_tokens_that_the_table_cannot_place(dtype, d):
+    """Rows or positions below zero, positions beyond the table row, table entries that are no block of
+    the pool: nothing is written for such tokens, every other token lands bit-exactly (the oracle appends
+    the placeable tokens only), and the slot map reports -1 for the others."""
+    sh = synth.LayerShape(Hq=4, Hkv=4, d=d, B=16, dtype=dtype)
+    w = synth.custom_workload("app-bad", sh, [37, 1, 16, 250], chunks=[(20, 70)], extra_blocks=5, range_fracs=(0.5, 0.5))
+    dw = DeviceWorkload(w, fill=False)
+    lens = w.seq_lens
+    seqs, poss, ks, vs = [], [], [], []
+    for s in range(len(lens)):
+        k, v = synth.kv_logical(w, s, 0, int(lens[s]))
+        ks.append(k); vs.append(v)
+        seqs += [s] * int(lens[s]); poss += list(range(int(lens[s])))
+    k_new = torch.cat(ks); v_new = torch.cat(vs)
+    seqs = np.asarray(seqs, dtype=np.int32); poss = np.asarray(poss, dtype=np.int32)
+    table = w.table_array(range(len(lens))).copy()
+    row_tokens = table.shape[1] * sh.B
+    rng = np.random.default_rng(4)
+    bad = rng.choice(len(seqs), size=24, replace=False)
+    poss[bad[:8]] = -1 - rng.integers(0, 50, size=8)              # positions below zero
+    poss[bad[8:16]] = row_tokens + rng.integers(0, 50, size=8)    # positions beyond the table row
+    seqs[bad[16:24]] = -1 - rng.integers(0, 3, size=8)            # rows below zero
+    table[3, 2] = -1                                              # tokens 32..47 of request 3: no block
+    table[3, 7] = w.num_blocks                                    # tokens 112..127: one past the last block
+    table[4, 1] = -7                                              # the chunk's request, tokens 16..31
+    placeable = np.array([seqs[i] >= 0 and 0 <= poss[i] < row_tokens and 0 <= table[seqs[i], poss[i] // sh.B] < w.num_blocks
+                          for i in range(len(seqs))])
+    assert 50 < (~placeable).sum() < len(seqs) // 2
+    opool = O.OraclePool([synth.to_host_bits(r).reshape(-1).copy() for r in dw.ranges], sh.Hkv, sh.d, sh.B, sh.dtype)
+    O.kv_append(opool, synth.to_host_bits(k_new)[placeable], synth.to_host_bits(v_new)[placeable], seqs[placeable],
+                poss[placeable], table)
+    dseq, dpos, dtab = torch.from_numpy(seqs).cuda(), torch.from_numpy(poss).cuda(), torch.from_numpy(table).cuda()
+    print(f"[gpu-case] append with {int((~placeable).sum())} unplaceable tokens of {len(seqs)}, {dtype}", flush=True)
+    kun.kun_kv_append(dw.pool, k_new.cuda(), v_new.cuda(), dseq, dpos, len(seqs), dtab, table.shape[1])
+    torch.cuda.synchronize()
+    for r in range(len(dw.ranges)):
+        assert np.array_equal(synth.to_host_bits(dw.ranges[r]).reshape(-1), opool.ranges[r], equal_nan=True)
+    rng_out = torch.empty(len(seqs), dtype=torch.int32, device="cuda")
+    k_off = torch.empty(len(seqs), dtype=torch.int64, device="cuda")
+    v_off = torch.empty(len(seqs), dtype=torch.int64, device="cuda")
+    kun.kun_slot_map(dw.pool, dseq, dpos, len(seqs), dtab, table.shape[1], 1, rng_out, k_off, v_off)
+    torch.cuda.synchronize()
+    gone = torch.from_numpy(~placeable).cuda()
+    assert (rng_out[gone] == -1).all() and (k_off[gone] == -1).all() and (v_off[gone] == -1).all()
+    assert (rng_out[~gone] >= 0).all() and (k_off[~gone] >= 0).all() and (v_off[~gone] > 0).all()
+    dw.close()
+
+
 def test_generator_is_identical_on_device_and_host():
     a = synth.normal_values(1003, synth.TENSOR_K, 17, 12345, 100000, torch.bfloat16, "cuda")
     b = synth.normal_values(1003, synth.TENSOR_K, 17, 12345, 100000, torch.bfloat16, "cpu")

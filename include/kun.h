@@ -22,7 +22,10 @@
  *   - Physical block ids are int32, cumulative over the ranges in the order the ranges were
  *     added, and never renumbered.  Block-table entries at or beyond ceil(L / block_size) of a
  *     request are ignored and may hold anything (e.g. -1).  Ids the kernels do read must be
- *     valid: check tables with kun_validate_block_table when in doubt.
+ *     valid: check tables with kun_validate_block_table when in doubt.  (An id outside the pool is
+ *     not followed: the attention kernels clamp it into [0, num_blocks), so the request it belongs
+ *     to reads some other block of the pool and its output means nothing, but no address outside
+ *     the pool's ranges is touched; kun_kv_append leaves such a token out.)
  *
  * Page layout (part of the ABI).  One block is num_kv_heads pages; page (block, kv head) is
  *   block_size / 16 tiles in token order, and the tile of tokens 16 i .. 16 i + 15 is

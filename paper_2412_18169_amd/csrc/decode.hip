@@ -47,6 +47,8 @@ struct DecodeArgs {
     float* part_acc;         // workspace: [item, kvh, G, d]
     int max_blocks;
     int S, Hkv, G;
+    int last_block;          // largest block id of the pool: table entries are clamped into [0, last_block] before they
+                             // become addresses, so that a bad entry reads some block of the pool, never anything else
     int B;                   // tokens per KV block: 16, 32, 64 or 128
     int tile_shift;          // log2(B / 16)
     int part_tokens;         // tokens per partition, multiple of 32
@@ -380,7 +382,7 @@ __global__ __launch_bounds__(256) void decode_partial_generic(const DecodeArgs a
     // b counts tiles of 16 tokens: tile b % (B / 16) of block b / (B / 16); a tile is K [16][D], then V^T [D][16]
     const int tiles_per_block = a.B / kBlock;
     for (int b = t0 / kBlock + wave; b * kBlock < t1; b += NW) {
-        const int blk = __builtin_amdgcn_readfirstlane(trow[b / tiles_per_block]);
+        const int blk = min(max(__builtin_amdgcn_readfirstlane(trow[b / tiles_per_block]), 0), a.last_block);
         const char* page = kun_block_addr(a.rt, blk, a.block_bytes) + (size_t)kvh * a.page_bytes +
                            (size_t)(b % tiles_per_block) * (2 * kBlock * D * sizeof(T));
         const int tb = b * kBlock;
@@ -557,7 +559,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const int pr_l = first_pair + (lane >> 1) * NW;
         int b = 2 * pr_l + (lane & 1);
         if (b >= nblk) b = (2 * pr_l < nblk) ? 2 * pr_l : nblk - 1;   // odd tail / beyond the partition
-        const int id = trow[b >> a.tile_shift];
+        const int id = min(max(trow[b >> a.tile_shift], 0), a.last_block);
         int first = a.rt.first[0];
         unsigned long long base = (unsigned long long)a.rt.base[0];
         for (int r = 1; r < a.rt.n; ++r) {
@@ -795,7 +797,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     auto load_pages = [&](int first_quad) -> unsigned long long {
         int t = tile0 + 4 * (first_quad + (lane >> 2) * NW) + (lane & 3);
         if (t >= ntile) t = ntile - 1;                 // beyond the partition: any valid tile
-        const int id = trow[t >> a.tile_shift];
+        const int id = min(max(trow[t >> a.tile_shift], 0), a.last_block);
         int first = a.rt.first[0];
         unsigned long long base = (unsigned long long)a.rt.base[0];
         for (int r = 1; r < a.rt.n; ++r) {
@@ -1099,6 +1101,7 @@ int kun_attend_rows_generic(const kun_kv_pool* p, const void* q, void* out, cons
     a.Hkv = p->Hkv;
     a.G = Hq / p->Hkv;
     a.B = p->B;
+    a.last_block = p->ranges.first[p->ranges.n] - 1;
     a.tile_shift = p->B == 128 ? 3 : p->B == 64 ? 2 : p->B == 32 ? 1 : 0;
     a.part_tokens = 1 << 30;
     a.max_items = T;
@@ -1204,6 +1207,7 @@ int decode_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* bloc
     a.Hkv = p->Hkv;
     a.G = G;
     a.B = p->B;
+    a.last_block = p->ranges.first[p->ranges.n] - 1;
     a.tile_shift = p->B == 128 ? 3 : p->B == 64 ? 2 : p->B == 32 ? 1 : 0;
     a.part_tokens = P;
     a.max_items = lay.max_items;

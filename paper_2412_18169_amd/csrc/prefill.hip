@@ -148,7 +148,8 @@ __device__ __forceinline__ int chunk_tokens(const int32_t* __restrict__ q_start,
 __device__ void resolve_tiles(const KunRanges& rt, const int32_t* __restrict__ q_start,
                               const int32_t* __restrict__ prior, const int32_t* __restrict__ table, int n_chunks,
                               int max_blocks, int sub_shift, unsigned block_bytes, unsigned tile_bytes,
-                              unsigned long long* __restrict__ page_addr, int first_wg, int n_wgs, int total_new) {
+                              unsigned long long* __restrict__ page_addr, int first_wg, int n_wgs, int total_new,
+                              int last_block) {
     const int tiles_per_row = page_row_entries(max_blocks, sub_shift);
     const long long total = (long long)n_chunks * tiles_per_row;
     for (long long e = (long long)(blockIdx.x - first_wg) * blockDim.x + threadIdx.x; e < total;
@@ -160,7 +161,8 @@ __device__ void resolve_tiles(const KunRanges& rt, const int32_t* __restrict__ q
         const int last = (ctx - 1) / kBlock;
         int t = (place & ~(kBlocksPerTile - 1)) + kun_tile_place(place & (kBlocksPerTile - 1));
         t = t < last ? t : last;
-        const int id = table[(size_t)ch * max_blocks + (t >> sub_shift)];
+        // (clamped into the pool: a bad table entry reads some block of the pool, never anything else)
+        const int id = min(max(table[(size_t)ch * max_blocks + (t >> sub_shift)], 0), last_block);
         page_addr[e] = (unsigned long long)kun_block_addr(rt, id, block_bytes) +
                        (unsigned)(t & ((1 << sub_shift) - 1)) * tile_bytes;
     }
@@ -172,6 +174,7 @@ struct ResolveArgs {
     unsigned long long* page_addr;
     int max_blocks, sub_shift, n_wgs;
     int total_new;                        // query rows of the call: chunks must lie inside
+    int last_block;                       // largest block id of the pool
     unsigned block_bytes, tile_bytes;     // tile_bytes: K and V^T of one 16-token page tile (8192 in bf16, 4096 in FP8)
 };
 
@@ -189,7 +192,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const Resolv
     if (blockIdx.x == 0 && threadIdx.x == 0) n_items[1] = tag;
     if (blockIdx.x > 0) {      // workgroups 1 .. n_wgs resolve the blocks; workgroup 0 makes the work list
         resolve_tiles(ra.rt, q_start, prior, ra.table, n_chunks, ra.max_blocks, ra.sub_shift, ra.block_bytes,
-                      ra.tile_bytes, ra.page_addr, 1, ra.n_wgs, ra.total_new);
+                      ra.tile_bytes, ra.page_addr, 1, ra.n_wgs, ra.total_new, ra.last_block);
         return;
     }
     // everything a workgroup needs to know about list entry i, so that it starts with one lookup
@@ -1394,6 +1397,7 @@ int prefill_enqueue(kun_kv_pool* p, const void* q, void* out, const int32_t* q_s
     ra.page_addr = (unsigned long long*)(ws + lay.off_pages);
     ra.max_blocks = max_blocks;
     ra.total_new = total_new_tokens;
+    ra.last_block = p->ranges.first[p->ranges.n] - 1;
     ra.sub_shift = a.sub_shift;
     ra.block_bytes = a.block_bytes;
     ra.tile_bytes = (unsigned)(2 * kBlock * D * p->elt);

@@ -331,6 +331,30 @@ def test_a_context_longer_than_the_table_row_is_left_out(dtype, d, merge):
         kun.kun_set_option("KUN_DECODE_PART", None)
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp8", 128), ("f32", 64)])
+def test_table_entries_outside_the_pool_are_not_followed(dtype, d):
+    """Block ids below zero or beyond the pool inside a request's context: the kernels clamp them into the
+    pool (the request's output then means nothing) and every other request comes out bit for bit as before."""
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=d, B=16, dtype=dtype)
+    lens = [700, 33, 1300, 5, 260]
+    w = synth.custom_workload("badids", sh, lens, extra_blocks=4, range_fracs=(0.6, 0.4))
+    dw = DeviceWorkload(w)
+    ref = dw.decode().clone()
+    torch.cuda.synchronize()
+    bad = 2
+    dw.dec_table[bad, 3] = -1
+    dw.dec_table[bad, 40] = 1 << 30
+    dw.dec_table[bad, 41] = w.num_blocks
+    dw.dec_table[bad, 80] = -(1 << 31)
+    print(f"[gpu-case] {dtype}: block ids outside the pool in request {bad}", flush=True)
+    got = dw.decode()
+    torch.cuda.synchronize()
+    for s_ in range(len(lens)):
+        if s_ != bad:
+            assert torch.equal(got[s_].view(torch.uint8), ref[s_].view(torch.uint8)), s_
+    dw.close()
+
+
 def test_block_permutation_gives_bit_identical_output():
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
     lens = [3, 100, 700, 1300]

@@ -402,6 +402,31 @@ def test_chunks_whose_lengths_do_not_fit_together_are_left_out(dtype, d, G):
     dw.close()
 
 
+@pytest.mark.parametrize("dtype,d,G", [("bf16", 128, 4), ("fp8", 128, 2), ("f32", 64, 2)])
+def test_table_entries_outside_the_pool_are_not_followed(dtype, d, G):
+    """Block ids below zero or beyond the pool inside a chunk's context are clamped into the pool: that chunk's
+    output means nothing, every other chunk comes out bit for bit as before."""
+    sh = synth.LayerShape(Hq=2 * G, Hkv=2, d=d, B=16, dtype=dtype)
+    chunks = [(0, 40), (100, 70), (33, 20), (250, 64)]
+    w = synth.custom_workload("badids", sh, [3], chunks=chunks, extra_blocks=3, range_fracs=(0.5, 0.5))
+    dw = DeviceWorkload(w)
+    ref = dw.prefill().clone()
+    torch.cuda.synchronize()
+    starts = [int(x) for x in dw.q_start_host]
+    bad = 3
+    dw.pre_table[bad, 0] = -1
+    dw.pre_table[bad, 7] = 1 << 30
+    dw.pre_table[bad, 19] = w.num_blocks
+    print(f"[gpu-case] {dtype}: block ids outside the pool in chunk {bad}", flush=True)
+    got = dw.prefill()
+    torch.cuda.synchronize()
+    for i in range(len(chunks)):
+        if i != bad:
+            rows = slice(starts[i], starts[i + 1])
+            assert torch.equal(got[rows].view(torch.int16), ref[rows].view(torch.int16)), i
+    dw.close()
+
+
 def test_chunk_rows_equal_unchunked_prefill_on_gpu():
     # a later chunk also attends to the earlier ones: rows of chunk (p, c) == rows p..p+c-1 of (0, p+c)
     sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")

@@ -304,3 +304,25 @@ def test_step_captured_in_a_hip_graph_replays_bit_identically(form):
         assert torch.equal(dw.out_pre.view(torch.int16), ref_p.view(torch.int16)), rep
         assert torch.equal(dw.out_dec.view(torch.int16), ref_d.view(torch.int16)), rep
     dw.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+def test_very_long_contexts(dtype):
+    """One request of 300 000 tokens next to short ones (586 split-K partitions whose records the last
+    workgroup to arrive merges) and a prefill chunk behind 200 000 prior tokens (3 130 key tiles per work
+    item): every decode row and a sample of the chunk's rows against the oracle."""
+    from test_gpu_prefill import check_prefill
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype=dtype)
+    lens = [300_000, 17, 70_001, 1]
+    w = synth.custom_workload("long", sh, lens, chunks=[(200_000, 300), (0, 33)], extra_blocks=7,
+                              range_fracs=(0.3, 0.5, 0.2))
+    dw = DeviceWorkload(w)
+    out = dw.decode().clone()
+    torch.cuda.synchronize()
+    dw.check_guards()
+    err = decode_err(dw, out, list(range(len(lens))))
+    print("decode max err", err, flush=True)
+    assert err <= TOL
+    perr = check_prefill(dw, rows_per_chunk=6)
+    print("prefill max err", perr, flush=True)
+    dw.close()

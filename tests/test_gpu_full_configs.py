@@ -326,3 +326,33 @@ def test_very_long_contexts(dtype):
     perr = check_prefill(dw, rows_per_chunk=6)
     print("prefill max err", perr, flush=True)
     dw.close()
+
+
+def test_very_many_small_requests():
+    """50 000 decode requests of 0 to 40 tokens (the work list is built 1 024 requests at a time) and 5 000
+    prefill chunks of 0 to 12 tokens (more work items than the plan sorts by cost): a seeded sample of
+    requests and chunks against the oracle, and no row of a live request or chunk left unwritten."""
+    from test_gpu_prefill import check_prefill
+    rng = np.random.default_rng(77)
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=128, B=16, dtype="bf16")
+    lens = rng.integers(0, 41, size=50_000).tolist()
+    chunks = [(int(rng.integers(0, 101)), int(rng.integers(0, 13))) for _ in range(5_000)]
+    w = synth.custom_workload("many", sh, lens, chunks=chunks, extra_blocks=11, range_fracs=(0.5, 0.25, 0.25))
+    dw = DeviceWorkload(w)
+    dw.out_dec.fill_(float("nan"))
+    out = dw.decode().clone()
+    torch.cuda.synchronize()
+    dw.check_guards()
+    live = torch.from_numpy(np.asarray(lens) > 0).to(out.device)
+    assert torch.isfinite(out[live].float()).all() and torch.isnan(out[~live].float()).all()
+    rows = sorted(set(rng.choice(len(lens), size=96, replace=False).tolist()) | {0, len(lens) - 1, 1023, 1024, 1025})
+    rows = [r for r in rows if lens[r] > 0]
+    err = decode_err(dw, out, rows)
+    print("decode max err", err, flush=True)
+    assert err <= TOL
+    dw.out_pre.fill_(float("nan"))
+    only = sorted(set(rng.choice(len(chunks), size=64, replace=False).tolist()) | {0, len(chunks) - 1, 4095, 4096, 4097})
+    perr = check_prefill(dw, only=only)
+    print("prefill max err", perr, flush=True)
+    assert torch.isfinite(dw.out_pre.float()).all()      # rows exist for non-empty chunks only: all written
+    dw.close()

@@ -356,3 +356,31 @@ def test_very_many_small_requests():
     print("prefill max err", perr, flush=True)
     assert torch.isfinite(dw.out_pre.float()).all()      # rows exist for non-empty chunks only: all written
     dw.close()
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp8", 128), ("f32", 64)])
+def test_pool_of_the_maximum_number_of_ranges(dtype, d):
+    """A pool grown fifteen times (KUN_MAX_RANGES = 16 ranges of unequal size), every request's blocks drawn from
+    all of them: decode, prefill and append against the oracle; the seventeenth range is refused."""
+    from test_gpu_prefill import check_prefill
+    sh = synth.LayerShape(Hq=8, Hkv=2, d=d, B=16, dtype=dtype)
+    fr = np.arange(1, kun.KUN_MAX_RANGES + 1, dtype=np.float64)
+    lens = [900, 1, 2500, 77, 1300, 16]
+    chunks = [(700, 130), (0, 90)] if d == 128 else [(60, 20), (0, 9)]
+    w = synth.custom_workload("r16", sh, lens, chunks=chunks, extra_blocks=40, range_fracs=tuple((fr / fr.sum()).tolist()))
+    assert len(w.range_blocks) == kun.KUN_MAX_RANGES
+    dw = DeviceWorkload(w)
+    assert kun.kun_kv_pool_num_ranges(dw.pool) == kun.KUN_MAX_RANGES
+    used = np.concatenate(w.block_tables)
+    r, _ = synth.range_of_blocks(w.range_blocks, used.astype(np.int64))
+    assert len(np.unique(r)) == kun.KUN_MAX_RANGES           # the tables name blocks of every range
+    out = dw.decode().clone()
+    torch.cuda.synchronize()
+    err = decode_err(dw, out, list(range(len(lens))))
+    assert err <= (1e-5 if dtype == "f32" else TOL)
+    if dtype != "f32":
+        check_prefill(dw)
+    extra = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(kun.KunError):
+        kun.kun_kv_pool_extend(dw.pool, extra, extra.numel())
+    dw.close()

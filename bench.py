@@ -12,9 +12,11 @@ the prefill rate, the per-part times and the oracle timed on the host cores are 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {2,3,4,5}]
 
 Without --config the line describes configuration 5 (the largest one-GPU workload) and carries, under
-"others", the decode and prefill rates of configurations 3, 4 and 2 measured the same way.
+"others", the decode and prefill rates of configurations 3, 4 and 2 measured the same way, and of the
+default workload over FP8 (E4M3) pages and over blocks of 64 tokens.
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -253,24 +255,32 @@ def main():
     for d in dws:
         d.close()
     del dw, dws
+    gc.collect()
     torch.cuda.empty_cache()
 
     # The other configurations the targets are quoted on, same number of steps each: the metric, value,
     # roofline and config above stay those of the default workload.
     if not args.config and not args.no_others and not args.pmc_calibration:
         out["others"] = {}
-        for c in OTHER_CONFIGS:
-            r, d0, ds = time_steps(c, args, args.block_size, args.q_heads, args.kv_dtype)
+        runs = [(f"cfg{c}", c, args.block_size, args.kv_dtype) for c in OTHER_CONFIGS]
+        if not args.block_size and not args.kv_dtype and not args.q_heads:
+            # the default workload in the two variants of the page format: FP8 (E4M3) pages, blocks of 64 tokens
+            runs += [(f"cfg{DEFAULT_CONFIG}_fp8_pages", DEFAULT_CONFIG, 0, "fp8"),
+                     (f"cfg{DEFAULT_CONFIG}_block_size_64", DEFAULT_CONFIG, 64, "")]
+        for name, c, block_size, kv_dtype in runs:
+            r, d0, ds = time_steps(c, args, block_size, args.q_heads, kv_dtype)
             o = {"decode_ms": r["decode"]["ms"], "GB_per_s": r["decode"]["GB_per_s"],
                  "frac": r["decode"]["frac_of_hbm_peak"], "decode_kv_tokens": r["config"]["decode_kv_tokens"],
-                 "ms_per_step": r["ms_per_step"]}
+                 "kv_tokens_per_s": r["decode"]["kv_tokens_per_s"], "block_size": r["config"]["block_size"],
+                 "kv_dtype": r["config"]["kv_dtype"], "ms_per_step": r["ms_per_step"]}
             if "prefill" in r:
                 o.update({"prefill_ms": r["prefill"]["ms"], "TFLOP_per_s": r["prefill"]["TFLOP_per_s"],
                           "prefill_frac": r["prefill"]["frac_of_mfma_peak"]})
-            out["others"][f"cfg{c}"] = o
+            out["others"][name] = o
             for d in ds:
                 d.close()
             del d0, ds
+            gc.collect()
             torch.cuda.empty_cache()
     print(json.dumps(out), flush=True)
 

@@ -157,6 +157,11 @@ class DeviceWorkload:
             assert ok, f"a kernel wrote outside the {name} workspace of {nbytes} bytes"
 
     def close(self):
+        """Destroys the pool object and lets go of the device buffers (the ranges are the caller's memory: here
+        the caller is this object)."""
         if self.pool is not None:
             kun.kun_kv_pool_destroy(self.pool)
             self.pool = None
+        self.ranges = []
+        self._ws_dec = self._ws_pre = None
+        self._guards = {}

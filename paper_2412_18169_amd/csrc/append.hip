@@ -29,17 +29,35 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const KunRanges rt, cons
                                                         unsigned block_bytes, unsigned page_bytes) {
     constexpr int CH = D * sizeof(E) / 16;             // 16-byte chunks per row
     constexpr int VPR = kTile * sizeof(E) / 16;        // 16-byte stores per full V^T row
-    __shared__ char* s_tile[kWindow];                  // address of the token's page tile (this kv head)
+    constexpr int NP = (kWindow * CH + 255) / 256;     // 16-byte pieces of the window's rows per thread
+    __shared__ char* s_tile[kWindow];                  // address of the token's page tile (this kv head), or null
     __shared__ int s_slot[kWindow], s_head[kWindow];   // slot in the tile; input offset of the token's run head, or -1
     __shared__ int s_len[kGroup];                      // length of the run that starts at offset t (0: none starts there)
     __shared__ __attribute__((aligned(16))) E s_v[kWindow][D];
     const int h = blockIdx.x % Hkv, base = (blockIdx.x / Hkv) * kGroup;
     const int tid = threadIdx.x;
-    if (tid < kWindow) {
+
+    // The rows of the window are requested first: they depend on nothing, and the chain token -> table
+    // entry -> page address, which decides where (and whether) they go, runs under their latency.
+    uint4 kreg[NP], vreg[NP];
+#pragma unroll
+    for (int n = 0; n < NP; ++n) {
+        const int x = tid + 256 * n, t = x / CH, c = x % CH;
+        kreg[n] = vreg[n] = make_uint4(0, 0, 0, 0);
+        if (x < kWindow * CH && base + t < T) {
+            const size_t src = ((size_t)(base + t) * Hkv + h) * D * sizeof(E) + (size_t)c * 16;
+            kreg[n] = *(const uint4*)((const char*)k_new + src);
+            vreg[n] = *(const uint4*)((const char*)v_new + src);
+        }
+    }
+
+    // Wave 0, lane t = token base + t of the window: its tile and slot, and the runs of the window.
+    if (tid < 64) {
         const int i = base + tid;
         char* tile = nullptr;
-        int slot = 0, starts = 0;
-        if (i < T) {
+        int slot = 0;
+        bool starts = false;
+        if (tid < kWindow && i < T) {
             const int seq = seq_of_tok[i], pos = pos_of_tok[i];
             // A token that its table row cannot place -- row or position below zero, position beyond the
             // row's max_blocks * B tokens, a block id outside the pool -- is left out: nothing is written
@@ -55,30 +73,43 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const KunRanges rt, cons
                 starts = i == 0 || slot == 0 || seq_of_tok[i - 1] != seq || pos_of_tok[i - 1] != pos - 1;
             }
         }
-        s_tile[tid] = tile;
-        s_slot[tid] = slot;
-        s_head[tid] = (tile && starts) ? tid : -1;
-    }
-    if (tid < kGroup) s_len[tid] = 0;
-    __syncthreads();
-    if (tid == 0) {
-        // runs whose head lies in [0, kGroup): tokens before the first head belong to the workgroup before
-        int head = -1;
-        for (int t = 0; t < kWindow; ++t) {
-            if (base + t >= T || !s_tile[t]) { s_head[t] = -1; head = -1; continue; }
-            if (s_head[t] == t) head = t < kGroup ? t : -1;
-            s_head[t] = head;
-            if (head >= 0) ++s_len[head];
+        // A run ends in front of the next run head, the next token that is left out, or the window's end.
+        // Runs whose head lies in [0, kGroup) are this workgroup's; tokens in front of the first head
+        // belong to the workgroup before, tokens behind a head at kGroup or later to the next one.
+        const bool in_window = tid < kWindow && i < T;
+        const unsigned long long heads = __builtin_amdgcn_ballot_w64(starts);
+        const unsigned long long breaks = __builtin_amdgcn_ballot_w64(in_window && (starts || !tile));
+        const int window_end = min(kWindow, T - base);
+        if (tid < kWindow) {
+            int head = -1;
+            if (tile) {
+                const unsigned long long upto = breaks & ((2ull << tid) - 1);      // breaks at or before this token
+                if (upto) {
+                    const int hb = 63 - __builtin_clzll(upto);
+                    if (((heads >> hb) & 1) && hb < kGroup) head = hb;
+                }
+            }
+            s_tile[tid] = tile;
+            s_slot[tid] = slot;
+            s_head[tid] = head;
+        }
+        if (tid < kGroup) {
+            int len = 0;
+            if (starts) {
+                const unsigned long long after = breaks & ~((2ull << tid) - 1);
+                len = (after ? min(__builtin_ctzll(after), window_end) : window_end) - tid;
+            }
+            s_len[tid] = len;
         }
     }
     __syncthreads();
     // K rows and staging of V rows: 16-byte pieces
-    for (int x = tid; x < kWindow * CH; x += 256) {
-        const int t = x / CH, c = x % CH;
-        if (s_head[t] < 0) continue;
-        const size_t src = ((size_t)(base + t) * Hkv + h) * D * sizeof(E) + (size_t)c * 16;
-        *(uint4*)(s_tile[t] + (size_t)s_slot[t] * D * sizeof(E) + c * 16) = *(const uint4*)((const char*)k_new + src);
-        *(uint4*)((char*)&s_v[t][0] + c * 16) = *(const uint4*)((const char*)v_new + src);
+#pragma unroll
+    for (int n = 0; n < NP; ++n) {
+        const int x = tid + 256 * n, t = x / CH, c = x % CH;
+        if (x >= kWindow * CH || s_head[t] < 0) continue;
+        *(uint4*)(s_tile[t] + (size_t)s_slot[t] * D * sizeof(E) + c * 16) = kreg[n];
+        *(uint4*)((char*)&s_v[t][0] + c * 16) = vreg[n];
     }
     __syncthreads();
     // V^T: thread = (run head, dim)
